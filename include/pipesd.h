@@ -1,0 +1,179 @@
+/*
+ * pipesd.h — C ABI of the MI355X (gfx950) implementation of the cloud-side hot path of PipeSD:
+ * the target model's non-autoregressive verification (NAV) pass.
+ *
+ * What one pass computes (Sec. 2.2 "speculative round", Sec. 2.3, Sec. 4.2 "Target Model",
+ * Appendix B): the cloud holds the committed text of a client; the edge sends k draft tokens;
+ * the target model runs ONE causal forward over them on top of its cached prefix, accepts the
+ * drafts that pass the speculative-sampling test, replaces the first rejected one by a corrected
+ * token (or, if all k pass, contributes one extra token), and drops the rejected suffix so that
+ * drafting can restart from the last accepted token.
+ *
+ * Sequence state between passes: committed tokens t_0..t_{n-1} (n = "prefix length"); keys and
+ * values cached for t_0..t_{n-2}; t_{n-1} is PENDING (it is the previous pass's corrected/extra
+ * token, or the last prompt token, and has not been through the model).  A pass therefore runs
+ * m = k + 1 rows: [pending, d_1..d_k] at positions n-1 .. n-1+k.  Row i-1 yields the target
+ * distribution p_i that judges draft i; row k yields the extra-token distribution p_{k+1}.
+ *
+ * Conventions
+ *   - every function returns PIPESD_OK (0) or a negative pipesd_status; nothing throws or aborts;
+ *   - a call that fails changes no state of its handles;
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers are ordinary
+ *     host memory; `stream` is a hipStream_t passed as void* (NULL = the null stream);
+ *   - handles are owned by the library; buffers passed in are borrowed only for the duration
+ *     stated at each function;
+ *   - calls on one handle are not thread-safe and calls that share a model overlap on the GPU only
+ *     if issued on the same stream (they share the model's activation workspace).
+ */
+#ifndef PIPESD_H
+#define PIPESD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PIPESD_OK = 0,
+  PIPESD_EINVAL = -1, /* null pointer, size or id out of range, unsupported shape */
+  PIPESD_ENOMEM = -2, /* KV pool has too few free blocks, or a device allocation failed */
+  PIPESD_ESTATE = -3, /* prefix_len differs from the stored length, rollback above it, verify before prefill */
+  PIPESD_EHIP = -4    /* a HIP runtime call failed (including: no GPU present) */
+} pipesd_status;
+
+enum { PIPESD_F32 = 0, PIPESD_BF16 = 1 };
+
+/* rows one pass can carry (pending + drafts), hence k <= PIPESD_MAX_ROWS - 1 */
+enum { PIPESD_MAX_ROWS = 32 };
+
+/* Decoder-only transformer (Sec. 2.1) in the Llama form: RMSNorm before attention and before the
+ * feed-forward block, rotary positions on element pairs (i, i + head_dim/2) with angle
+ * pos * rope_base^(-2i/head_dim), grouped-query attention (query head g reads KV head
+ * g / (n_q_heads / n_kv_heads)), SwiGLU feed-forward, no biases, untied LM head.
+ * dtype selects the storage type of all matrices and of the KV cache; norm gains are fp32. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype; /* PIPESD_F32 or PIPESD_BF16 */
+} pipesd_config;
+
+/* Device pointers to the caller's weights, every matrix [out][in] row-major in `dtype`.
+ * Arrays of per-layer pointers are host arrays of n_layers device pointers. */
+typedef struct {
+  const void *tok_emb;         /* [vocab][d_model] */
+  const void *final_norm;      /* [d_model] fp32 */
+  const void *lm_head;         /* [vocab][d_model] */
+  const void *const *attn_norm; /* [d_model] fp32 each */
+  const void *const *ffn_norm;  /* [d_model] fp32 each */
+  const void *const *wq;        /* [n_q_heads*head_dim][d_model] */
+  const void *const *wk;        /* [n_kv_heads*head_dim][d_model] */
+  const void *const *wv;        /* [n_kv_heads*head_dim][d_model] */
+  const void *const *wo;        /* [d_model][n_q_heads*head_dim] */
+  const void *const *w_gate;    /* [d_ffn][d_model] */
+  const void *const *w_up;      /* [d_ffn][d_model] */
+  const void *const *w_down;    /* [d_model][d_ffn] */
+} pipesd_weights;
+
+typedef struct pipesd_model pipesd_model;
+typedef struct pipesd_kv pipesd_kv;
+
+/* Target model handle (Sec. 4.2: the cloud keeps one target model for all clients, Appendix I).
+ * The weights are re-tiled into library-owned device memory in the order the matrix cores read
+ * them, synchronously: when the call returns the caller may free its own copies.
+ * weights == NULL creates a shape-only handle without device memory (for planning KV pools and
+ * exercising the bookkeeping without a GPU); compute calls on it return PIPESD_ESTATE.
+ * EINVAL: null cfg/out, non-positive sizes, n_q_heads not a multiple of n_kv_heads, odd head_dim,
+ * head_dim > 256, or (bf16) d_model, n_q_heads*head_dim or d_ffn not a multiple of 512 or
+ * head_dim not a multiple of 16. */
+int pipesd_model_create(const pipesd_config *cfg, const pipesd_weights *weights, pipesd_model **out);
+int pipesd_model_destroy(pipesd_model *model);
+
+/* Bytes of one KV block: block_tokens tokens x all layers x (K and V) x n_kv_heads x head_dim. */
+size_t pipesd_kv_block_bytes(const pipesd_model *model, int32_t block_tokens);
+
+/* Paged KV cache for up to max_seqs clients over a caller-allocated device pool (borrowed until
+ * pipesd_kv_destroy).  The pool holds floor(pool_bytes / block_bytes) blocks of block_tokens
+ * (16) tokens; per layer the keys of a block are [kv_head][token][head_dim] and the values
+ * [kv_head][head_dim][token].  pool == NULL gives bookkeeping only (see pipesd_model_create).
+ * EINVAL: block_tokens != 16, max_seqs < 1, pool too small for one block, pool not 256-byte aligned. */
+int pipesd_kv_create(const pipesd_model *model, int32_t max_seqs, int32_t block_tokens, void *pool,
+                     size_t pool_bytes, pipesd_kv **out);
+int pipesd_kv_destroy(pipesd_kv *kv);
+
+/* Forget client `seq`: length 0, all its blocks back to the pool. */
+int pipesd_seq_reset(pipesd_kv *kv, int32_t seq);
+
+/* Commit n more tokens (host array) to client `seq`: afterwards keys/values are cached for all
+ * committed tokens but the last, which is pending.  Runs the same forward as a verify pass in row
+ * chunks, without the LM head.  Returns after the work is enqueued on `stream`.
+ * ENOMEM if the pool cannot hold the new rows. */
+int pipesd_prefill(pipesd_model *model, pipesd_kv *kv, int32_t seq, const int32_t *tokens, int32_t n,
+                   void *stream);
+
+/* One NAV pass for one client (Sec. 2.2; Appendix B).
+ *   prefix_len    committed length the caller believes the client has (ESTATE if it differs);
+ *   draft_tokens  host [k], 1 <= k <= PIPESD_MAX_ROWS - 1;
+ *   draft_probs   device fp32 [k][vocab]: the draft model's full distribution q_i at each draft
+ *                 position; NULL selects token matching (accept d_i iff it is the target's argmax,
+ *                 lowest index on ties; next = argmax);
+ *   uniforms      host [k+1] in [0,1): u_1..u_k for the tests, u_{k+1} for the one draw (ignored
+ *                 when draft_probs is NULL, may then be NULL).
+ * Rule: accept d_i iff u_i < min(1, p_i(d_i) / q_i(d_i)) (fp32 division; 0/0 rejects), stopping at
+ * the first rejection; accepted_len = a.  next_token is drawn from max(0, p_{a+1} - q_{a+1}) if
+ * a < k, else from p_{k+1}, by the integer inverse CDF: weights floor(w * 2^40) summed as 64-bit
+ * integers to W, threshold T = floor(u * 2^24) * W >> 24, result the smallest j whose running sum
+ * exceeds T (W = 0: lowest-index argmax of p_{a+1}).
+ * Afterwards the client's committed length is prefix_len + a + 1 with next_token pending, the
+ * cache keeps the pending row and the a accepted rows, the k - a rejected rows are zeroed and
+ * blocks wholly beyond the kept rows return to the pool.  Synchronises `stream`; the two host
+ * outputs are valid on return. */
+int pipesd_nav_verify(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t prefix_len,
+                      const int32_t *draft_tokens, int32_t k, const float *draft_probs,
+                      const float *uniforms, int32_t *accepted_len, int32_t *next_token, void *stream);
+
+/* Cut client `seq` back to new_prefix_len committed tokens (1 <= new <= current, else ESTATE); the
+ * last kept token becomes pending (Appendix B: buffered drafts that are no longer valid are
+ * discarded and drafting restarts from the last accepted token).  Host bookkeeping only. */
+int pipesd_kv_rollback(pipesd_kv *kv, int32_t seq, int32_t new_prefix_len);
+int pipesd_kv_len(const pipesd_kv *kv, int32_t seq, int32_t *prefix_len);
+/* Blocks currently free in the pool / held by a client. */
+int pipesd_kv_free_blocks(const pipesd_kv *kv, int32_t *n_free);
+int pipesd_kv_seq_blocks(const pipesd_kv *kv, int32_t seq, int32_t *n_blocks);
+
+/* Test hook: run rows [pending, tokens[0..n_extra-1]] (n_extra >= 0 host tokens) through the
+ * forward and copy the (n_extra + 1) x vocab fp32 logits to the host array `logits_out`.  The rows
+ * are written to the cache but not committed: the client's state is unchanged.  Synchronises. */
+int pipesd_forward_logits(pipesd_model *model, pipesd_kv *kv, int32_t seq, const int32_t *tokens,
+                          int32_t n_extra, float *logits_out, void *stream);
+
+/* Test hook: the decision step alone on caller-supplied probabilities.
+ *   p device fp32 [k+1][vocab], q device fp32 [k][vocab], draft_tokens host [k], uniforms host [k+1].
+ * Same rule and same kernels as pipesd_nav_verify.  Synchronises. */
+int pipesd_spec_accept(const float *p, const float *q, const int32_t *draft_tokens, int32_t k,
+                       int32_t vocab, const float *uniforms, int32_t *accepted_len, int32_t *next_token,
+                       void *stream);
+
+/* Test hook: copy the cached key and value of one (layer, position) of client `seq` to host fp32
+ * arrays [n_kv_heads*head_dim] (keys as stored, i.e. rotated).  Synchronises the device. */
+int pipesd_kv_read(const pipesd_model *model, const pipesd_kv *kv, int32_t seq, int32_t layer,
+                   int32_t pos, float *k_out, float *v_out);
+
+/* Per-kernel timing for roofline accounting: when enabled, every launch of the selected kernel
+ * class is bracketed by HIP events on its stream.  pipesd_profile_read waits for them and returns
+ * the number of launches and their summed duration since the last read. */
+enum { PIPESD_PROF_OFF = 0, PIPESD_PROF_GEMM_QKV = 1, PIPESD_PROF_GEMM_O = 2, PIPESD_PROF_GEMM_GATEUP = 3,
+       PIPESD_PROF_GEMM_DOWN = 4, PIPESD_PROF_GEMM_LMHEAD = 5, PIPESD_PROF_ATTN = 6, PIPESD_PROF_VERIFY = 7,
+       PIPESD_PROF_ALL_GEMM = 8 };
+int pipesd_profile_select(pipesd_model *model, int32_t kernel_class);
+int pipesd_profile_read(pipesd_model *model, int32_t *n_launches, double *total_ms);
+
+const char *pipesd_strerror(int status);
+/* Text of the HIP call that made this thread's most recent call return PIPESD_EHIP ("" if none). */
+const char *pipesd_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPESD_H */

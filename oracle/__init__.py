@@ -10,7 +10,9 @@ It shares no code with the HIP library and imports nothing from it; inputs arriv
 numpy arrays.
 
 Precision: fp32 arrays throughout (weights stored as bf16 are widened exactly), which is the
-precision the decision step is defined in; matmuls are numpy's.
+precision the decision step is defined in; matmuls are numpy's.  The KV cache is part of the
+state's definition: a bf16 model keeps its keys and values in bf16, so the checker rounds them
+on append exactly as any bf16 cache must, and reads the rounded values.
 
 Pins (tests/test_oracle_*.py): row block == sequential single-token forwards; greedy ==
 longest argmax-matching prefix; exact output law == target law on tiny vocabularies, measured

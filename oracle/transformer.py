@@ -19,6 +19,16 @@ def widen(w) -> np.ndarray:
     return w
 
 
+def to_cache_format(x: np.ndarray, bf16: bool) -> np.ndarray:
+    """Keys and values are stored in the model's storage type.  For bf16 models that is a
+    round-to-nearest-even of the fp32 value to 8 significand bits; later reads see that value."""
+    if not bf16:
+        return x
+    b = np.ascontiguousarray(x, dtype=F32).view(np.uint32)
+    r = ((b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) << np.uint32(16)
+    return r.view(F32).reshape(x.shape)
+
+
 def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
     """h = x / sqrt(mean(x^2) + eps) * g, per row."""
     ms = np.mean(x.astype(F32) ** 2, axis=-1, keepdims=True, dtype=F32)
@@ -78,8 +88,8 @@ class OracleModel:
             v = (h @ widen(w["wv"][l]).T).reshape(m, s.n_kv_heads, s.head_dim)
             q = rope(q, cos, sin)
             k = rope(k, cos, sin)
-            K[l][start_pos:start_pos + m] = k
-            V[l][start_pos:start_pos + m] = v
+            K[l][start_pos:start_pos + m] = to_cache_format(k, s.dtype == 1)
+            V[l][start_pos:start_pos + m] = to_cache_format(v, s.dtype == 1)
             o = np.empty((m, s.n_q_heads, s.head_dim), dtype=F32)
             for g in range(s.n_q_heads):
                 kvh = g // group

@@ -1,0 +1,784 @@
+// Host side of the NAV library: handles, paged-KV bookkeeping, the per-pass launch sequence.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace pipesd;
+
+namespace pipesd {
+void gemm_scratch_need(int N, int K, int n_cu, size_t* partial_floats, size_t* ssq_floats, size_t* counters);
+int device_cu_count();
+}
+
+// text of the most recent failing HIP call of this thread, for pipesd_last_hip_error()
+static thread_local char g_hip_msg[256] = "";
+static int hip_fail(hipError_t e, const char* what) {
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
+  return PIPESD_EHIP;
+}
+
+#define HIP_TRY(expr)                                 \
+  do {                                                \
+    hipError_t _e = (expr);                           \
+    if (_e != hipSuccess) return hip_fail(_e, #expr); \
+  } while (0)
+
+extern "C" const char* pipesd_last_hip_error(void) { return g_hip_msg; }
+
+// ---------------------------------------------------------------------------------------------
+// handles
+// ---------------------------------------------------------------------------------------------
+struct pipesd_model {
+  pipesd_config cfg{};
+  bool on_device = false;
+  size_t esz = 2;
+  // library-owned device copies
+  void* tok_emb = nullptr;
+  float* final_norm = nullptr;
+  void* lm_head = nullptr;
+  std::vector<float*> attn_norm, ffn_norm;
+  std::vector<void*> wqkv, wo, wgu, wdown;  // fp32: row-major stacks; bf16: matrix-core tiles
+  GemmPlan p_qkv{}, p_o{}, p_gu{}, p_down{}, p_lm{};
+  double* theta = nullptr;
+  // activation workspace (rows x width, fp32)
+  float *xres = nullptr, *hbuf = nullptr, *qkv = nullptr, *qbuf = nullptr, *attn_out = nullptr, *gu = nullptr,
+        *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
+  float* gemm_partial = nullptr;
+  float* ssq_partial = nullptr;
+  unsigned* counters = nullptr;
+  float* attn_part = nullptr;
+  size_t attn_part_floats = 0;
+  float* row_stats = nullptr;
+  unsigned long long* scan_partial = nullptr;
+  int32_t* result_dev = nullptr;
+  int32_t* result_host = nullptr;  // pinned
+  std::vector<void*> owned;
+  // kernel timing
+  int prof_class = PIPESD_PROF_OFF;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  size_t prof_used = 0;
+};
+
+struct SeqState {
+  std::vector<int32_t> text;    // committed tokens; all but the last are cached, the last is pending
+  std::vector<int32_t> blocks;  // KV blocks in position order
+  int32_t table_synced = 0;     // block-table entries already mirrored on the device
+};
+
+struct pipesd_kv {
+  const pipesd_model* model = nullptr;
+  int32_t max_seqs = 0, n_blocks = 0;
+  void* pool = nullptr;
+  std::vector<int32_t> free_list;
+  std::vector<SeqState> seqs;
+  int32_t* table_dev = nullptr;  // [max_seqs][n_blocks]
+  int64_t layer_stride = 0, v_offset = 0;
+  int32_t block_elems = 0;
+};
+
+static constexpr int kCounterSlots = 1 << 16;
+static constexpr int kAttnChunk = 32;
+
+static int dev_alloc(pipesd_model* m, void** p, size_t bytes) {
+  if (hipMalloc(p, bytes ? bytes : 256) != hipSuccess) return PIPESD_ENOMEM;
+  m->owned.push_back(*p);
+  return PIPESD_OK;
+}
+
+static int check_config(const pipesd_config* c) {
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 ||
+      c->d_ffn < 1 || c->vocab < 1)
+    return PIPESD_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0 || (c->head_dim & 1) || c->head_dim > 128) return PIPESD_EINVAL;
+  if (c->dtype != PIPESD_F32 && c->dtype != PIPESD_BF16) return PIPESD_EINVAL;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return PIPESD_EINVAL;
+  if (c->dtype == PIPESD_BF16) {
+    const int qd = c->n_q_heads * c->head_dim;
+    if (c->d_model % 512 || qd % 512 || c->d_ffn % 512 || c->head_dim % 16) return PIPESD_EINVAL;
+  } else {
+    if (c->d_model % 4 || c->d_ffn % 4) return PIPESD_EINVAL;
+  }
+  return PIPESD_OK;
+}
+
+static void model_free(pipesd_model* m) {
+  if (!m) return;
+  for (void* p : m->owned) (void)hipFree(p);
+  if (m->result_host) (void)hipHostFree(m->result_host);
+  for (auto& e : m->prof_events) {
+    (void)hipEventDestroy(e.first);
+    (void)hipEventDestroy(e.second);
+  }
+  delete m;
+}
+
+static int copy_dev(pipesd_model* m, void** dst, const void* src, size_t bytes) {
+  int rc = dev_alloc(m, dst, bytes);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpy(*dst, src, bytes, hipMemcpyDeviceToDevice));
+  return PIPESD_OK;
+}
+
+static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
+  const pipesd_config& c = m->cfg;
+  const size_t e = m->esz;
+  const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+  const int L = c.n_layers;
+  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->attn_norm || !w->ffn_norm || !w->wq || !w->wk || !w->wv ||
+      !w->wo || !w->w_gate || !w->w_up || !w->w_down)
+    return PIPESD_EINVAL;
+  for (int l = 0; l < L; ++l)
+    if (!w->attn_norm[l] || !w->ffn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->w_gate[l] ||
+        !w->w_up[l] || !w->w_down[l])
+      return PIPESD_EINVAL;
+  int rc;
+  if ((rc = copy_dev(m, &m->tok_emb, w->tok_emb, (size_t)V * d * e))) return rc;
+  if ((rc = copy_dev(m, (void**)&m->final_norm, w->final_norm, (size_t)d * 4))) return rc;
+  m->attn_norm.resize(L);
+  m->ffn_norm.resize(L);
+  m->wqkv.resize(L);
+  m->wo.resize(L);
+  m->wgu.resize(L);
+  m->wdown.resize(L);
+  const int nqkv = qd + 2 * kvd;
+  if (c.dtype == PIPESD_F32) {
+    if ((rc = copy_dev(m, &m->lm_head, w->lm_head, (size_t)V * d * e))) return rc;
+  } else {
+    const int nt = (V + 15) / 16;
+    if ((rc = dev_alloc(m, &m->lm_head, (size_t)nt * 16 * d * e))) return rc;
+    PackSrc ps{{(const uint16_t*)w->lm_head, nullptr, nullptr}, {V, 0, 0}};
+    HIP_TRY(launch_pack_bf16(ps, 1, d, PACK_PLAIN, 0, m->lm_head, nt, nullptr));
+  }
+  for (int l = 0; l < L; ++l) {
+    if ((rc = copy_dev(m, (void**)&m->attn_norm[l], w->attn_norm[l], (size_t)d * 4))) return rc;
+    if ((rc = copy_dev(m, (void**)&m->ffn_norm[l], w->ffn_norm[l], (size_t)d * 4))) return rc;
+    if (c.dtype == PIPESD_F32) {
+      if ((rc = dev_alloc(m, &m->wqkv[l], (size_t)nqkv * d * e))) return rc;
+      char* p = (char*)m->wqkv[l];
+      HIP_TRY(hipMemcpy(p, w->wq[l], (size_t)qd * d * e, hipMemcpyDeviceToDevice));
+      HIP_TRY(hipMemcpy(p + (size_t)qd * d * e, w->wk[l], (size_t)kvd * d * e, hipMemcpyDeviceToDevice));
+      HIP_TRY(hipMemcpy(p + (size_t)(qd + kvd) * d * e, w->wv[l], (size_t)kvd * d * e, hipMemcpyDeviceToDevice));
+      if ((rc = copy_dev(m, &m->wo[l], w->wo[l], (size_t)d * qd * e))) return rc;
+      if ((rc = dev_alloc(m, &m->wgu[l], (size_t)2 * F * d * e))) return rc;
+      p = (char*)m->wgu[l];
+      HIP_TRY(hipMemcpy(p, w->w_gate[l], (size_t)F * d * e, hipMemcpyDeviceToDevice));
+      HIP_TRY(hipMemcpy(p + (size_t)F * d * e, w->w_up[l], (size_t)F * d * e, hipMemcpyDeviceToDevice));
+      if ((rc = copy_dev(m, &m->wdown[l], w->w_down[l], (size_t)d * F * e))) return rc;
+    } else {
+      if ((rc = dev_alloc(m, &m->wqkv[l], (size_t)nqkv * d * e))) return rc;
+      PackSrc pq{{(const uint16_t*)w->wq[l], (const uint16_t*)w->wk[l], (const uint16_t*)w->wv[l]}, {qd, kvd, kvd}};
+      HIP_TRY(launch_pack_bf16(pq, 3, d, PACK_HALVES, c.head_dim / 2, m->wqkv[l], nqkv / 16, nullptr));
+      if ((rc = dev_alloc(m, &m->wo[l], (size_t)d * qd * e))) return rc;
+      PackSrc po{{(const uint16_t*)w->wo[l], nullptr, nullptr}, {d, 0, 0}};
+      HIP_TRY(launch_pack_bf16(po, 1, qd, PACK_PLAIN, 0, m->wo[l], d / 16, nullptr));
+      if ((rc = dev_alloc(m, &m->wgu[l], (size_t)2 * F * d * e))) return rc;
+      PackSrc pg{{(const uint16_t*)w->w_gate[l], (const uint16_t*)w->w_up[l], nullptr}, {F, F, 0}};
+      HIP_TRY(launch_pack_bf16(pg, 2, d, PACK_HALVES, F, m->wgu[l], 2 * F / 16, nullptr));
+      if ((rc = dev_alloc(m, &m->wdown[l], (size_t)d * F * e))) return rc;
+      PackSrc pd{{(const uint16_t*)w->w_down[l], nullptr, nullptr}, {d, 0, 0}};
+      HIP_TRY(launch_pack_bf16(pd, 1, F, PACK_PLAIN, 0, m->wdown[l], d / 16, nullptr));
+    }
+  }
+  m->p_qkv = plan_gemm(nqkv, d, 0);
+  m->p_o = plan_gemm(d, qd, 0);
+  m->p_gu = plan_gemm(2 * F, d, 0);
+  m->p_down = plan_gemm(d, F, 0);
+  m->p_lm = plan_gemm(V, d, 0);
+
+  // rotary frequencies theta_i = base^(-2i/h), fp64
+  std::vector<double> th(c.head_dim / 2);
+  for (int i = 0; i < c.head_dim / 2; ++i) th[i] = pow((double)c.rope_base, -2.0 * i / c.head_dim);
+  if ((rc = dev_alloc(m, (void**)&m->theta, th.size() * 8))) return rc;
+  HIP_TRY(hipMemcpy(m->theta, th.data(), th.size() * 8, hipMemcpyHostToDevice));
+
+  const size_t R = kMaxRows;
+  if ((rc = dev_alloc(m, (void**)&m->xres, R * d * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->hbuf, R * (size_t)(d > qd ? d : qd) * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->qkv, R * nqkv * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->qbuf, R * qd * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->attn_out, R * qd * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->gu, R * 2 * (size_t)F * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->act2, R * (size_t)F * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->logits, R * (size_t)V * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->rope_cs, R * c.head_dim * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->row_stats, (R * 64 * 2 + 64) * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->scan_partial, 64 * 8))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->result_dev, 4 * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->counters, (size_t)kCounterSlots * 4))) return rc;
+  HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
+  if (c.dtype == PIPESD_BF16) {
+    const int n_cu = device_cu_count();
+    if (n_cu <= 0) return PIPESD_EHIP;
+    size_t pf = 0, sf = 0, cn = 0;
+    const int shapes[5][2] = {{nqkv, d}, {d, qd}, {2 * F, d}, {d, F}, {V, d}};
+    for (auto& sh : shapes) {
+      size_t a = 0, b = 0, cc = 0;
+      gemm_scratch_need(sh[0], sh[1], n_cu, &a, &b, &cc);
+      if (a > pf) pf = a;
+      if (b > sf) sf = b;
+      if (cc > cn) cn = cc;
+    }
+    if (cn >= (size_t)kCounterSlots - 1) return PIPESD_EINVAL;
+    if ((rc = dev_alloc(m, (void**)&m->gemm_partial, pf * 4))) return rc;
+    if ((rc = dev_alloc(m, (void**)&m->ssq_partial, sf * 4))) return rc;
+  }
+  HIP_TRY(hipHostMalloc((void**)&m->result_host, 64, hipHostMallocDefault));
+  HIP_TRY(hipDeviceSynchronize());
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_model_create(const pipesd_config* cfg, const pipesd_weights* weights, pipesd_model** out) {
+  if (!cfg || !out) return PIPESD_EINVAL;
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  pipesd_model* m = new (std::nothrow) pipesd_model();
+  if (!m) return PIPESD_ENOMEM;
+  m->cfg = *cfg;
+  m->esz = cfg->dtype == PIPESD_F32 ? 4 : 2;
+  if (weights) {
+    rc = build_device_model(m, weights);
+    if (rc) {
+      model_free(m);
+      return rc;
+    }
+    m->on_device = true;
+  }
+  *out = m;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_model_destroy(pipesd_model* model) {
+  if (!model) return PIPESD_EINVAL;
+  if (model->on_device) (void)hipDeviceSynchronize();
+  model_free(model);
+  return PIPESD_OK;
+}
+
+extern "C" size_t pipesd_kv_block_bytes(const pipesd_model* model, int32_t block_tokens) {
+  if (!model || block_tokens != kBlockTokens) return 0;
+  const pipesd_config& c = model->cfg;
+  return (size_t)c.n_layers * 2 * c.n_kv_heads * c.head_dim * block_tokens * model->esz;
+}
+
+extern "C" int pipesd_kv_create(const pipesd_model* model, int32_t max_seqs, int32_t block_tokens, void* pool,
+                                size_t pool_bytes, pipesd_kv** out) {
+  if (!model || !out || max_seqs < 1 || block_tokens != kBlockTokens) return PIPESD_EINVAL;
+  const size_t bb = pipesd_kv_block_bytes(model, block_tokens);
+  if (pool_bytes / bb < 1 || pool_bytes / bb > 0x7fffffff) return PIPESD_EINVAL;
+  if (pool && ((uintptr_t)pool & 255)) return PIPESD_EINVAL;
+  if (pool && !model->on_device) return PIPESD_ESTATE;
+  pipesd_kv* kv = new (std::nothrow) pipesd_kv();
+  if (!kv) return PIPESD_ENOMEM;
+  kv->model = model;
+  kv->max_seqs = max_seqs;
+  kv->n_blocks = (int32_t)(pool_bytes / bb);
+  kv->pool = pool;
+  kv->seqs.resize(max_seqs);
+  kv->free_list.reserve(kv->n_blocks);
+  for (int32_t b = kv->n_blocks - 1; b >= 0; --b) kv->free_list.push_back(b);  // block 0 is handed out first
+  const pipesd_config& c = model->cfg;
+  kv->block_elems = c.n_kv_heads * kBlockTokens * c.head_dim;
+  kv->v_offset = (int64_t)kv->n_blocks * kv->block_elems;
+  kv->layer_stride = 2 * kv->v_offset;
+  if (pool) {
+    if (hipMalloc((void**)&kv->table_dev, (size_t)max_seqs * kv->n_blocks * 4) != hipSuccess) {
+      delete kv;
+      return PIPESD_ENOMEM;
+    }
+    if (hipMemset(kv->table_dev, 0, (size_t)max_seqs * kv->n_blocks * 4) != hipSuccess) {
+      (void)hipFree(kv->table_dev);
+      delete kv;
+      return PIPESD_EHIP;
+    }
+  }
+  *out = kv;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_destroy(pipesd_kv* kv) {
+  if (!kv) return PIPESD_EINVAL;
+  if (kv->table_dev) {
+    (void)hipDeviceSynchronize();
+    (void)hipFree(kv->table_dev);
+  }
+  delete kv;
+  return PIPESD_OK;
+}
+
+static bool seq_ok(const pipesd_kv* kv, int32_t seq) { return kv && seq >= 0 && seq < kv->max_seqs; }
+
+// blocks needed to hold `rows` cached rows
+static int32_t blocks_for(int32_t rows) { return (rows + kBlockTokens - 1) / kBlockTokens; }
+
+// give back every block wholly beyond `rows` cached rows
+static void release_beyond(pipesd_kv* kv, SeqState& s, int32_t rows) {
+  const int32_t keep = blocks_for(rows);
+  while ((int32_t)s.blocks.size() > keep) {
+    kv->free_list.push_back(s.blocks.back());
+    s.blocks.pop_back();
+  }
+  if (s.table_synced > keep) s.table_synced = keep;
+}
+
+extern "C" int pipesd_seq_reset(pipesd_kv* kv, int32_t seq) {
+  if (!seq_ok(kv, seq)) return PIPESD_EINVAL;
+  SeqState& s = kv->seqs[seq];
+  release_beyond(kv, s, 0);
+  s.text.clear();
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_rollback(pipesd_kv* kv, int32_t seq, int32_t new_prefix_len) {
+  if (!seq_ok(kv, seq)) return PIPESD_EINVAL;
+  SeqState& s = kv->seqs[seq];
+  if (new_prefix_len < 1 || new_prefix_len > (int32_t)s.text.size()) return PIPESD_ESTATE;
+  s.text.resize(new_prefix_len);
+  release_beyond(kv, s, new_prefix_len - 1);
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_len(const pipesd_kv* kv, int32_t seq, int32_t* prefix_len) {
+  if (!seq_ok(kv, seq) || !prefix_len) return PIPESD_EINVAL;
+  *prefix_len = (int32_t)kv->seqs[seq].text.size();
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_free_blocks(const pipesd_kv* kv, int32_t* n_free) {
+  if (!kv || !n_free) return PIPESD_EINVAL;
+  *n_free = (int32_t)kv->free_list.size();
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_seq_blocks(const pipesd_kv* kv, int32_t seq, int32_t* n_blocks) {
+  if (!seq_ok(kv, seq) || !n_blocks) return PIPESD_EINVAL;
+  *n_blocks = (int32_t)kv->seqs[seq].blocks.size();
+  return PIPESD_OK;
+}
+
+extern "C" const char* pipesd_strerror(int status) {
+  switch (status) {
+    case PIPESD_OK: return "ok";
+    case PIPESD_EINVAL: return "invalid argument";
+    case PIPESD_ENOMEM: return "out of KV blocks or device memory";
+    case PIPESD_ESTATE: return "call does not fit the sequence state";
+    case PIPESD_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernel timing
+// ---------------------------------------------------------------------------------------------
+extern "C" int pipesd_profile_select(pipesd_model* model, int32_t kernel_class) {
+  if (!model || kernel_class < PIPESD_PROF_OFF || kernel_class > PIPESD_PROF_ALL_GEMM) return PIPESD_EINVAL;
+  model->prof_class = kernel_class;
+  model->prof_used = 0;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_profile_read(pipesd_model* model, int32_t* n_launches, double* total_ms) {
+  if (!model || !n_launches || !total_ms) return PIPESD_EINVAL;
+  double tot = 0.0;
+  for (size_t i = 0; i < model->prof_used; ++i) {
+    HIP_TRY(hipEventSynchronize(model->prof_events[i].second));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, model->prof_events[i].first, model->prof_events[i].second));
+    tot += ms;
+  }
+  *n_launches = (int32_t)model->prof_used;
+  *total_ms = tot;
+  model->prof_used = 0;
+  return PIPESD_OK;
+}
+
+namespace {
+struct ProfScope {
+  pipesd_model* m;
+  hipStream_t st;
+  bool on;
+  ProfScope(pipesd_model* m_, int cls, hipStream_t st_) : m(m_), st(st_) {
+    on = m->prof_class != PIPESD_PROF_OFF &&
+         (m->prof_class == cls || (m->prof_class == PIPESD_PROF_ALL_GEMM && cls >= PIPESD_PROF_GEMM_QKV &&
+                                   cls <= PIPESD_PROF_GEMM_LMHEAD));
+    if (!on) return;
+    if (m->prof_used == m->prof_events.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        on = false;
+        return;
+      }
+      m->prof_events.emplace_back(a, b);
+    }
+    (void)hipEventRecord(m->prof_events[m->prof_used].first, st);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(m->prof_events[m->prof_used].second, st);
+    ++m->prof_used;
+  }
+};
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// the forward over a row block
+// ---------------------------------------------------------------------------------------------
+static KvView view_of(const pipesd_kv* kv, int32_t seq) {
+  KvView v;
+  v.pool = kv->pool;
+  v.table = kv->table_dev + (size_t)seq * kv->n_blocks;
+  v.layer_stride = kv->layer_stride;
+  v.v_offset = kv->v_offset;
+  v.block_elems = kv->block_elems;
+  v.n_kv_heads = kv->model->cfg.n_kv_heads;
+  v.head_dim = kv->model->cfg.head_dim;
+  return v;
+}
+
+// make sure the sequence owns blocks for `rows` cached rows and the device table shows them
+static int ensure_blocks(pipesd_kv* kv, int32_t seq, int32_t rows, hipStream_t st) {
+  SeqState& s = kv->seqs[seq];
+  const int32_t need = blocks_for(rows);
+  const int32_t have = (int32_t)s.blocks.size();
+  if (need - have > (int32_t)kv->free_list.size()) return PIPESD_ENOMEM;
+  for (int32_t i = have; i < need; ++i) {
+    s.blocks.push_back(kv->free_list.back());
+    kv->free_list.pop_back();
+  }
+  if (kv->table_dev && s.table_synced < (int32_t)s.blocks.size()) {
+    const int32_t first = s.table_synced, n = (int32_t)s.blocks.size() - first;
+    HIP_TRY(launch_set_table(kv->table_dev + (size_t)seq * kv->n_blocks, first, s.blocks.data() + first, n, st));
+    s.table_synced = (int32_t)s.blocks.size();
+  }
+  return PIPESD_OK;
+}
+
+static int ensure_attn_scratch(pipesd_model* m, size_t floats) {
+  if (floats <= m->attn_part_floats) return PIPESD_OK;
+  HIP_TRY(hipDeviceSynchronize());
+  if (m->attn_part) (void)hipFree(m->attn_part);
+  m->attn_part = nullptr;
+  m->attn_part_floats = 0;
+  const size_t want = floats + floats / 2;
+  if (hipMalloc((void**)&m->attn_part, want * 4) != hipSuccess) return PIPESD_ENOMEM;
+  m->attn_part_floats = want;
+  return PIPESD_OK;
+}
+
+static GemmCall gemm_call(pipesd_model* m, const GemmPlan& p, const void* wp, const float* act, int lda, int rows,
+                          const float* gain, int epi, float* out, int ldo) {
+  GemmCall c{};
+  c.plan = p;
+  c.wp = wp;
+  c.act = act;
+  c.lda = lda;
+  c.m = rows;
+  c.gain = gain;
+  c.eps = m->cfg.rms_eps;
+  c.epi = epi;
+  c.out = out;
+  c.ldo = ldo;
+  c.partial = m->gemm_partial;
+  c.ssq_partial = m->ssq_partial;
+  c.counters = m->counters;
+  c.rope_cs = m->rope_cs;
+  return c;
+}
+
+static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* row_tokens, int rows, int start_pos,
+                    bool want_logits, hipStream_t st) {
+  const pipesd_config& c = m->cfg;
+  const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
+  const int nqkv = qd + 2 * kvd;
+  const KvView view = view_of(kv, seq);
+  RowTokens rt{};
+  for (int r = 0; r < rows; ++r) rt.tok[r] = row_tokens[r];
+  const int nsplit = attn_nsplit(start_pos + rows, kAttnChunk);
+  int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 2));
+  if (rc) return rc;
+  HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
+                            st));
+  for (int l = 0; l < c.n_layers; ++l) {
+    AttnCall at{};
+    at.dtype = c.dtype;
+    at.q = m->qbuf;
+    at.kv = view;
+    at.layer = l;
+    at.m = rows;
+    at.start_pos = start_pos;
+    at.n_q_heads = c.n_q_heads;
+    at.chunk = kAttnChunk;
+    at.part = m->attn_part;
+    at.out = m->attn_out;
+    if (c.dtype == PIPESD_F32) {
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
+        HIP_TRY(launch_rmsnorm_rows(m->xres, m->attn_norm[l], c.rms_eps, rows, d, m->hbuf, st));
+        HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->wqkv[l], nqkv, d, rows, m->qkv, nqkv, 0, st));
+        HIP_TRY(launch_rope_append_f32(m->qkv, rows, start_pos, l, c.n_q_heads, view, m->rope_cs, m->qbuf, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_ATTN, st);
+        HIP_TRY(launch_attention(at, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_O, st);
+        HIP_TRY(launch_gemm_f32(m->attn_out, qd, (const float*)m->wo[l], d, qd, rows, m->xres, d, 1, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_GATEUP, st);
+        HIP_TRY(launch_rmsnorm_rows(m->xres, m->ffn_norm[l], c.rms_eps, rows, d, m->hbuf, st));
+        HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->wgu[l], 2 * F, d, rows, m->gu, 2 * F, 0, st));
+        HIP_TRY(launch_silu_mul(m->gu, rows, F, m->act2, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_DOWN, st);
+        HIP_TRY(launch_gemm_f32(m->act2, F, (const float*)m->wdown[l], d, F, rows, m->xres, d, 1, st));
+      }
+    } else {
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
+        GemmCall g = gemm_call(m, m->p_qkv, m->wqkv[l], m->xres, d, rows, m->attn_norm[l], EPI_QKV, m->qbuf, qd);
+        g.kv = view;
+        g.layer = l;
+        g.start_pos = start_pos;
+        g.n_q_heads = c.n_q_heads;
+        HIP_TRY(launch_gemm_bf16(g, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_ATTN, st);
+        HIP_TRY(launch_attention(at, st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_O, st);
+        HIP_TRY(launch_gemm_bf16(gemm_call(m, m->p_o, m->wo[l], m->attn_out, qd, rows, nullptr, EPI_RESID, m->xres, d),
+                                 st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_GATEUP, st);
+        HIP_TRY(launch_gemm_bf16(
+            gemm_call(m, m->p_gu, m->wgu[l], m->xres, d, rows, m->ffn_norm[l], EPI_SWIGLU, m->act2, F), st));
+      }
+      {
+        ProfScope ps(m, PIPESD_PROF_GEMM_DOWN, st);
+        HIP_TRY(launch_gemm_bf16(gemm_call(m, m->p_down, m->wdown[l], m->act2, F, rows, nullptr, EPI_RESID, m->xres, d),
+                                 st));
+      }
+    }
+  }
+  if (want_logits) {
+    ProfScope ps(m, PIPESD_PROF_GEMM_LMHEAD, st);
+    if (c.dtype == PIPESD_F32) {
+      HIP_TRY(launch_rmsnorm_rows(m->xres, m->final_norm, c.rms_eps, rows, d, m->hbuf, st));
+      HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->lm_head, V, d, rows, m->logits, V, 0, st));
+    } else {
+      HIP_TRY(launch_gemm_bf16(
+          gemm_call(m, m->p_lm, m->lm_head, m->xres, d, rows, m->final_norm, EPI_STORE, m->logits, V), st));
+    }
+  }
+  return PIPESD_OK;
+}
+
+static bool compute_ready(const pipesd_model* m, const pipesd_kv* kv) {
+  return m && kv && kv->model == m && m->on_device && kv->pool && kv->table_dev;
+}
+
+extern "C" int pipesd_prefill(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* tokens, int32_t n,
+                              void* stream) {
+  if (!model || !kv || !tokens || n < 1 || !seq_ok(kv, seq) || kv->model != model) return PIPESD_EINVAL;
+  for (int32_t i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= model->cfg.vocab) return PIPESD_EINVAL;
+  if (!compute_ready(model, kv)) return PIPESD_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  std::vector<int32_t> rows;
+  if (lp > 0) rows.push_back(s.text.back());
+  rows.insert(rows.end(), tokens, tokens + n - 1);
+  const int32_t start = lp > 0 ? lp - 1 : 0;
+  const int32_t cached_before = start;
+  int rc = ensure_blocks(kv, seq, start + (int32_t)rows.size(), st);
+  if (rc) return rc;
+  for (size_t i = 0; i < rows.size(); i += kMaxRows) {
+    const int nr = (int)((rows.size() - i < (size_t)kMaxRows) ? rows.size() - i : kMaxRows);
+    rc = run_rows(model, kv, seq, rows.data() + i, nr, start + (int)i, false, st);
+    if (rc) {
+      release_beyond(kv, s, cached_before);
+      return rc;
+    }
+  }
+  s.text.insert(s.text.end(), tokens, tokens + n);
+  return PIPESD_OK;
+}
+
+static int verify_common(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* extra, int32_t k,
+                         int32_t* start_out, hipStream_t st) {
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  int32_t rows[kMaxRows];
+  rows[0] = s.text.back();
+  for (int32_t i = 0; i < k; ++i) rows[i + 1] = extra[i];
+  int rc = ensure_blocks(kv, seq, lp + k, st);
+  if (rc) return rc;
+  rc = run_rows(model, kv, seq, rows, k + 1, lp - 1, true, st);
+  if (rc) release_beyond(kv, s, lp - 1);
+  *start_out = lp - 1;
+  return rc;
+}
+
+extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t prefix_len,
+                                 const int32_t* draft_tokens, int32_t k, const float* draft_probs,
+                                 const float* uniforms, int32_t* accepted_len, int32_t* next_token, void* stream) {
+  if (!model || !kv || !draft_tokens || !accepted_len || !next_token || !seq_ok(kv, seq) || kv->model != model)
+    return PIPESD_EINVAL;
+  if (k < 1 || k > kMaxRows - 1) return PIPESD_EINVAL;
+  if (draft_probs && !uniforms) return PIPESD_EINVAL;
+  for (int32_t i = 0; i < k; ++i)
+    if (draft_tokens[i] < 0 || draft_tokens[i] >= model->cfg.vocab) return PIPESD_EINVAL;
+  if (draft_probs)
+    for (int32_t i = 0; i <= k; ++i)
+      if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return PIPESD_EINVAL;
+  if (!compute_ready(model, kv)) return PIPESD_ESTATE;
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  if (lp < 1 || prefix_len != lp) return PIPESD_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t start = 0;
+  int rc = verify_common(model, kv, seq, draft_tokens, k, &start, st);
+  if (rc) return rc;
+
+  VerifyCall vc{};
+  vc.logits_or_p = model->logits;
+  vc.q = draft_probs;
+  vc.k = k;
+  vc.V = model->cfg.vocab;
+  for (int32_t i = 0; i < k; ++i) vc.drafts.tok[i] = draft_tokens[i];
+  if (draft_probs)
+    for (int32_t i = 0; i <= k; ++i) vc.u[i] = uniforms[i];
+  vc.row_stats = model->row_stats;
+  vc.scan_partial = model->scan_partial;
+  vc.counter = model->counters + (kCounterSlots - 1);
+  vc.result = model->result_dev;
+  hipError_t e = hipSuccess;
+  {
+    ProfScope ps(model, PIPESD_PROF_VERIFY, st);
+    if (draft_probs) {
+      e = launch_softmax_rows(vc, st);
+      if (e == hipSuccess) e = launch_spec_accept(vc, st);
+    } else {
+      e = launch_greedy_accept(vc, st);
+    }
+    if (e == hipSuccess) e = launch_kv_trim(model->cfg.dtype, view_of(kv, seq), model->cfg.n_layers, start, k,
+                                            model->result_dev, st);
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(model->result_host, model->result_dev, 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    release_beyond(kv, s, lp - 1);
+    return hip_fail(e, "verify step");
+  }
+  const int32_t a = model->result_host[0], nxt = model->result_host[1];
+  if (a < 0 || a > k || nxt < 0 || nxt >= model->cfg.vocab) {
+    release_beyond(kv, s, lp - 1);
+    return PIPESD_EHIP;
+  }
+  s.text.insert(s.text.end(), draft_tokens, draft_tokens + a);
+  s.text.push_back(nxt);
+  release_beyond(kv, s, lp + a);
+  *accepted_len = a;
+  *next_token = nxt;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_forward_logits(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* tokens,
+                                     int32_t n_extra, float* logits_out, void* stream) {
+  if (!model || !kv || !logits_out || !seq_ok(kv, seq) || kv->model != model) return PIPESD_EINVAL;
+  if (n_extra < 0 || n_extra > kMaxRows - 1 || (n_extra > 0 && !tokens)) return PIPESD_EINVAL;
+  for (int32_t i = 0; i < n_extra; ++i)
+    if (tokens[i] < 0 || tokens[i] >= model->cfg.vocab) return PIPESD_EINVAL;
+  if (!compute_ready(model, kv)) return PIPESD_ESTATE;
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  if (lp < 1) return PIPESD_ESTATE;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t start = 0;
+  int rc = verify_common(model, kv, seq, tokens, n_extra, &start, st);
+  if (rc) return rc;
+  hipError_t e = hipMemcpyAsync(logits_out, model->logits, (size_t)(n_extra + 1) * model->cfg.vocab * 4,
+                                hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  release_beyond(kv, s, lp - 1);
+  return e == hipSuccess ? PIPESD_OK : hip_fail(e, "logits copy");
+}
+
+extern "C" int pipesd_spec_accept(const float* p, const float* q, const int32_t* draft_tokens, int32_t k, int32_t vocab,
+                                  const float* uniforms, int32_t* accepted_len, int32_t* next_token, void* stream) {
+  if (!p || !q || !draft_tokens || !uniforms || !accepted_len || !next_token) return PIPESD_EINVAL;
+  if (k < 1 || k > kMaxRows - 1 || vocab < 1) return PIPESD_EINVAL;
+  for (int32_t i = 0; i < k; ++i)
+    if (draft_tokens[i] < 0 || draft_tokens[i] >= vocab) return PIPESD_EINVAL;
+  for (int32_t i = 0; i <= k; ++i)
+    if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return PIPESD_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  char* scratch = nullptr;
+  HIP_TRY(hipMalloc((void**)&scratch, 4096));
+  hipError_t e = hipMemsetAsync(scratch, 0, 4096, st);
+  VerifyCall vc{};
+  vc.logits_or_p = const_cast<float*>(p);
+  vc.q = q;
+  vc.k = k;
+  vc.V = vocab;
+  for (int32_t i = 0; i < k; ++i) vc.drafts.tok[i] = draft_tokens[i];
+  for (int32_t i = 0; i <= k; ++i) vc.u[i] = uniforms[i];
+  vc.scan_partial = (unsigned long long*)scratch;      // 64 x 8 bytes
+  vc.counter = (unsigned*)(scratch + 1024);
+  vc.result = (int32_t*)(scratch + 2048);
+  int32_t host[2] = {-1, -1};
+  if (e == hipSuccess) e = launch_spec_accept(vc, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(host, vc.result, 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  (void)hipFree(scratch);
+  if (e != hipSuccess) return hip_fail(e, "decision step");
+  *accepted_len = host[0];
+  *next_token = host[1];
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_kv_read(const pipesd_model* model, const pipesd_kv* kv, int32_t seq, int32_t layer, int32_t pos,
+                              float* k_out, float* v_out) {
+  if (!model || !kv || !k_out || !v_out || !seq_ok(kv, seq) || kv->model != model) return PIPESD_EINVAL;
+  if (!compute_ready(model, kv)) return PIPESD_ESTATE;
+  const pipesd_config& c = model->cfg;
+  const SeqState& s = kv->seqs[seq];
+  if (layer < 0 || layer >= c.n_layers || pos < 0 || pos / kBlockTokens >= (int32_t)s.blocks.size())
+    return PIPESD_EINVAL;
+  HIP_TRY(hipDeviceSynchronize());
+  const size_t e = model->esz;
+  const int h = c.head_dim, slot = pos % kBlockTokens;
+  const int64_t base = (int64_t)layer * kv->layer_stride + (int64_t)s.blocks[pos / kBlockTokens] * kv->block_elems;
+  std::vector<unsigned char> tk((size_t)h * e), tv((size_t)h * e);
+  for (int kvh = 0; kvh < c.n_kv_heads; ++kvh) {
+    const char* kp = (const char*)kv->pool + (base + ((int64_t)kvh * kBlockTokens + slot) * h) * e;
+    const char* vp = (const char*)kv->pool + (base + kv->v_offset + (int64_t)kvh * h * kBlockTokens + slot) * e;
+    HIP_TRY(hipMemcpy(tk.data(), kp, (size_t)h * e, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy2D(tv.data(), e, vp, (size_t)kBlockTokens * e, e, h, hipMemcpyDeviceToHost));
+    for (int i = 0; i < h; ++i) {
+      if (e == 4) {
+        memcpy(&k_out[kvh * h + i], tk.data() + (size_t)i * 4, 4);
+        memcpy(&v_out[kvh * h + i], tv.data() + (size_t)i * 4, 4);
+      } else {
+        uint16_t kb, vb;
+        memcpy(&kb, tk.data() + (size_t)i * 2, 2);
+        memcpy(&vb, tv.data() + (size_t)i * 2, 2);
+        const uint32_t ku = (uint32_t)kb << 16, vu = (uint32_t)vb << 16;
+        memcpy(&k_out[kvh * h + i], &ku, 4);
+        memcpy(&v_out[kvh * h + i], &vu, 4);
+      }
+    }
+  }
+  return PIPESD_OK;
+}

@@ -1,0 +1,146 @@
+// Shared declarations of the NAV library's HIP sources (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pipesd.h"
+
+namespace pipesd {
+
+constexpr int kMaxRows = PIPESD_MAX_ROWS;  // rows per pass
+constexpr int kBlockTokens = 16;           // tokens per KV block
+constexpr int kWave = 64;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_bits_to_f32(p[i]); }
+__device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
+
+// Where a sequence's keys and values live.  Per layer the pool holds all key blocks, then all
+// value blocks; a key block is [kv_head][token][head_dim], a value block [kv_head][head_dim][token].
+struct KvView {
+  void* pool;
+  const int32_t* table;  // device block table of the sequence
+  int64_t layer_stride;  // elements between layers (2 * n_blocks * block_elems)
+  int64_t v_offset;      // elements from a layer's key blocks to its value blocks
+  int32_t block_elems;   // n_kv_heads * 16 * head_dim
+  int32_t n_kv_heads, head_dim;
+};
+
+__device__ __forceinline__ int64_t k_index(const KvView& kv, int layer, int pos, int kvh, int e) {
+  const int blk = kv.table[pos / kBlockTokens];
+  return (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems +
+         ((int64_t)kvh * kBlockTokens + (pos % kBlockTokens)) * kv.head_dim + e;
+}
+__device__ __forceinline__ int64_t v_index(const KvView& kv, int layer, int pos, int kvh, int e) {
+  const int blk = kv.table[pos / kBlockTokens];
+  return (int64_t)layer * kv.layer_stride + kv.v_offset + (int64_t)blk * kv.block_elems +
+         ((int64_t)kvh * kv.head_dim + e) * kBlockTokens + (pos % kBlockTokens);
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers (one per kernel family); all enqueue on `st` and return the launch status
+// ---------------------------------------------------------------------------------------------
+struct RowTokens {
+  int32_t tok[kMaxRows];
+};
+
+// embedding gather into the fp32 residual stream + rotary cos/sin of the m positions
+hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, int m, int start_pos, int d_model,
+                             int head_dim, const double* theta, float* xres, float* rope_cs, hipStream_t st);
+
+// ---- fp32 path (plain ALU kernels) ----
+hipError_t launch_rmsnorm_rows(const float* x, const float* gain, float eps, int m, int d, float* out, hipStream_t st);
+hipError_t launch_gemm_f32(const float* act, int lda, const float* w, int N, int K, int m, float* out, int ldo,
+                           int add_to_out, hipStream_t st);
+hipError_t launch_rope_append_f32(const float* qkv, int m, int start_pos, int layer, int n_q_heads, const KvView& kv,
+                                  const float* rope_cs, float* qbuf, hipStream_t st);
+hipError_t launch_silu_mul(const float* gu, int m, int d_ffn, float* act2, hipStream_t st);
+
+// ---- bf16 path: skinny GEMM on the matrix cores over re-tiled weights ----
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
+enum PackMode { PACK_PLAIN = 0, PACK_HALVES = 1 };
+
+struct GemmPlan {  // launch shape of one GEMM, fixed when the model is created
+  int K, N, ntiles;
+  int W, S, grid, tpr, nt;  // waves per workgroup, K splits, workgroups, n-tiles per range, reduce batch
+};
+GemmPlan plan_gemm(int N, int K, int n_cu);
+
+struct GemmCall {
+  GemmPlan plan;
+  const void* wp;     // re-tiled weights
+  const float* act;   // [m][lda] fp32
+  int lda, m;
+  const float* gain;  // RMSNorm gain [K] (fused norm) or nullptr
+  float eps;
+  int epi;
+  float* out;         // STORE: [m][ldo]; RESID: residual stream [m][ldo]; SWIGLU: [m][ldo]; QKV: query buffer
+  int ldo;
+  // QKV epilogue
+  KvView kv;
+  int layer, start_pos, n_q_heads;
+  const float* rope_cs;
+  // split-K scratch
+  float* partial;
+  float* ssq_partial;
+  unsigned* counters;
+};
+hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st);
+
+// re-tile [rows][K] bf16 row-major (up to 3 stacked sources) into 16-row x 32-column matrix-core
+// fragments; PACK_HALVES makes tile rows 8..15 the partners (second source half / second half of
+// the head) of rows 0..7.
+struct PackSrc {
+  const uint16_t* src[3];
+  int rows[3];
+};
+hipError_t launch_pack_bf16(const PackSrc& s, int n_src, int K, int mode, int pair_span, void* dst, int ntiles,
+                            hipStream_t st);
+
+// ---- attention over the paged cache (both dtypes) ----
+struct AttnCall {
+  int dtype;
+  const float* q;  // [m][n_q_heads*head_dim]
+  KvView kv;
+  int layer, m, start_pos, n_q_heads;
+  int chunk;       // tokens per workgroup
+  float* part;     // [(head*m + r)*nsplit + split][head_dim + 2]
+  float* out;      // [m][n_q_heads*head_dim]
+};
+int attn_nsplit(int total_tokens, int chunk);
+hipError_t launch_attention(const AttnCall& c, hipStream_t st);
+
+// ---- vocabulary-wide decision ----
+struct VerifyCall {
+  float* logits_or_p;   // [k+1][V]
+  const float* q;       // [k][V] or nullptr (token matching)
+  int k, V;
+  RowTokens drafts;     // tok[0..k-1]
+  float u[kMaxRows];    // u[0..k]
+  float* row_stats;     // scratch [rows][nchunk][2]
+  unsigned long long* scan_partial;  // scratch [nblocks]
+  unsigned* counter;    // one zeroed counter
+  int32_t* result;      // device [2]: accepted_len, next_token
+};
+hipError_t launch_softmax_rows(const VerifyCall& c, hipStream_t st);  // logits -> probabilities in place
+hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st);   // decision on probabilities
+hipError_t launch_greedy_accept(const VerifyCall& c, hipStream_t st); // decision on logits
+
+// zero the cached rows of positions [first_pos + result[0] + 1, first_pos + k] in every layer
+hipError_t launch_kv_trim(int dtype, const KvView& kv, int n_layers, int first_pos, int k, const int32_t* result,
+                          hipStream_t st);
+
+hipError_t launch_set_table(int32_t* table, int first, const int32_t* entries, int n, hipStream_t st);
+
+}  // namespace pipesd

@@ -1,0 +1,261 @@
+"""Thin ctypes binding over the C-ABI library (include/pipesd.h): argument marshalling only.
+
+Importing this module loads paper_2605_13319_amd/libpipesd.so and fails loudly if it has not been
+built (run `python __graft_entry__.py`) or lacks a declared entry point.  PyTorch is used for
+device memory and streams; every step of the NAV pass runs in the library's HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch  # first: the library must bind to the HIP runtime PyTorch has already loaded, not a second one
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpipesd.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python __graft_entry__.py` "
+                      "(there is no CPU fallback for the NAV pass)")
+_lib = C.CDLL(LIB_PATH)
+
+OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
+MAX_ROWS = 32
+PROF = dict(off=0, qkv=1, o=2, gateup=3, down=4, lmhead=5, attn=6, verify=7, all_gemm=8)
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "ffn_norm", "wq", "wk", "wv", "wo",
+                                                      "w_gate", "w_up", "w_down")]
+
+
+_i32p, _f32p = C.POINTER(C.c_int32), C.POINTER(C.c_float)
+_SIGS = {
+    "pipesd_model_create": (C.c_int, [C.POINTER(Config), C.POINTER(Weights), C.POINTER(C.c_void_p)]),
+    "pipesd_model_destroy": (C.c_int, [C.c_void_p]),
+    "pipesd_kv_block_bytes": (C.c_size_t, [C.c_void_p, C.c_int32]),
+    "pipesd_kv_create": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]),
+    "pipesd_kv_destroy": (C.c_int, [C.c_void_p]),
+    "pipesd_seq_reset": (C.c_int, [C.c_void_p, C.c_int32]),
+    "pipesd_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_void_p]),
+    "pipesd_nav_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_int32, C.c_void_p,
+                                    _f32p, _i32p, _i32p, C.c_void_p]),
+    "pipesd_kv_rollback": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "pipesd_kv_len": (C.c_int, [C.c_void_p, C.c_int32, _i32p]),
+    "pipesd_kv_free_blocks": (C.c_int, [C.c_void_p, _i32p]),
+    "pipesd_kv_seq_blocks": (C.c_int, [C.c_void_p, C.c_int32, _i32p]),
+    "pipesd_forward_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, _f32p, C.c_void_p]),
+    "pipesd_spec_accept": (C.c_int, [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_int32, _f32p, _i32p, _i32p,
+                                     C.c_void_p]),
+    "pipesd_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p]),
+    "pipesd_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
+    "pipesd_profile_read": (C.c_int, [C.c_void_p, _i32p, C.POINTER(C.c_double)]),
+    "pipesd_strerror": (C.c_char_p, [C.c_int]),
+    "pipesd_last_hip_error": (C.c_char_p, []),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)  # AttributeError = the library lacks a declared entry point
+    _fn.restype, _fn.argtypes = _res, _args
+EXPORTS = tuple(_SIGS)
+
+
+class PipesdError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = f" [{_lib.pipesd_last_hip_error().decode()}]" if status == EHIP else ""
+        super().__init__(f"{where}: {_lib.pipesd_strerror(status).decode()} ({status}){detail}")
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise PipesdError(status, where)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a: Optional[np.ndarray], typ):
+    return None if a is None else a.ctypes.data_as(typ)
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def config_of(shape) -> Config:
+    return Config(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                  shape.vocab, shape.rms_eps, shape.rope_base, shape.dtype)
+
+
+class Model:
+    """Target model handle.  `weights` maps names to numpy arrays (float32, or uint16 bf16 bits) as
+    produced by inputs.make_weights; None gives a shape-only handle (no GPU needed)."""
+
+    def __init__(self, shape, weights: Optional[Dict[str, object]] = None, device: str = "cuda:0"):
+        self.shape = shape
+        self.handle = C.c_void_p()
+        cfg = config_of(shape)
+        if weights is None:
+            _check(_lib.pipesd_model_create(C.byref(cfg), None, C.byref(self.handle)), "pipesd_model_create")
+            return
+        torch.cuda.set_device(device)
+        keep = []
+
+        def up(a: np.ndarray) -> int:
+            t = torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(device)
+            keep.append(t)
+            return t.data_ptr()
+
+        w = Weights()
+        w.tok_emb, w.final_norm, w.lm_head = up(weights["tok_emb"]), up(weights["final_norm"]), up(weights["lm_head"])
+        arrays = []
+        for name in ("attn_norm", "ffn_norm", "wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            arr = (C.c_void_p * shape.n_layers)(*[up(a) for a in weights[name]])
+            arrays.append(arr)
+            setattr(w, name, arr)
+        torch.cuda.synchronize()
+        _check(_lib.pipesd_model_create(C.byref(cfg), C.byref(w), C.byref(self.handle)), "pipesd_model_create")
+        del keep  # the library holds its own re-tiled copies
+
+    def close(self) -> None:
+        if self.handle:
+            _lib.pipesd_model_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def profile_select(self, which: str) -> None:
+        _check(_lib.pipesd_profile_select(self.handle, PROF[which]), "pipesd_profile_select")
+
+    def profile_read(self):
+        n, ms = C.c_int32(), C.c_double()
+        _check(_lib.pipesd_profile_read(self.handle, C.byref(n), C.byref(ms)), "pipesd_profile_read")
+        return n.value, ms.value
+
+
+class KVCache:
+    """Paged KV cache over a torch-allocated device pool (or bookkeeping only when the model is
+    shape-only)."""
+
+    def __init__(self, model: Model, max_seqs: int, n_blocks: int, block_tokens: int = 16,
+                 device: str = "cuda:0", on_device: Optional[bool] = None):
+        self.model = model
+        self.handle = C.c_void_p()
+        bb = _lib.pipesd_kv_block_bytes(model.handle, block_tokens)
+        if bb == 0:
+            raise PipesdError(EINVAL, "pipesd_kv_block_bytes")
+        self.block_bytes = bb
+        self.pool = None
+        pool_ptr = None
+        if on_device is None:
+            on_device = True
+        if on_device:
+            self.pool = torch.zeros(n_blocks * bb, dtype=torch.uint8, device=device)
+            pool_ptr = self.pool.data_ptr()
+        _check(_lib.pipesd_kv_create(model.handle, max_seqs, block_tokens, pool_ptr, n_blocks * bb,
+                                     C.byref(self.handle)), "pipesd_kv_create")
+
+    def close(self) -> None:
+        if self.handle:
+            _lib.pipesd_kv_destroy(self.handle)
+            self.handle = C.c_void_p()
+            self.pool = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self, seq: int) -> None:
+        _check(_lib.pipesd_seq_reset(self.handle, seq), "pipesd_seq_reset")
+
+    def prefill(self, seq: int, tokens: Sequence[int]) -> None:
+        t = _i32(tokens)
+        _check(_lib.pipesd_prefill(self.model.handle, self.handle, seq, _ptr(t, _i32p), len(t), _stream()),
+               "pipesd_prefill")
+
+    def nav_verify(self, seq: int, drafts: Sequence[int], draft_probs=None, uniforms=None,
+                   prefix_len: Optional[int] = None):
+        """draft_probs: torch CUDA float32 tensor [k][V], or numpy (uploaded), or None (token matching)."""
+        d = _i32(drafts)
+        k = len(d)
+        qptr, keep = None, None
+        if draft_probs is not None:
+            if isinstance(draft_probs, np.ndarray):
+                keep = torch.from_numpy(_f32(draft_probs)).cuda()
+            else:
+                keep = draft_probs.contiguous()
+            assert keep.dtype == torch.float32 and keep.numel() == k * self.model.shape.vocab
+            qptr = keep.data_ptr()
+        u = None if uniforms is None else _f32(uniforms)
+        if prefix_len is None:
+            prefix_len = self.length(seq)
+        a, n = C.c_int32(-1), C.c_int32(-1)
+        _check(_lib.pipesd_nav_verify(self.model.handle, self.handle, seq, prefix_len, _ptr(d, _i32p), k, qptr,
+                                      _ptr(u, _f32p), C.byref(a), C.byref(n), _stream()), "pipesd_nav_verify")
+        return a.value, n.value
+
+    def rollback(self, seq: int, new_prefix_len: int) -> None:
+        _check(_lib.pipesd_kv_rollback(self.handle, seq, new_prefix_len), "pipesd_kv_rollback")
+
+    def length(self, seq: int) -> int:
+        n = C.c_int32()
+        _check(_lib.pipesd_kv_len(self.handle, seq, C.byref(n)), "pipesd_kv_len")
+        return n.value
+
+    def free_blocks(self) -> int:
+        n = C.c_int32()
+        _check(_lib.pipesd_kv_free_blocks(self.handle, C.byref(n)), "pipesd_kv_free_blocks")
+        return n.value
+
+    def seq_blocks(self, seq: int) -> int:
+        n = C.c_int32()
+        _check(_lib.pipesd_kv_seq_blocks(self.handle, seq, C.byref(n)), "pipesd_kv_seq_blocks")
+        return n.value
+
+    def forward_logits(self, seq: int, tokens: Sequence[int] = ()) -> np.ndarray:
+        t = _i32(tokens)
+        out = np.empty((len(t) + 1, self.model.shape.vocab), dtype=np.float32)
+        _check(_lib.pipesd_forward_logits(self.model.handle, self.handle, seq, _ptr(t, _i32p) if len(t) else None,
+                                          len(t), _ptr(out, _f32p), _stream()), "pipesd_forward_logits")
+        return out
+
+    def read_kv(self, seq: int, layer: int, pos: int):
+        s = self.model.shape
+        k = np.empty(s.n_kv_heads * s.head_dim, dtype=np.float32)
+        v = np.empty_like(k)
+        _check(_lib.pipesd_kv_read(self.model.handle, self.handle, seq, layer, pos, _ptr(k, _f32p), _ptr(v, _f32p)),
+               "pipesd_kv_read")
+        return k, v
+
+
+def spec_accept(p, q, drafts: Sequence[int], uniforms) -> tuple:
+    """Decision step alone on device tensors p [k+1][V], q [k][V] (torch CUDA float32)."""
+    d = _i32(drafts)
+    u = _f32(uniforms)
+    k = len(d)
+    vocab = p.shape[-1]
+    assert p.is_contiguous() and q.is_contiguous() and p.shape[0] == k + 1 and q.shape[0] == k
+    a, n = C.c_int32(-1), C.c_int32(-1)
+    _check(_lib.pipesd_spec_accept(p.data_ptr(), q.data_ptr(), _ptr(d, _i32p), k, vocab, _ptr(u, _f32p), C.byref(a),
+                                   C.byref(n), _stream()), "pipesd_spec_accept")
+    return a.value, n.value

@@ -1,0 +1,111 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared entry point, and
+rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_13319_amd import inputs as I
+from paper_2605_13319_amd import nav
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            txt = open(os.path.join(ROOT, "include", fn)).read()
+            txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+            names |= set(re.findall(r"\b(pipesd_[a-z0-9_]+)\s*\(", txt))
+    return names
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    decl = _declared()
+    assert len(decl) >= 15
+    lib = C.CDLL(nav.LIB_PATH)
+    for name in decl:
+        assert hasattr(lib, name), name
+    assert decl == set(nav.EXPORTS)
+
+
+def test_strerror():
+    for st in (0, -1, -2, -3, -4, -99):
+        assert isinstance(nav._lib.pipesd_strerror(st), bytes)
+
+
+def _create(shape, weights_ptr=None):
+    h = C.c_void_p()
+    cfg = nav.config_of(shape)
+    return nav._lib.pipesd_model_create(C.byref(cfg), weights_ptr, C.byref(h)), h
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_layers=0), dict(n_q_heads=6, n_kv_heads=4), dict(head_dim=63), dict(head_dim=256, n_q_heads=2, n_kv_heads=2),
+    dict(d_model=1000), dict(d_ffn=1000), dict(vocab=0), dict(dtype=7), dict(rope_base=0.0)])
+def test_model_create_rejects_bad_shapes(bad):
+    import dataclasses
+    shape = dataclasses.replace(I.LLAMA_1B, **bad)
+    rc, _ = _create(shape)
+    assert rc == nav.EINVAL
+
+
+def test_null_arguments():
+    assert nav._lib.pipesd_model_create(None, None, None) == nav.EINVAL
+    assert nav._lib.pipesd_model_destroy(None) == nav.EINVAL
+    assert nav._lib.pipesd_kv_destroy(None) == nav.EINVAL
+    assert nav._lib.pipesd_kv_block_bytes(None, 16) == 0
+    n = C.c_int32()
+    assert nav._lib.pipesd_kv_len(None, 0, C.byref(n)) == nav.EINVAL
+
+
+def test_shape_only_handles_do_bookkeeping_but_refuse_compute():
+    m = nav.Model(I.LLAMA_8B, None)
+    assert nav._lib.pipesd_kv_block_bytes(m.handle, 16) == 32 * 2 * 8 * 128 * 16 * 2
+    assert nav._lib.pipesd_kv_block_bytes(m.handle, 32) == 0
+    kv = nav.KVCache(m, max_seqs=4, n_blocks=100, on_device=False)
+    assert kv.free_blocks() == 100 and kv.length(3) == 0 and kv.seq_blocks(0) == 0
+    with pytest.raises(nav.PipesdError) as e:
+        kv.length(4)
+    assert e.value.status == nav.EINVAL
+    with pytest.raises(nav.PipesdError) as e:
+        kv.rollback(0, 1)
+    assert e.value.status == nav.ESTATE
+    import numpy as np
+    toks = np.arange(5, dtype=np.int32)
+    rc = nav._lib.pipesd_prefill(m.handle, kv.handle, 0, toks.ctypes.data_as(nav._i32p), 5, None)
+    assert rc == nav.ESTATE
+    a, nx = C.c_int32(), C.c_int32()
+    rc = nav._lib.pipesd_nav_verify(m.handle, kv.handle, 0, 5, toks.ctypes.data_as(nav._i32p), 4, None, None,
+                                    C.byref(a), C.byref(nx), None)
+    assert rc == nav.ESTATE
+    # argument checks come first
+    rc = nav._lib.pipesd_nav_verify(m.handle, kv.handle, 0, 5, toks.ctypes.data_as(nav._i32p), 0, None, None,
+                                    C.byref(a), C.byref(nx), None)
+    assert rc == nav.EINVAL
+    rc = nav._lib.pipesd_nav_verify(m.handle, kv.handle, 0, 5, toks.ctypes.data_as(nav._i32p), 32, None, None,
+                                    C.byref(a), C.byref(nx), None)
+    assert rc == nav.EINVAL
+    bad = np.array([1, 2, I.LLAMA_8B.vocab], dtype=np.int32)
+    rc = nav._lib.pipesd_nav_verify(m.handle, kv.handle, 0, 5, bad.ctypes.data_as(nav._i32p), 3, None, None,
+                                    C.byref(a), C.byref(nx), None)
+    assert rc == nav.EINVAL
+    assert kv.free_blocks() == 100
+    kv.close()
+    m.close()
+
+
+def test_kv_create_argument_checks():
+    m = nav.Model(I.TINY, None)
+    h = C.c_void_p()
+    bb = nav._lib.pipesd_kv_block_bytes(m.handle, 16)
+    assert bb == 2 * 2 * 4 * 64 * 16 * 4
+    assert nav._lib.pipesd_kv_create(m.handle, 0, 16, None, 10 * bb, C.byref(h)) == nav.EINVAL
+    assert nav._lib.pipesd_kv_create(m.handle, 1, 8, None, 10 * bb, C.byref(h)) == nav.EINVAL
+    assert nav._lib.pipesd_kv_create(m.handle, 1, 16, None, bb - 1, C.byref(h)) == nav.EINVAL
+    assert nav._lib.pipesd_kv_create(m.handle, 1, 16, C.c_void_p(0x1010), 10 * bb, C.byref(h)) == nav.EINVAL
+    # a device pool cannot be attached to a shape-only model
+    assert nav._lib.pipesd_kv_create(m.handle, 1, 16, C.c_void_p(0x1000), 10 * bb, C.byref(h)) == nav.ESTATE
+    m.close()

@@ -1,0 +1,168 @@
+"""GPU parity of the whole NAV pass against the CPU checker on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from oracle.transformer import softmax_rows
+from paper_2605_13319_amd import inputs as I
+from tests.helpers import decision_excused, drafts_from_oracle, oracle_side
+
+pytestmark = pytest.mark.gpu
+TOL_F32, TOL_BF16 = 1e-4, 2e-2
+
+
+@pytest.fixture(scope="module")
+def nav():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2605_13319_amd import nav as n
+    return n
+
+
+def _both(nav, shape, seed, prefix, n_blocks, max_len=None):
+    w = I.make_weights(shape, seed + I.SEED_WEIGHTS)
+    toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX)
+    oseq = oracle_side(shape, w, toks, max_len or prefix + 64)
+    model = nav.Model(shape, w)
+    kv = nav.KVCache(model, max_seqs=2, n_blocks=n_blocks)
+    kv.prefill(0, toks)
+    return oseq, model, kv
+
+
+def _check_pass(kv, oseq, d, q, u, tol):
+    lp = oseq.prefix_len
+    z_ref = oseq.forward_logits(d)
+    z = kv.forward_logits(0, d)
+    err = float(np.abs(z - z_ref).max())
+    assert err <= tol, f"logits max-abs {err} > {tol}"
+    assert kv.length(0) == lp
+    p_ref = softmax_rows(z_ref)
+    a_ref, n_ref = oseq.nav_verify(d, q, u)
+    a, n = kv.nav_verify(0, d, q, u)
+    if (a, n) != (a_ref, n_ref):
+        assert q is not None and a != a_ref and decision_excused(p_ref, q, d, u, a, a_ref), \
+            f"decision {(a, n)} vs checker {(a_ref, n_ref)}"
+        # bring the checker onto the GPU's branch so later rounds compare like with like
+        oseq.rollback(lp)
+        oseq.committed += [int(t) for t in d[:a]] + [n]
+        oseq.cached = lp + a
+    assert kv.length(0) == lp + a + 1
+    return err, a
+
+
+def test_tiny_fp32_config(nav):
+    """Config 'tiny': 2 layers, d 256, 4 heads x 64, FFN 1024, vocab 4096, fp32; prefix 128, k = 4,
+    q = softmax(2 N(0,1))."""
+    wl = I.WORKLOADS["tiny"]
+    shape, seed = wl["shape"], wl["seed"]
+    oseq, model, kv = _both(nav, shape, seed, wl["prefix"], n_blocks=16)
+    for r in range(4):
+        d, q = I.make_independent_drafts(wl["k"], shape.vocab, seed + I.SEED_NOISE + 10 * r,
+                                         seed + I.SEED_DRAFT_U + 10 * r)
+        u = I.make_uniforms(wl["k"] + 1, seed + I.SEED_VERIFY_U + 10 * r)
+        err, a = _check_pass(kv, oseq, d, q, u, TOL_F32)
+        print(f"round {r}: err {err:.2e} accepted {a}", flush=True)
+    # cache contents agree position by position (keys as stored, i.e. rotated)
+    for layer in (0, 1):
+        for pos in (0, 17, 126, oseq.cached - 1):
+            k_gpu, v_gpu = kv.read_kv(0, layer, pos)
+            np.testing.assert_allclose(k_gpu, oseq.K[layer][pos].reshape(-1), atol=1e-5)
+            np.testing.assert_allclose(v_gpu, oseq.V[layer][pos].reshape(-1), atol=1e-5)
+
+
+def test_tiny_fp32_token_matching_and_row_counts(nav):
+    wl = I.WORKLOADS["tiny"]
+    shape, seed = wl["shape"], wl["seed"]
+    oseq, model, kv = _both(nav, shape, seed, 33, n_blocks=16)
+    for k in (1, 2, 7, 16, 31):
+        z = oseq.forward_logits([])
+        d = [int(np.argmax(z[0]))]
+        while len(d) < k:  # the checker's own argmax continuation, broken at a random place
+            d.append(int(np.argmax(oseq.forward_logits(d)[-1])))
+        d = np.array(d, dtype=np.int32)
+        if k > 2:
+            d[k // 2] = (d[k // 2] + 1) % shape.vocab
+        err, a = _check_pass(kv, oseq, d, None, None, TOL_F32)
+        assert a == (k // 2 if k > 2 else k)
+        oseq.rollback(33)
+        kv.rollback(0, 33)
+
+
+SMALL_BF16 = I.ModelShape("small-bf16", 3, 512, 8, 2, 64, 1024, 2048)
+SMALL_MHA = I.ModelShape("small-mha", 2, 1024, 8, 8, 128, 1536, 1000, rope_base=500000.0)
+
+
+@pytest.mark.parametrize("shape,prefix,ks", [(SMALL_BF16, 70, (8, 1, 16, 4, 31)), (SMALL_MHA, 45, (3, 17, 15))])
+def test_small_bf16_models(nav, shape, prefix, ks):
+    """Several tiles, ragged vocab (1000 = 62.5 tiles), both row variants (m <= 16 and m > 16)."""
+    oseq, model, kv = _both(nav, shape, 4242, prefix, n_blocks=24, max_len=prefix + 200)
+    for r, k in enumerate(ks):
+        d, q = drafts_from_oracle(oseq, k, 0.5, 4300 + r, 4400 + r)
+        u = I.make_uniforms(k + 1, 4500 + r)
+        err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
+        print(f"{shape.name} k={k}: err {err:.2e} accepted {a}", flush=True)
+    # the bf16 cache holds the same values as the checker's, up to rare one-step rounding flips
+    bad = 0
+    for layer in range(shape.n_layers):
+        for pos in range(0, oseq.cached, 7):
+            k_gpu, v_gpu = kv.read_kv(0, layer, pos)
+            bad += int((np.abs(k_gpu - oseq.K[layer][pos].reshape(-1)) > 0).sum())
+            bad += int((np.abs(v_gpu - oseq.V[layer][pos].reshape(-1)) > 0).sum())
+            np.testing.assert_allclose(k_gpu, oseq.K[layer][pos].reshape(-1), rtol=2 ** -6, atol=3e-4)
+            np.testing.assert_allclose(v_gpu, oseq.V[layer][pos].reshape(-1), rtol=2 ** -6, atol=3e-4)
+    print("cache entries off by one bf16 step:", bad, flush=True)
+
+
+def test_rollback_reproduces_and_matches_fresh_prefill(nav):
+    shape = SMALL_BF16
+    oseq, model, kv = _both(nav, shape, 5151, 40, n_blocks=24, max_len=300)
+    d, q = drafts_from_oracle(oseq, 6, 0.5, 1, 2)
+    u = I.make_uniforms(7, 3)
+    free0, blocks0 = kv.free_blocks(), kv.seq_blocks(0)
+    z1 = kv.forward_logits(0, d)
+    assert (kv.free_blocks(), kv.seq_blocks(0)) == (free0, blocks0)
+    r1 = kv.nav_verify(0, d, q, u)
+    assert kv.length(0) == 40 + r1[0] + 1
+    assert kv.seq_blocks(0) == (40 + r1[0] + 15) // 16
+    kv.rollback(0, 40)
+    assert (kv.free_blocks(), kv.seq_blocks(0)) == (free0, blocks0)
+    z2 = kv.forward_logits(0, d)
+    r2 = kv.nav_verify(0, d, q, u)
+    np.testing.assert_array_equal(z1, z2)  # bit-for-bit
+    assert r1 == r2
+    # rejected rows are cleared in place, kept rows are not
+    a = r1[0]
+    if a < 6:
+        kv2, vv2 = kv.read_kv(0, 1, 39 + 6) if (39 + 6) // 16 < kv.seq_blocks(0) else (np.zeros(1), np.zeros(1))
+        assert not kv2.any() and not vv2.any()
+    kk, vv = kv.read_kv(0, 1, 39 + a)
+    assert kk.any() and vv.any()
+    # compare against a second sequence prefilled with the committed text
+    text = list(I.make_tokens(40, shape.vocab, 5151 + I.SEED_PREFIX)) + [int(t) for t in d[:a]] + [r1[1]]
+    kv.prefill(1, text)
+    probe = I.make_tokens(5, shape.vocab, 9)
+    za, zb = kv.forward_logits(0, probe), kv.forward_logits(1, probe)
+    assert float(np.abs(za - zb).max()) < 2e-3
+    # state errors leave everything untouched
+    with pytest.raises(nav.PipesdError) as e:
+        kv.nav_verify(0, d, q, u, prefix_len=40)
+    assert e.value.status == nav.ESTATE
+    with pytest.raises(nav.PipesdError) as e:
+        kv.rollback(0, kv.length(0) + 1)
+    assert e.value.status == nav.ESTATE
+    assert kv.length(0) == 40 + a + 1
+
+
+def test_pool_exhaustion_changes_nothing(nav):
+    shape = SMALL_BF16
+    w = I.make_weights(shape, 1)
+    model = nav.Model(shape, w)
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=3)
+    kv.prefill(0, I.make_tokens(40, shape.vocab, 2))  # 39 rows -> 3 blocks
+    assert kv.free_blocks() == 0
+    d = I.make_tokens(12, shape.vocab, 3)             # rows up to 39 + 13 = 52 > 48
+    with pytest.raises(nav.PipesdError) as e:
+        kv.nav_verify(0, d)
+    assert e.value.status == nav.ENOMEM
+    assert kv.length(0) == 40 and kv.seq_blocks(0) == 3
+    a, n = kv.nav_verify(0, d[:8])                    # 39 + 9 = 48 fits
+    assert 0 <= a <= 8
