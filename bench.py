@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the NAV pass on one MI355X.
+
+A step = one whole pass of the hot path for one client: forward of [pending, d_1..d_k] over the
+paged KV cache, softmax, accept tests, corrected/extra-token draw, KV trim, then the host-side
+rollback to the starting prefix so every step does identical work.  Inputs (weights, prefilled
+cache, draft distributions) are resident in HBM before the timed region.
+
+Prints ONE JSON line: verified tokens/s (k / t_pass), ms per pass, the algorithmic HBM rate of the
+whole pass, a `roofline` object for the weight-streaming GEMM kernel measured with HIP events in
+the timed region, and a `cpu_baseline` object: the CPU checker timed on this host on a
+layer-truncated sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(shape, weights, prefix, k, layers):
+    """The checker's verify pass (k + 1 rows over an already-cached prefix + decision) on a model
+    truncated to `layers` layers; layer time is scaled to the full depth, head time added once."""
+    import numpy as np
+    from oracle.nav import OracleSeq
+    from oracle.spec_sampling import spec_accept
+    from oracle.transformer import OracleModel, softmax_rows
+    from paper_2605_13319_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    small = shape.truncated(layers)
+    w = dict(weights)
+    for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "attn_norm", "ffn_norm"):
+        w[name] = weights[name][:layers]
+    om = OracleModel(small, w)
+    seq = OracleSeq(om, prefix + k + 1)
+    rng = np.random.default_rng(1)
+    for l in range(layers):  # timing does not depend on the cached values
+        seq.K[l][:prefix - 1] = rng.standard_normal(seq.K[l][:prefix - 1].shape, dtype=np.float32)
+        seq.V[l][:prefix - 1] = rng.standard_normal(seq.V[l][:prefix - 1].shape, dtype=np.float32)
+    seq.committed = [0] * prefix
+    seq.cached = prefix - 1
+    d, q = I.make_independent_drafts(k, shape.vocab, 11, 12, scale=1.0)
+    u = I.make_uniforms(k + 1, 13)
+    # layers-only time: same model without the head is not expressible in the checker, so time the
+    # full truncated pass and a 0-layer pass (embedding + head + decision) and subtract
+    head = OracleModel(shape.truncated(0), w)
+    hseq = OracleSeq(head, 4)
+    hseq.committed = [0]
+
+    def timed(fn, reps):
+        ts = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            fn()
+            ts.append(time.perf_counter() - t0)
+        return sorted(ts)[len(ts) // 2]
+
+    def full():
+        z = seq.forward_logits(d)
+        spec_accept(softmax_rows(z), q, d, u)
+
+    def head_only():
+        z = hseq.forward_logits(d)
+        spec_accept(softmax_rows(z), q, d, u)
+
+    t_full = timed(full, 3)
+    t_head = timed(head_only, 3)
+    t_layer = max(t_full - t_head, 0.0) / layers
+    t_pass = t_layer * shape.n_layers + t_head
+    return {"value": k / t_pass, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "ms_per_pass": t_pass * 1e3,
+            "sample": f"{layers}-layer truncation of {shape.name} (full width, vocab, ctx {prefix}, k={k}); "
+                      f"per-layer time x {shape.n_layers} + head/decision time; median of 3"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama-8b")
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--prefix", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="truncate the model (debugging; not the headline)")
+    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prof", default="all_gemm", help="kernel class bracketed by HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the NAV pass on ONE GPU; --gpus N with N > 1 is not supported")
+
+    import numpy as np
+    import torch
+    from paper_2605_13319_amd import inputs as I
+    from paper_2605_13319_amd import nav
+
+    wl = I.WORKLOADS[args.workload]
+    shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
+    k = args.k or wl["k"]
+    prefix = args.prefix or wl["prefix"]
+    seed = wl["seed"]
+    sigma = wl["sigma"]
+
+    t0 = time.time()
+    weights = I.make_weights(shape, seed + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+    log(f"[bench] weights for {shape.name} drawn in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    model = nav.Model(shape, weights)
+    n_blocks = (prefix + nav.MAX_ROWS + 15) // 16 + 2
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=n_blocks)
+    toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX)
+    kv.prefill(0, toks)
+    torch.cuda.synchronize()
+    log(f"[bench] model on device and {prefix}-token prefix cached in {time.time() - t0:.1f}s")
+
+    # drafts: q_i = softmax(target logits + sigma N(0,1)), d_i ~ q_i (fp32 model: independent drafts)
+    if sigma is None:
+        d, q = I.make_independent_drafts(k, shape.vocab, seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U)
+    else:
+        d, q = I.make_noisy_target_drafts(lambda ds: kv.forward_logits(0, ds)[-1], k, shape.vocab, sigma,
+                                          seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U)
+    q_dev = torch.from_numpy(q).cuda()
+    u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U)
+
+    def step():
+        a, n = kv.nav_verify(0, d, q_dev, u)
+        kv.rollback(0, prefix)
+        return a, n
+
+    for _ in range(args.warmup):
+        first = step()
+    torch.cuda.synchronize()
+    model.profile_select(args.prof)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = step()
+        assert res == first, "the pass is not reproducible"
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_launch, kern_ms = model.profile_read()
+    model.profile_select("off")
+    # the same steps without event bracketing, to show what the events cost
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed_plain = time.perf_counter() - t1
+
+    t_pass = min(elapsed, elapsed_plain) / args.steps
+    alg_bytes = shape.algorithmic_bytes(prefix, k)
+    esz = 4 if shape.dtype == I.DTYPE_F32 else 2
+    gemm_bytes = shape.n_params_streamed() * esz  # what the GEMM launches of one pass must read
+    launches_per_pass = n_launch / args.steps if args.steps else 0
+    roof = None
+    if n_launch:
+        per_launch_bytes = gemm_bytes / launches_per_pass
+        avg_ms = kern_ms / n_launch
+        achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "kernel": "gemm_bf16_kernel (all weight-streaming GEMMs of the pass)" if esz == 2 else "gemm_f32_kernel",
+                "launches_per_pass": launches_per_pass, "avg_launch_us": avg_ms * 1e3,
+                "algorithmic_bytes_per_launch": per_launch_bytes}
+
+    out = {
+        "metric": "verified_tokens_per_sec", "value": k / t_pass, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_pass * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
+        "config": {"workload": f"{shape.name}: NAV pass, prefix {prefix}, k={k}, batch 1, paged KV (16-token blocks)",
+                   "rows_per_pass": k + 1, "accepted_len": first[0]},
+        "committed_tokens_per_sec": (first[0] + 1) / t_pass,
+        "hbm_algorithmic_gbps": alg_bytes / t_pass / 1e9, "hbm_frac_of_peak": alg_bytes / t_pass / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_pass": alg_bytes,
+        "ms_per_step_with_events": elapsed / args.steps * 1e3, "ms_per_step_plain": elapsed_plain / args.steps * 1e3,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(wl["shape"], weights, prefix, k, min(args.cpu_layers, shape.n_layers))
+        log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

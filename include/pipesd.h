@@ -85,8 +85,8 @@ typedef struct pipesd_kv pipesd_kv;
  * weights == NULL creates a shape-only handle without device memory (for planning KV pools and
  * exercising the bookkeeping without a GPU); compute calls on it return PIPESD_ESTATE.
  * EINVAL: null cfg/out, non-positive sizes, n_q_heads not a multiple of n_kv_heads, odd head_dim,
- * head_dim > 256, or (bf16) d_model, n_q_heads*head_dim or d_ffn not a multiple of 512 or
- * head_dim not a multiple of 16. */
+ * head_dim > 128, or (bf16) d_model, n_q_heads*head_dim or d_ffn not a multiple of 512 or
+ * head_dim other than 64 or 128. */
 int pipesd_model_create(const pipesd_config *cfg, const pipesd_weights *weights, pipesd_model **out);
 int pipesd_model_destroy(pipesd_model *model);
 

@@ -11,7 +11,6 @@
 using namespace pipesd;
 
 namespace pipesd {
-void gemm_scratch_need(int N, int K, int n_cu, size_t* partial_floats, size_t* ssq_floats, size_t* counters);
 int device_cu_count();
 }
 
@@ -48,8 +47,6 @@ struct pipesd_model {
   // activation workspace (rows x width, fp32)
   float *xres = nullptr, *hbuf = nullptr, *qkv = nullptr, *qbuf = nullptr, *attn_out = nullptr, *gu = nullptr,
         *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
-  float* gemm_partial = nullptr;
-  float* ssq_partial = nullptr;
   unsigned* counters = nullptr;
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
@@ -82,7 +79,6 @@ struct pipesd_kv {
 };
 
 static constexpr int kCounterSlots = 1 << 16;
-static constexpr int kAttnChunk = 32;
 
 static int dev_alloc(pipesd_model* m, void** p, size_t bytes) {
   if (hipMalloc(p, bytes ? bytes : 256) != hipSuccess) return PIPESD_ENOMEM;
@@ -99,7 +95,8 @@ static int check_config(const pipesd_config* c) {
   if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return PIPESD_EINVAL;
   if (c->dtype == PIPESD_BF16) {
     const int qd = c->n_q_heads * c->head_dim;
-    if (c->d_model % 512 || qd % 512 || c->d_ffn % 512 || c->head_dim % 16) return PIPESD_EINVAL;
+    if (c->d_model % 512 || qd % 512 || c->d_ffn % 512) return PIPESD_EINVAL;
+    if (c->head_dim != 64 && c->head_dim != 128) return PIPESD_EINVAL;
   } else {
     if (c->d_model % 4 || c->d_ffn % 4) return PIPESD_EINVAL;
   }
@@ -211,22 +208,7 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   if ((rc = dev_alloc(m, (void**)&m->result_dev, 4 * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->counters, (size_t)kCounterSlots * 4))) return rc;
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
-  if (c.dtype == PIPESD_BF16) {
-    const int n_cu = device_cu_count();
-    if (n_cu <= 0) return PIPESD_EHIP;
-    size_t pf = 0, sf = 0, cn = 0;
-    const int shapes[5][2] = {{nqkv, d}, {d, qd}, {2 * F, d}, {d, F}, {V, d}};
-    for (auto& sh : shapes) {
-      size_t a = 0, b = 0, cc = 0;
-      gemm_scratch_need(sh[0], sh[1], n_cu, &a, &b, &cc);
-      if (a > pf) pf = a;
-      if (b > sf) sf = b;
-      if (cc > cn) cn = cc;
-    }
-    if (cn >= (size_t)kCounterSlots - 1) return PIPESD_EINVAL;
-    if ((rc = dev_alloc(m, (void**)&m->gemm_partial, pf * 4))) return rc;
-    if ((rc = dev_alloc(m, (void**)&m->ssq_partial, sf * 4))) return rc;
-  }
+  if (c.dtype == PIPESD_BF16 && device_cu_count() <= 0) return PIPESD_EHIP;
   HIP_TRY(hipHostMalloc((void**)&m->result_host, 64, hipHostMallocDefault));
   HIP_TRY(hipDeviceSynchronize());
   return PIPESD_OK;
@@ -482,9 +464,6 @@ static GemmCall gemm_call(pipesd_model* m, const GemmPlan& p, const void* wp, co
   c.epi = epi;
   c.out = out;
   c.ldo = ldo;
-  c.partial = m->gemm_partial;
-  c.ssq_partial = m->ssq_partial;
-  c.counters = m->counters;
   c.rope_cs = m->rope_cs;
   return c;
 }
@@ -497,7 +476,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   const KvView view = view_of(kv, seq);
   RowTokens rt{};
   for (int r = 0; r < rows; ++r) rt.tok[r] = row_tokens[r];
-  const int nsplit = attn_nsplit(start_pos + rows, kAttnChunk);
+  const int chunk = attn_chunk_tokens(c.dtype);
+  const int nsplit = attn_nsplit(start_pos + rows, chunk);
   int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 2));
   if (rc) return rc;
   HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
@@ -511,7 +491,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     at.m = rows;
     at.start_pos = start_pos;
     at.n_q_heads = c.n_q_heads;
-    at.chunk = kAttnChunk;
+    at.chunk = chunk;
     at.part = m->attn_part;
     at.out = m->attn_out;
     if (c.dtype == PIPESD_F32) {

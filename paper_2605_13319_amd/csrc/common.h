@@ -73,7 +73,7 @@ enum PackMode { PACK_PLAIN = 0, PACK_HALVES = 1 };
 
 struct GemmPlan {  // launch shape of one GEMM, fixed when the model is created
   int K, N, ntiles;
-  int W, S, grid, tpr, nt;  // waves per workgroup, K splits, workgroups, n-tiles per range, reduce batch
+  int W, P, grid, tg;  // waves per workgroup, K phases per wave, workgroups, n-tiles per group
 };
 GemmPlan plan_gemm(int N, int K, int n_cu);
 
@@ -91,10 +91,6 @@ struct GemmCall {
   KvView kv;
   int layer, start_pos, n_q_heads;
   const float* rope_cs;
-  // split-K scratch
-  float* partial;
-  float* ssq_partial;
-  unsigned* counters;
 };
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st);
 
@@ -119,6 +115,7 @@ struct AttnCall {
   float* out;      // [m][n_q_heads*head_dim]
 };
 int attn_nsplit(int total_tokens, int chunk);
+int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type
 hipError_t launch_attention(const AttnCall& c, hipStream_t st);
 
 // ---- vocabulary-wide decision ----

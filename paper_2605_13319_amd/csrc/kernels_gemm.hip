@@ -10,10 +10,10 @@
 //    Each wave owns one K slice; its activation fragments stay in registers for the whole kernel,
 //    as a bf16 hi + lo pair so that no activation precision is lost (two MFMAs per weight fragment;
 //    the matrix cores idle otherwise).
-//  * A workgroup's W waves cover W consecutive K slices of the same n-tiles and add their 16x16
-//    partial tiles through LDS; if the GEMM is further split over S workgroups along K, the
-//    partial tiles go through a global scratch and the last workgroup to arrive adds them in a fixed
-//    order.  No floating-point atomics: results are bit-reproducible.
+//  * A workgroup's W waves cover W K slices of the same n-tiles at a time (and, for long K, P
+//    such phases one after the other, accumulators kept in registers) and add their 16x16 partial
+//    tiles through LDS in a fixed order.  Nothing crosses workgroups: no global partials, no
+//    device-scope fences, no floating-point atomics; results are bit-reproducible.
 //  * RMSNorm is fused: the kernel multiplies the activations by the gain on load, accumulates
 //    sum(x^2) of the raw activations on the way, and scales the finished tile by rstd per row.
 //  * Epilogues: plain store (logits), residual add, SiLU(gate)*up, or rotary + query buffer / paged
@@ -30,12 +30,9 @@ struct GemmArgs {
   const float* act;
   const float* gain;
   float* out;
-  float* partial;
-  float* ssq_partial;
-  unsigned* counters;
   const float* rope_cs;
   KvView kv;
-  int lda, m, K, N, ntiles, kst, W, S, tpr, nt, ldo, epi, layer, start_pos, n_q_heads;
+  int lda, m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
   float eps;
 };
 
@@ -104,37 +101,17 @@ __device__ __forceinline__ void epilogue_pair(const GemmArgs& a, int t, int wr, 
   }
 }
 
+// Loads this wave's activation fragments for K slice `slice` (KSTEPS k-steps of 32 columns): lane
+// (c = row, g = k-group) takes 8 consecutive fp32 values per k-step, multiplies by the norm gain if
+// one is fused, adds the raw squares to ssq, and splits into bf16 hi + lo.
 template <int MT, int KSTEPS>
-__global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
-  extern __shared__ float lds[];
-  // red[nt][W][MT][64] float4, then ssq[W][MT*16], then one flag
-  f32x4* red = (f32x4*)lds;
-  float* ssq_lds = lds + (size_t)a.nt * a.W * MT * 64 * 4;
-  int* flag = (int*)(ssq_lds + a.W * MT * 16);
-
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int c = lane & 15, g = lane >> 4;
-  const int s = blockIdx.x % a.S, ri = blockIdx.x / a.S;
-  const int k0 = (s * a.W + w) * KSTEPS * 32;
-  const int t_begin = ri * a.tpr, t_end = min(a.ntiles, t_begin + a.tpr);
-  const int nthreads = a.W * 64;
-
-  // the weight stream starts first: it does not depend on the activations
-  const u32x4* wlane = a.wp + (size_t)(k0 / 32) * 64 + lane;
-  u32x4 af[KSTEPS];
-  if (t_begin < t_end) {
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks)
-      af[ks] = __builtin_nontemporal_load(wlane + ((size_t)t_begin * a.kst + ks) * 64);
-  }
-
-  // activation fragments of this wave's K slice, kept for the whole kernel
-  bf16x8 bhi[MT][KSTEPS], blo[MT][KSTEPS];
-  float ssq[MT];
+__device__ __forceinline__ void load_act_frags(const GemmArgs& a, int slice, int c, int g, bf16x8 (&bhi)[MT][KSTEPS],
+                                               bf16x8 (&blo)[MT][KSTEPS], float (&ssq)[MT]) {
+  const int k0 = slice * KSTEPS * 32;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    ssq[mt] = 0.f;
     const int row = mt * 16 + c;
+    float part = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks) {
       const int kk = k0 + ks * 32 + g * 8;
@@ -153,172 +130,122 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
         const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          ssq[mt] = fmaf(v[i], v[i], ssq[mt]);
+          part = fmaf(v[i], v[i], part);
           v[i] *= gv[i];
         }
       }
       split_hi_lo(v, bhi[mt][ks], blo[mt][ks]);
     }
-    ssq[mt] += __shfl_xor(ssq[mt], 16, 64);
-    ssq[mt] += __shfl_xor(ssq[mt], 32, 64);
-    if (g == 0) ssq_lds[w * MT * 16 + mt * 16 + c] = ssq[mt];
+    part += __shfl_xor(part, 16, 64);
+    part += __shfl_xor(part, 32, 64);
+    ssq[mt] += part;
+  }
+}
+
+// Work decomposition: K is cut into W * P slices of KSTEPS*32 columns; wave w of a workgroup takes
+// slices p*W + w, p = 0..P-1, one phase after the other, for a group of tg n-tiles, keeping its
+// running 16x16 sums in its own LDS slots.  After the last phase the W waves' sums are added.  Groups are dealt to workgroups round-robin.  The weight stream of a wave is a
+// fixed sequence of 1 KB-per-instruction chunks and the next chunk is always requested while the
+// current one is multiplied, also across phase and group boundaries.
+template <int MT, int KSTEPS>
+__global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
+  extern __shared__ float lds[];
+  f32x4* red = (f32x4*)lds;                                     // [tg][W][MT][64]
+  float* ssq_lds = lds + (size_t)a.tg * a.W * MT * 64 * 4;      // [W][MT*16]
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int nthreads = a.W * 64;
+  const int ngroups = (a.ntiles + a.tg - 1) / a.tg;
+  int grp = blockIdx.x;
+  if (grp >= ngroups) return;
+
+  const u32x4* wlane = a.wp + lane;
+  auto chunk = [&](int tile, int p) { return wlane + ((size_t)tile * a.kst + (size_t)(p * a.W + w) * KSTEPS) * 64; };
+
+  // the weight stream starts first: it does not depend on the activations
+  u32x4 af[KSTEPS];
+  {
+    const u32x4* first = chunk(grp * a.tg, 0);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = __builtin_nontemporal_load(first + ks * 64);
   }
 
-  int nb = 0;
-  for (int t = t_begin; t < t_end; ++t) {
-    f32x4 acc[MT];
+  bf16x8 bhi[MT][KSTEPS], blo[MT][KSTEPS];
+  float ssq[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const bool more = t + 1 < t_end;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      const bf16x8 av = as_bf16x8(af[ks]);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[mt][ks], acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[mt][ks], acc[mt], 0, 0, 0);
-      }
-      if (more) af[ks] = __builtin_nontemporal_load(wlane + ((size_t)(t + 1) * a.kst + ks) * 64);
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) red[((size_t)(nb * a.W + w) * MT + mt) * 64 + lane] = acc[mt];
-    ++nb;
-    if (nb < a.nt && more) continue;
+  for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
+  if (a.P == 1) load_act_frags<MT, KSTEPS>(a, w, c, g, bhi, blo, ssq);
 
-    // ---- add the W partial tiles of this batch and finish (or hand over to the last arriver) ----
-    const int t_first = t - nb + 1;
-    const int npairs = nb * MT * 128;
-    const float inv_k = 1.0f / (float)a.K;
+  for (; grp < ngroups; grp += gridDim.x) {
+    const int t0 = grp * a.tg;
+    const int nt_g = min(a.tg, a.ntiles - t0);
+    if (a.P > 1) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
+    }
+    for (int p = 0; p < a.P; ++p) {
+      if (a.P > 1) load_act_frags<MT, KSTEPS>(a, p * a.W + w, c, g, bhi, blo, ssq);
+      for (int t = 0; t < nt_g; ++t) {
+        const u32x4* nxt = nullptr;
+        if (t + 1 < nt_g) nxt = chunk(t0 + t + 1, p);
+        else if (p + 1 < a.P) nxt = chunk(t0, p + 1);
+        else if (grp + (int)gridDim.x < ngroups) nxt = chunk((grp + (int)gridDim.x) * a.tg, 0);
+        f32x4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+          const bf16x8 av = as_bf16x8(af[ks]);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[mt][ks], acc[mt], 0, 0, 0);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[mt][ks], acc[mt], 0, 0, 0);
+          }
+          if (nxt != nullptr) af[ks] = __builtin_nontemporal_load(nxt + ks * 64);
+        }
+        // this wave's running sum over its phases lives in its own LDS slot
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          f32x4* slot = red + ((size_t)(t * a.W + w) * MT + mt) * 64 + lane;
+          *slot = (p == 0) ? acc[mt] : (*slot + acc[mt]);
+        }
+      }
+    }
+    if (a.gain != nullptr && g == 0) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) ssq_lds[w * MT * 16 + mt * 16 + c] = ssq[mt];
+    }
     __syncthreads();
-    if (a.S == 1) {
-      for (int e = tid; e < npairs; e += nthreads) {
-        const int tt = e / (MT * 128), rem = e % (MT * 128), mt = rem / 128, pr = rem % 128;
-        const int wr = pr >> 4, cc = pr & 15;
-        const int l0 = (wr >> 2) * 16 + cc, comp = wr & 3;
-        float v0 = 0.f, v1 = 0.f;
-        for (int ww = 0; ww < a.W; ++ww) {
-          const float* rp = (const float*)(red + ((size_t)(tt * a.W + ww) * MT + mt) * 64);
-          v0 += rp[l0 * 4 + comp];
-          v1 += rp[(l0 + 32) * 4 + comp];
-        }
-        float rstd = 1.0f;
-        if (a.gain != nullptr) {
-          float q = 0.f;
-          for (int ww = 0; ww < a.W; ++ww) q += ssq_lds[ww * MT * 16 + mt * 16 + cc];
-          rstd = 1.0f / sqrtf(q * inv_k + a.eps);
-        }
-        epilogue_pair(a, t_first + tt, wr, mt * 16 + cc, v0, v1, rstd);
+    // add the W partial tiles and finish each (row pair, activation row)
+    const int npairs = nt_g * MT * 128;
+    const float inv_k = 1.0f / (float)a.K;
+    for (int e = tid; e < npairs; e += nthreads) {
+      const int tt = e / (MT * 128), rem = e % (MT * 128), mt = rem / 128, pr = rem % 128;
+      const int wr = pr >> 4, cc = pr & 15;
+      const int l0 = (wr >> 2) * 16 + cc, comp = wr & 3;
+      float v0 = 0.f, v1 = 0.f;
+      for (int ww = 0; ww < a.W; ++ww) {
+        const float* rp = (const float*)(red + ((size_t)(tt * a.W + ww) * MT + mt) * 64);
+        v0 += rp[l0 * 4 + comp];
+        v1 += rp[(l0 + 32) * 4 + comp];
       }
-    } else {
-      const int bpr = (a.tpr + a.nt - 1) / a.nt;
-      const int cidx = ri * bpr + (t_first - t_begin) / a.nt;
-      for (int e = tid; e < npairs; e += nthreads) {
-        const int tt = e / (MT * 128), rem = e % (MT * 128), mt = rem / 128, pr = rem % 128;
-        const int wr = pr >> 4, cc = pr & 15;
-        const int l0 = (wr >> 2) * 16 + cc, comp = wr & 3;
-        float v0 = 0.f, v1 = 0.f;
-        for (int ww = 0; ww < a.W; ++ww) {
-          const float* rp = (const float*)(red + ((size_t)(tt * a.W + ww) * MT + mt) * 64);
-          v0 += rp[l0 * 4 + comp];
-          v1 += rp[(l0 + 32) * 4 + comp];
-        }
-        float2* dst = (float2*)(a.partial + ((((size_t)s * a.ntiles + t_first + tt) * MT + mt) * 128 + pr) * 2);
-        *dst = make_float2(v0, v1);
-      }
-      if (a.gain != nullptr && tid < MT * 16) {
+      float rstd = 1.0f;
+      if (a.gain != nullptr) {
         float q = 0.f;
-        for (int ww = 0; ww < a.W; ++ww) q += ssq_lds[ww * MT * 16 + tid];
-        a.ssq_partial[((size_t)cidx * a.S + s) * 32 + tid] = q;
+        for (int ww = 0; ww < a.W; ++ww) q += ssq_lds[ww * MT * 16 + mt * 16 + cc];
+        rstd = 1.0f / sqrtf(q * inv_k + a.eps);
       }
-      __threadfence();
-      __syncthreads();
-      if (tid == 0) {
-        const unsigned prev = atomicAdd(a.counters + cidx, 1u);
-        *flag = (prev == (unsigned)a.S - 1u) ? 1 : 0;
-      }
-      __syncthreads();
-      if (*flag) {
-        __threadfence();
-        for (int e = tid; e < npairs; e += nthreads) {
-          const int tt = e / (MT * 128), rem = e % (MT * 128), mt = rem / 128, pr = rem % 128;
-          const int wr = pr >> 4, cc = pr & 15;
-          float v0 = 0.f, v1 = 0.f;
-          for (int ss = 0; ss < a.S; ++ss) {
-            const float2 pv =
-                *(const float2*)(a.partial + ((((size_t)ss * a.ntiles + t_first + tt) * MT + mt) * 128 + pr) * 2);
-            v0 += pv.x;
-            v1 += pv.y;
-          }
-          float rstd = 1.0f;
-          if (a.gain != nullptr) {
-            float q = 0.f;
-            for (int ss = 0; ss < a.S; ++ss) q += a.ssq_partial[((size_t)cidx * a.S + ss) * 32 + mt * 16 + cc];
-            rstd = 1.0f / sqrtf(q * inv_k + a.eps);
-          }
-          epilogue_pair(a, t_first + tt, wr, mt * 16 + cc, v0, v1, rstd);
-        }
-        if (tid == 0) a.counters[cidx] = 0u;
-      }
+      epilogue_pair(a, t0 + tt, wr, mt * 16 + cc, v0, v1, rstd);
     }
     __syncthreads();  // red is free again
-    nb = 0;
   }
 }
 
 // ------------------------------------------------------------------------------------------------
 // launch shape
 // ------------------------------------------------------------------------------------------------
-static int slice_cols(int m) { return m <= 16 ? 512 : 256; }
-
-GemmPlan plan_gemm(int N, int K, int n_cu) {
-  // planned for the 16-row variant; launch_gemm_bf16 re-derives W and S for the 32-row variant
-  GemmPlan p{};
-  p.K = K;
-  p.N = N;
-  p.ntiles = (N + 15) / 16;
-  (void)n_cu;
-  return p;
-}
-
-static void shape_for(const GemmPlan& base, int m, int n_cu, GemmPlan& p) {
-  p = base;
-  const int nsl = base.K / slice_cols(m);
-  int W = 1;
-  for (int cand = 8; cand >= 1; --cand)
-    if (nsl % cand == 0) { W = cand; break; }
-  p.W = W;
-  p.S = nsl / W;
-  const int wg_per_cu = 8 / W > 0 ? 8 / W : 1;
-  int target = n_cu * wg_per_cu;
-  int nranges = target / p.S;
-  if (nranges < 1) nranges = 1;
-  if (nranges > p.ntiles) nranges = p.ntiles;
-  p.tpr = (p.ntiles + nranges - 1) / nranges;
-  nranges = (p.ntiles + p.tpr - 1) / p.tpr;
-  p.grid = nranges * p.S;
-  const int nt_max = m <= 16 ? 4 : 2;  // keeps the LDS reduce area under 64 KB
-  p.nt = p.tpr < nt_max ? p.tpr : nt_max;
-}
-
-// scratch one GEMM shape can need (both row variants): split-K partial tiles, per-batch sum-of-squares
-// partials, and arrival counters
-void gemm_scratch_need(int N, int K, int n_cu, size_t* partial_floats, size_t* ssq_floats, size_t* counters) {
-  *partial_floats = *ssq_floats = *counters = 0;
-  for (int m : {16, 32}) {
-    GemmPlan base{}, p{};
-    base.K = K;
-    base.N = N;
-    base.ntiles = (N + 15) / 16;
-    shape_for(base, m, n_cu, p);
-    const int mt = m <= 16 ? 1 : 2;
-    const size_t nranges = p.grid / p.S, bpr = (p.tpr + p.nt - 1) / p.nt;
-    const size_t pf = p.S > 1 ? (size_t)p.S * p.ntiles * mt * 256 : 0;
-    const size_t cn = p.S > 1 ? nranges * bpr : 0;
-    if (pf > *partial_floats) *partial_floats = pf;
-    if (cn > *counters) *counters = cn;
-    if (cn * p.S * 32 > *ssq_floats) *ssq_floats = cn * p.S * 32;
-  }
-}
+constexpr int kTmax16 = 7, kTmax32 = 3;  // n-tiles per group at W = 8 (the LDS reduce area stays under 64 KB)
 
 int device_cu_count() {
   static int n_cu = 0;
@@ -331,10 +258,43 @@ int device_cu_count() {
   return n_cu;
 }
 
+GemmPlan plan_gemm(int N, int K, int n_cu) {
+  GemmPlan p{};
+  p.K = K;
+  p.N = N;
+  p.ntiles = (N + 15) / 16;
+  (void)n_cu;
+  return p;
+}
+
+static void shape_for(const GemmPlan& base, int m, int n_cu, GemmPlan& p) {
+  p = base;
+  const int slices = base.K / (m <= 16 ? 512 : 256);
+  int W = 1;
+  for (int cand = 8; cand >= 1; --cand)
+    if (slices % cand == 0) { W = cand; break; }
+  p.W = W;
+  p.P = slices / W;
+  const int slots = n_cu * (8 / W > 0 ? 8 / W : 1);
+  const int tmax = (m <= 16 ? kTmax16 : kTmax32) * 8 / W;
+  int best_tg = 1;
+  long best_cost = -1;
+  for (int tg = 1; tg <= tmax; ++tg) {
+    const int groups = (p.ntiles + tg - 1) / tg;
+    const long rounds = (groups + slots - 1) / slots;
+    const long cost = rounds * tg;
+    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best_tg = tg; }
+  }
+  p.tg = best_tg;
+  const int groups = (p.ntiles + p.tg - 1) / p.tg;
+  p.grid = groups < slots ? groups : slots;
+}
+
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   const int n_cu = device_cu_count();
   if (n_cu <= 0) return hipErrorUnknown;
-  if (c.m < 1 || c.m > kMaxRows || c.plan.K % slice_cols(c.m) != 0 || (c.lda & 3) != 0) return hipErrorInvalidValue;
+  const int slice = c.m <= 16 ? 512 : 256;
+  if (c.m < 1 || c.m > kMaxRows || c.plan.K % slice != 0 || (c.lda & 3) != 0) return hipErrorInvalidValue;
   GemmPlan p;
   shape_for(c.plan, c.m, n_cu, p);
   GemmArgs a{};
@@ -342,9 +302,6 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.act = c.act;
   a.gain = c.gain;
   a.out = c.out;
-  a.partial = c.partial;
-  a.ssq_partial = c.ssq_partial;
-  a.counters = c.counters;
   a.rope_cs = c.rope_cs;
   a.kv = c.kv;
   a.lda = c.lda;
@@ -354,9 +311,8 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.ntiles = p.ntiles;
   a.kst = p.K / 32;
   a.W = p.W;
-  a.S = p.S;
-  a.tpr = p.tpr;
-  a.nt = p.nt;
+  a.P = p.P;
+  a.tg = p.tg;
   a.ldo = c.ldo;
   a.epi = c.epi;
   a.layer = c.layer;
@@ -364,7 +320,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.n_q_heads = c.n_q_heads;
   a.eps = c.eps;
   const int mt = c.m <= 16 ? 1 : 2;
-  const size_t lds = ((size_t)p.nt * p.W * mt * 64 * 4 + (size_t)p.W * mt * 16 + 4) * sizeof(float);
+  const size_t lds = ((size_t)p.tg * p.W * mt * 64 * 4 + (size_t)p.W * mt * 16) * sizeof(float);
   if (mt == 1)
     gemm_bf16_kernel<1, 16><<<p.grid, p.W * 64, lds, st>>>(a);
   else
