@@ -42,12 +42,14 @@ struct pipesd_model {
   void* lm_head = nullptr;
   std::vector<float*> attn_norm, ffn_norm;
   std::vector<void*> wqkv, wo, wgu, wdown;  // fp32: row-major stacks; bf16: matrix-core tiles
-  GemmPlan p_qkv{}, p_o{}, p_gu{}, p_down{}, p_lm{};
   double* theta = nullptr;
   // activation workspace (rows x width, fp32)
   float *xres = nullptr, *hbuf = nullptr, *qkv = nullptr, *qbuf = nullptr, *attn_out = nullptr, *gu = nullptr,
         *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
   unsigned* counters = nullptr;
+  void *xpk = nullptr, *apk = nullptr, *gpk = nullptr;  // packed activations feeding the bf16 GEMMs
+  float* ssq = nullptr;                                  // [rows][ssq_stride] partial sums of x^2
+  int ssq_stride = 0;
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
   float* row_stats = nullptr;
@@ -181,12 +183,6 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
       HIP_TRY(launch_pack_bf16(pd, 1, F, PACK_PLAIN, 0, m->wdown[l], d / 16, nullptr));
     }
   }
-  m->p_qkv = plan_gemm(nqkv, d, 0);
-  m->p_o = plan_gemm(d, qd, 0);
-  m->p_gu = plan_gemm(2 * F, d, 0);
-  m->p_down = plan_gemm(d, F, 0);
-  m->p_lm = plan_gemm(V, d, 0);
-
   // rotary frequencies theta_i = base^(-2i/h), fp64
   std::vector<double> th(c.head_dim / 2);
   for (int i = 0; i < c.head_dim / 2; ++i) th[i] = pow((double)c.rope_base, -2.0 * i / c.head_dim);
@@ -208,7 +204,17 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   if ((rc = dev_alloc(m, (void**)&m->result_dev, 4 * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->counters, (size_t)kCounterSlots * 4))) return rc;
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
-  if (c.dtype == PIPESD_BF16 && device_cu_count() <= 0) return PIPESD_EHIP;
+  if (c.dtype == PIPESD_BF16) {
+    if (device_cu_count() <= 0) return PIPESD_EHIP;
+    if ((rc = dev_alloc(m, &m->xpk, act_pack_bytes(d)))) return rc;
+    if ((rc = dev_alloc(m, &m->apk, act_pack_bytes(qd)))) return rc;
+    if ((rc = dev_alloc(m, &m->gpk, act_pack_bytes(F)))) return rc;
+    HIP_TRY(hipMemset(m->xpk, 0, act_pack_bytes(d)));
+    HIP_TRY(hipMemset(m->apk, 0, act_pack_bytes(qd)));
+    HIP_TRY(hipMemset(m->gpk, 0, act_pack_bytes(F)));
+    m->ssq_stride = d / 16;
+    if ((rc = dev_alloc(m, (void**)&m->ssq, R * m->ssq_stride * 4))) return rc;
+  }
   HIP_TRY(hipHostMalloc((void**)&m->result_host, 64, hipHostMallocDefault));
   HIP_TRY(hipDeviceSynchronize());
   return PIPESD_OK;
@@ -451,19 +457,19 @@ static int ensure_attn_scratch(pipesd_model* m, size_t floats) {
   return PIPESD_OK;
 }
 
-static GemmCall gemm_call(pipesd_model* m, const GemmPlan& p, const void* wp, const float* act, int lda, int rows,
-                          const float* gain, int epi, float* out, int ldo) {
+static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int rows, const void* actp, bool norm,
+                          int norm_parts, int epi) {
   GemmCall c{};
-  c.plan = p;
   c.wp = wp;
-  c.act = act;
-  c.lda = lda;
+  c.N = N;
+  c.K = K;
   c.m = rows;
-  c.gain = gain;
+  c.actp = actp;
+  c.ssq_in = norm ? m->ssq : nullptr;
+  c.ssq_parts = norm_parts;
+  c.ssq_stride = m->ssq_stride;
   c.eps = m->cfg.rms_eps;
   c.epi = epi;
-  c.out = out;
-  c.ldo = ldo;
   c.rope_cs = m->rope_cs;
   return c;
 }
@@ -481,7 +487,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 2));
   if (rc) return rc;
   HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
-                            st));
+                            c.dtype == PIPESD_BF16 ? m->attn_norm[0] : nullptr, m->xpk, m->ssq, m->ssq_stride, st));
+  int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
   for (int l = 0; l < c.n_layers; ++l) {
     AttnCall at{};
     at.dtype = c.dtype;
@@ -494,6 +501,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     at.chunk = chunk;
     at.part = m->attn_part;
     at.out = m->attn_out;
+    at.outp = m->apk;
     if (c.dtype == PIPESD_F32) {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
@@ -522,7 +530,9 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     } else {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
-        GemmCall g = gemm_call(m, m->p_qkv, m->wqkv[l], m->xres, d, rows, m->attn_norm[l], EPI_QKV, m->qbuf, qd);
+        GemmCall g = gemm_call(m, m->wqkv[l], nqkv, d, rows, m->xpk, true, norm_parts, EPI_QKV);
+        g.out = m->qbuf;
+        g.ldo = qd;
         g.kv = view;
         g.layer = l;
         g.start_pos = start_pos;
@@ -535,18 +545,30 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_O, st);
-        HIP_TRY(launch_gemm_bf16(gemm_call(m, m->p_o, m->wo[l], m->attn_out, qd, rows, nullptr, EPI_RESID, m->xres, d),
-                                 st));
+        GemmCall g = gemm_call(m, m->wo[l], d, qd, rows, m->apk, false, 0, EPI_RESID);
+        g.out = m->xres;
+        g.ldo = d;
+        g.outp = m->xpk;
+        g.gain_next = m->ffn_norm[l];
+        g.ssq_out = m->ssq;
+        HIP_TRY(launch_gemm_bf16(g, st));
+        norm_parts = d / 16;
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_GATEUP, st);
-        HIP_TRY(launch_gemm_bf16(
-            gemm_call(m, m->p_gu, m->wgu[l], m->xres, d, rows, m->ffn_norm[l], EPI_SWIGLU, m->act2, F), st));
+        GemmCall g = gemm_call(m, m->wgu[l], 2 * F, d, rows, m->xpk, true, norm_parts, EPI_SWIGLU);
+        g.outp = m->gpk;
+        HIP_TRY(launch_gemm_bf16(g, st));
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_DOWN, st);
-        HIP_TRY(launch_gemm_bf16(gemm_call(m, m->p_down, m->wdown[l], m->act2, F, rows, nullptr, EPI_RESID, m->xres, d),
-                                 st));
+        GemmCall g = gemm_call(m, m->wdown[l], d, F, rows, m->gpk, false, 0, EPI_RESID);
+        g.out = m->xres;
+        g.ldo = d;
+        g.outp = m->xpk;
+        g.gain_next = l + 1 < c.n_layers ? m->attn_norm[l + 1] : m->final_norm;
+        g.ssq_out = m->ssq;
+        HIP_TRY(launch_gemm_bf16(g, st));
       }
     }
   }
@@ -556,8 +578,10 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
       HIP_TRY(launch_rmsnorm_rows(m->xres, m->final_norm, c.rms_eps, rows, d, m->hbuf, st));
       HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->lm_head, V, d, rows, m->logits, V, 0, st));
     } else {
-      HIP_TRY(launch_gemm_bf16(
-          gemm_call(m, m->p_lm, m->lm_head, m->xres, d, rows, m->final_norm, EPI_STORE, m->logits, V), st));
+      GemmCall g = gemm_call(m, m->lm_head, V, d, rows, m->xpk, true, norm_parts, EPI_STORE);
+      g.out = m->logits;
+      g.ldo = V;
+      HIP_TRY(launch_gemm_bf16(g, st));
     }
   }
   return PIPESD_OK;

@@ -48,6 +48,31 @@ __device__ __forceinline__ int64_t v_index(const KvView& kv, int layer, int pos,
          ((int64_t)kvh * kv.head_dim + e) * kBlockTokens + (pos % kBlockTokens);
 }
 
+// ActPack: activations handed from one kernel to the next GEMM, already in the B-operand layout of
+// the 16x16x32 bf16 MFMA and split into a bf16 hi + lo pair.  For a consumer with K columns the
+// buffer is uint4[K/32][2 row tiles][hi, lo][64 lanes]; lane g*16 + (row % 16) of k-step ks holds
+// columns ks*32 + g*8 .. +7 of row (row tile)*16 + row % 16.
+__device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int lane) {
+  return (((size_t)kstep * 2 + mt) * 2 + hl) * 64 + lane;
+}
+inline size_t act_pack_bytes(int K) { return (size_t)(K / 32) * 2 * 2 * 64 * 16; }
+
+// split 8 consecutive columns k0..k0+7 (k0 % 8 == 0) of `row` into hi + lo and store them
+__device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const float (&v)[8]) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
+    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
+    h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+  }
+  const int lane = ((k0 & 31) >> 3) * 16 + (row & 15);
+  buf[act_index(k0 >> 5, row >> 4, 0, lane)] = make_uint4(h[0], h[1], h[2], h[3]);
+  buf[act_index(k0 >> 5, row >> 4, 1, lane)] = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers (one per kernel family); all enqueue on `st` and return the launch status
 // ---------------------------------------------------------------------------------------------
@@ -55,9 +80,11 @@ struct RowTokens {
   int32_t tok[kMaxRows];
 };
 
-// embedding gather into the fp32 residual stream + rotary cos/sin of the m positions
+// embedding gather into the fp32 residual stream + rotary cos/sin of the m positions; for bf16
+// models also the packed, gained copy and the per-row sum of squares for the first fused norm
 hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, int m, int start_pos, int d_model,
-                             int head_dim, const double* theta, float* xres, float* rope_cs, hipStream_t st);
+                             int head_dim, const double* theta, float* xres, float* rope_cs, const float* gain,
+                             void* xpk, float* ssq_out, int ssq_stride, hipStream_t st);
 
 // ---- fp32 path (plain ALU kernels) ----
 hipError_t launch_rmsnorm_rows(const float* x, const float* gain, float eps, int m, int d, float* out, hipStream_t st);
@@ -71,22 +98,24 @@ hipError_t launch_silu_mul(const float* gu, int m, int d_ffn, float* act2, hipSt
 enum GemmEpilogue { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
 enum PackMode { PACK_PLAIN = 0, PACK_HALVES = 1 };
 
-struct GemmPlan {  // launch shape of one GEMM, fixed when the model is created
+struct GemmPlan {  // launch shape of one GEMM
   int K, N, ntiles;
   int W, P, grid, tg;  // waves per workgroup, K phases per wave, workgroups, n-tiles per group
 };
-GemmPlan plan_gemm(int N, int K, int n_cu);
 
 struct GemmCall {
-  GemmPlan plan;
-  const void* wp;     // re-tiled weights
-  const float* act;   // [m][lda] fp32
-  int lda, m;
-  const float* gain;  // RMSNorm gain [K] (fused norm) or nullptr
+  const void* wp;     // re-tiled weights [N][K]
+  int N, K, m;
+  const void* actp;   // packed activations (ActPack with K columns)
+  const float* ssq_in;  // fused RMSNorm: [row][ssq_stride] partial sums of x^2 (ssq_parts used), or nullptr
+  int ssq_parts, ssq_stride;
   float eps;
   int epi;
-  float* out;         // STORE: [m][ldo]; RESID: residual stream [m][ldo]; SWIGLU: [m][ldo]; QKV: query buffer
+  float* out;         // STORE: [m][ldo] logits; RESID: residual stream [m][ldo]; QKV: query buffer [m][ldo]
   int ldo;
+  void* outp;         // RESID: packed x_new * gain_next; SWIGLU: packed silu(gate)*up
+  const float* gain_next;
+  float* ssq_out;     // RESID: [row][ssq_stride] per-tile sums of x_new^2
   // QKV epilogue
   KvView kv;
   int layer, start_pos, n_q_heads;
@@ -112,7 +141,8 @@ struct AttnCall {
   int layer, m, start_pos, n_q_heads;
   int chunk;       // tokens per workgroup
   float* part;     // [(head*m + r)*nsplit + split][head_dim + 2]
-  float* out;      // [m][n_q_heads*head_dim]
+  float* out;      // fp32 cache: [m][n_q_heads*head_dim]
+  void* outp;      // bf16 cache: packed output (ActPack with n_q_heads*head_dim columns)
 };
 int attn_nsplit(int total_tokens, int chunk);
 int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type

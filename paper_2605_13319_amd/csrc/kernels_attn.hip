@@ -269,36 +269,39 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
   }
 }
 
-// merge the splits of one (row, head), one wave each:
-// o = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s, splits taken in index order
+// merge the splits of one (row, head): o = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s, splits taken
+// in index order.  h/8 threads per (row, head), 8 consecutive elements each; the result goes out as
+// fp32 or, for the next GEMM, packed (ActPack).
+template <bool PACKED>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part, int m, int n_q_heads, int h,
-                                                           int nsplit, float* __restrict__ out) {
-  const int lane = threadIdx.x & 63;
-  const int pair = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);  // head * m + r
+                                                           int nsplit, float* __restrict__ out, uint4* outp) {
+  const int tpp = h / 8;  // threads per pair
+  const int gt = blockIdx.x * blockDim.x + threadIdx.x;
+  const int pair = gt / tpp, e0 = (gt % tpp) * 8;  // pair = head * m + r
   if (pair >= m * n_q_heads) return;
   const int head = pair / m, r = pair % m;
   const float* p = part + (size_t)pair * nsplit * (h + 2);
   float M = -INFINITY;
-  for (int s = lane; s < nsplit; s += 64) M = fmaxf(M, p[(size_t)s * (h + 2) + h]);
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[(size_t)s * (h + 2) + h]);
+  float L = 0.f, acc[8];
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
-  float L = 0.f;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};  // h <= 256
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   for (int s = 0; s < nsplit; ++s) {
-    const float ms = p[(size_t)s * (h + 2) + h];
+    const float* ps = p + (size_t)s * (h + 2);
+    const float ms = ps[h];
     if (ms == -INFINITY) continue;
     const float wgt = expf(ms - M);
-    L += p[(size_t)s * (h + 2) + h + 1] * wgt;
+    L += ps[h + 1] * wgt;
 #pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int e = lane + x * 64;
-      if (e < h) acc[x] += p[(size_t)s * (h + 2) + e] * wgt;
-    }
+    for (int i = 0; i < 8; ++i) acc[i] += ps[e0 + i] * wgt;
   }
 #pragma unroll
-  for (int x = 0; x < 4; ++x) {
-    const int e = lane + x * 64;
-    if (e < h) out[((size_t)r * n_q_heads + head) * h + e] = acc[x] / L;
+  for (int i = 0; i < 8; ++i) acc[i] /= L;
+  if (PACKED) {
+    store_act8(outp, r, head * h + e0, acc);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[((size_t)r * n_q_heads + head) * h + e0 + i] = acc[i];
   }
 }
 
@@ -328,8 +331,13 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int pairs = c.m * c.n_q_heads;
-  attn_combine_kernel<<<(pairs + 3) / 4, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, c.out);
+  const int threads = c.m * c.n_q_heads * (h / 8);
+  if (c.dtype == PIPESD_F32)
+    attn_combine_kernel<false><<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, c.out,
+                                                                      nullptr);
+  else
+    attn_combine_kernel<true><<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, nullptr,
+                                                                     (uint4*)c.outp);
   return hipGetLastError();
 }
 

@@ -7,18 +7,20 @@
 //    8*(l/16)..+7.  A wave's load instruction then reads 1 KB contiguous and the data lands directly
 //    in MFMA operand registers: no LDS pass, no barrier in the main loop.
 //  * W is the A operand (16 weight rows x 32 k), the activations are the B operand (32 k x 16 rows).
-//    Each wave owns one K slice; its activation fragments stay in registers for the whole kernel,
-//    as a bf16 hi + lo pair so that no activation precision is lost (two MFMAs per weight fragment;
-//    the matrix cores idle otherwise).
+//    Activations travel between kernels already in B-operand layout as a bf16 hi + lo pair (see
+//    ActPack in common.h): the producing epilogue splits each value once, every consuming wave just
+//    loads registers.  Two MFMAs per weight fragment keep 16 significand bits of the activations;
+//    the matrix cores idle otherwise.
 //  * A workgroup's W waves cover W K slices of the same n-tiles at a time (and, for long K, P
-//    such phases one after the other, accumulators kept in registers) and add their 16x16 partial
-//    tiles through LDS in a fixed order.  Nothing crosses workgroups: no global partials, no
-//    device-scope fences, no floating-point atomics; results are bit-reproducible.
-//  * RMSNorm is fused: the kernel multiplies the activations by the gain on load, accumulates
-//    sum(x^2) of the raw activations on the way, and scales the finished tile by rstd per row.
-//  * Epilogues: plain store (logits), residual add, SiLU(gate)*up, or rotary + query buffer / paged
-//    KV-cache append.  Rows 8..15 of a weight tile are the partners of rows 0..7 (other half of the
-//    head for the rotary pair; the up-projection row for a gate row) so a pair is finished together.
+//    such phases one after the other) and add their 16x16 partial tiles through LDS in a fixed
+//    order.  Nothing crosses workgroups: no global partials, no device-scope fences, no
+//    floating-point atomics; results are bit-reproducible.
+//  * RMSNorm is fused: the producer stores x * gain and per-tile sums of x^2; the consumer scales the
+//    finished tile by rstd per row.
+//  * Epilogues: plain store (logits), residual add (+ packed, gained copy for the next GEMM),
+//    SiLU(gate)*up (packed), or rotary + query buffer / paged KV-cache append.  Rows 8..15 of a
+//    weight tile are the partners of rows 0..7 (other half of the head for the rotary pair; the
+//    up-projection row for a gate row) so a pair is finished by one thread.
 #include "common.h"
 
 namespace pipesd {
@@ -27,134 +29,173 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 struct GemmArgs {
   const u32x4* wp;
-  const float* act;
-  const float* gain;
-  float* out;
+  const u32x4* actp;      // packed activations (ActPack, K columns)
+  const float* ssq_in;    // fused norm: [row][ssq_stride] partial sums of x^2, or nullptr
+  int ssq_parts, ssq_stride;
+  float* out;             // STORE: logits; RESID: residual stream; QKV: query buffer
+  u32x4* outp;            // RESID / SWIGLU: packed output for the next GEMM
+  const float* gain_next; // RESID: gain applied to the packed copy
+  float* ssq_out;         // RESID: [row][ssq_stride] per-tile sums of x_new^2
   const float* rope_cs;
   KvView kv;
-  int lda, m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
+  int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
   float eps;
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ void split_hi_lo(const float (&v)[8], bf16x8& hi, bf16x8& lo) {
-  uint32_t h[4], l[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
-    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
-    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
-    h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-    l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-  }
-  hi = as_bf16x8(u32x4{h[0], h[1], h[2], h[3]});
-  lo = as_bf16x8(u32x4{l[0], l[1], l[2], l[3]});
+// The weight stream is issued and awaited by hand: the loads are opaque to the compiler's wait-count
+// bookkeeping, and each use is preceded by an explicit s_waitcnt tied to the register it releases.
+// Vector memory loads return in order, so "at most N younger loads outstanding" is exact here: the
+// compiler would otherwise join the with-next and without-next paths into vmcnt(0) and drain the
+// pipeline at every chunk.
+__device__ __forceinline__ u32x4 stream_load(const u32x4* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
+  return v;
+}
+__device__ __forceinline__ u32x4 cached_load(const u32x4* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_younger(u32x4& v) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N));
 }
 
-__device__ __forceinline__ void epilogue_pair(const GemmArgs& a, int t, int wr, int row, float v0, float v1,
-                                              float rstd) {
-  if (row >= a.m) return;
+// one chunk = KSTEPS weight fragments of one n-tile against this wave's activation fragments; while
+// fragment ks is multiplied, fragment ks of the next chunk is requested into the same registers
+template <int MT, int KSTEPS, bool HAS_NEXT, int KS = 0>
+__device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bhi)[MT][KSTEPS],
+                                           const u32x4 (&blo)[MT][KSTEPS], f32x4 (&acc)[MT], const u32x4* nxt) {
+  if constexpr (KS < KSTEPS) {
+    wait_younger<HAS_NEXT ? KSTEPS - 1 : KSTEPS - 1 - KS>(af[KS]);
+    const bf16x8 av = as_bf16x8(af[KS]);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bhi[mt][KS]), acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(blo[mt][KS]), acc[mt], 0, 0, 0);
+    }
+    if constexpr (HAS_NEXT) af[KS] = stream_load(nxt + KS * 64);
+    chunk_mfma<MT, KSTEPS, HAS_NEXT, KS + 1>(af, bhi, blo, acc, nxt);
+  }
+}
+
+// finish one (n-tile t, activation row `row`): v[i] is the dot product with weight row i of the tile
+__device__ __forceinline__ void epilogue_column(const GemmArgs& a, int t, int row, const float (&v)[16], float rstd) {
   switch (a.epi) {
     case EPI_STORE: {
-      const int n0 = t * 16 + wr, n1 = n0 + 8;
-      if (n0 < a.N) a.out[(size_t)row * a.ldo + n0] = v0 * rstd;
-      if (n1 < a.N) a.out[(size_t)row * a.ldo + n1] = v1 * rstd;
+      float* o = a.out + (size_t)row * a.ldo + t * 16;
+      if (t * 16 + 16 <= a.N && (a.ldo & 3) == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; i += 4)
+          *(float4*)(o + i) = make_float4(v[i] * rstd, v[i + 1] * rstd, v[i + 2] * rstd, v[i + 3] * rstd);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (t * 16 + i < a.N) o[i] = v[i] * rstd;
+      }
       break;
     }
     case EPI_RESID: {
-      const int n0 = t * 16 + wr, n1 = n0 + 8;
-      if (n0 < a.N) a.out[(size_t)row * a.ldo + n0] += v0;
-      if (n1 < a.N) a.out[(size_t)row * a.ldo + n1] += v1;
+      float* o = a.out + (size_t)row * a.ldo + t * 16;
+      float x[16], sq = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i += 4) {
+        const float4 old = *(const float4*)(o + i);
+        x[i] = old.x + v[i]; x[i + 1] = old.y + v[i + 1]; x[i + 2] = old.z + v[i + 2]; x[i + 3] = old.w + v[i + 3];
+        *(float4*)(o + i) = make_float4(x[i], x[i + 1], x[i + 2], x[i + 3]);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sq = fmaf(x[i], x[i], sq);
+      a.ssq_out[(size_t)row * a.ssq_stride + t] = sq;
+      const float* gn = a.gain_next + t * 16;
+      float y0[8], y1[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        y0[i] = x[i] * gn[i];
+        y1[i] = x[i + 8] * gn[i + 8];
+      }
+      store_act8((uint4*)a.outp, row, t * 16, y0);
+      store_act8((uint4*)a.outp, row, t * 16 + 8, y1);
       break;
     }
     case EPI_SWIGLU: {
-      const int j = t * 8 + wr;
-      const float gt = v0 * rstd, up = v1 * rstd;
-      a.out[(size_t)row * a.ldo + j] = (gt / (1.0f + expf(-gt))) * up;
+      float y[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float gt = v[i] * rstd, up = v[i + 8] * rstd;
+        y[i] = (gt / (1.0f + expf(-gt))) * up;
+      }
+      store_act8((uint4*)a.outp, row, t * 8, y);
       break;
     }
     case EPI_QKV: {
       const int h = a.kv.head_dim, half = h >> 1, hpt = h >> 4;
-      const int hd = t / hpt, i = (t % hpt) * 8 + wr;
-      const float x0 = v0 * rstd, x1 = v1 * rstd;
+      const int hd = t / hpt, i0 = (t % hpt) * 8;
+      float r0[8], r1[8];
       if (hd < a.n_q_heads + a.kv.n_kv_heads) {
-        const float c = a.rope_cs[((size_t)row * half + i) * 2], s = a.rope_cs[((size_t)row * half + i) * 2 + 1];
-        const float r0 = x0 * c - x1 * s, r1 = x1 * c + x0 * s;
-        if (hd < a.n_q_heads) {
-          a.out[(size_t)row * a.ldo + hd * h + i] = r0;
-          a.out[(size_t)row * a.ldo + hd * h + i + half] = r1;
-        } else {
-          uint16_t* pool = (uint16_t*)a.kv.pool;
-          const int kvh = hd - a.n_q_heads;
-          pool[k_index(a.kv, a.layer, a.start_pos + row, kvh, i)] = f32_to_bf16_bits(r0);
-          pool[k_index(a.kv, a.layer, a.start_pos + row, kvh, i + half)] = f32_to_bf16_bits(r1);
+        const float* cs = a.rope_cs + ((size_t)row * half + i0) * 2;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float x0 = v[i] * rstd, x1 = v[i + 8] * rstd, c = cs[2 * i], s = cs[2 * i + 1];
+          r0[i] = x0 * c - x1 * s;
+          r1[i] = x1 * c + x0 * s;
         }
       } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          r0[i] = v[i] * rstd;
+          r1[i] = v[i + 8] * rstd;
+        }
+      }
+      if (hd < a.n_q_heads) {
+        float* o = a.out + (size_t)row * a.ldo + hd * h + i0;
+        *(float4*)o = make_float4(r0[0], r0[1], r0[2], r0[3]);
+        *(float4*)(o + 4) = make_float4(r0[4], r0[5], r0[6], r0[7]);
+        *(float4*)(o + half) = make_float4(r1[0], r1[1], r1[2], r1[3]);
+        *(float4*)(o + half + 4) = make_float4(r1[4], r1[5], r1[6], r1[7]);
+      } else {
         uint16_t* pool = (uint16_t*)a.kv.pool;
-        const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
-        pool[v_index(a.kv, a.layer, a.start_pos + row, kvh, i)] = f32_to_bf16_bits(x0);
-        pool[v_index(a.kv, a.layer, a.start_pos + row, kvh, i + half)] = f32_to_bf16_bits(x1);
+        const int pos = a.start_pos + row;
+        if (hd < a.n_q_heads + a.kv.n_kv_heads) {
+          const int kvh = hd - a.n_q_heads;
+          uint16_t b0[8], b1[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            b0[i] = f32_to_bf16_bits(r0[i]);
+            b1[i] = f32_to_bf16_bits(r1[i]);
+          }
+          *(uint4*)(pool + k_index(a.kv, a.layer, pos, kvh, i0)) = *(const uint4*)b0;
+          *(uint4*)(pool + k_index(a.kv, a.layer, pos, kvh, i0 + half)) = *(const uint4*)b1;
+        } else {
+          const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            pool[v_index(a.kv, a.layer, pos, kvh, i0 + i)] = f32_to_bf16_bits(r0[i]);
+            pool[v_index(a.kv, a.layer, pos, kvh, i0 + half + i)] = f32_to_bf16_bits(r1[i]);
+          }
+        }
       }
       break;
     }
-  }
-}
-
-// Loads this wave's activation fragments for K slice `slice` (KSTEPS k-steps of 32 columns): lane
-// (c = row, g = k-group) takes 8 consecutive fp32 values per k-step, multiplies by the norm gain if
-// one is fused, adds the raw squares to ssq, and splits into bf16 hi + lo.
-template <int MT, int KSTEPS>
-__device__ __forceinline__ void load_act_frags(const GemmArgs& a, int slice, int c, int g, bf16x8 (&bhi)[MT][KSTEPS],
-                                               bf16x8 (&blo)[MT][KSTEPS], float (&ssq)[MT]) {
-  const int k0 = slice * KSTEPS * 32;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int row = mt * 16 + c;
-    float part = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      const int kk = k0 + ks * 32 + g * 8;
-      float v[8];
-      if (row < a.m) {
-        const float4 x0 = *(const float4*)(a.act + (size_t)row * a.lda + kk);
-        const float4 x1 = *(const float4*)(a.act + (size_t)row * a.lda + kk + 4);
-        v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
-        v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = 0.f;
-      }
-      if (a.gain != nullptr) {
-        const float4 g0 = *(const float4*)(a.gain + kk), g1 = *(const float4*)(a.gain + kk + 4);
-        const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          part = fmaf(v[i], v[i], part);
-          v[i] *= gv[i];
-        }
-      }
-      split_hi_lo(v, bhi[mt][ks], blo[mt][ks]);
-    }
-    part += __shfl_xor(part, 16, 64);
-    part += __shfl_xor(part, 32, 64);
-    ssq[mt] += part;
   }
 }
 
 // Work decomposition: K is cut into W * P slices of KSTEPS*32 columns; wave w of a workgroup takes
 // slices p*W + w, p = 0..P-1, one phase after the other, for a group of tg n-tiles, keeping its
-// running 16x16 sums in its own LDS slots.  After the last phase the W waves' sums are added.  Groups are dealt to workgroups round-robin.  The weight stream of a wave is a
-// fixed sequence of 1 KB-per-instruction chunks and the next chunk is always requested while the
-// current one is multiplied, also across phase and group boundaries.
+// running 16x16 sums in its own LDS slots.  After the last phase the W waves' sums are added.
+// Groups are dealt to workgroups round-robin.  The weight stream of a wave is a fixed sequence of
+// 1 KB-per-instruction chunks and the next chunk is always requested while the current one is
+// multiplied, also across phase and group boundaries.
 template <int MT, int KSTEPS>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ float lds[];
   f32x4* red = (f32x4*)lds;                                     // [tg][W][MT][64]
-  float* ssq_lds = lds + (size_t)a.tg * a.W * MT * 64 * 4;      // [W][MT*16]
+  float* rstd_lds = lds + (size_t)a.tg * a.W * MT * 64 * 4;     // [MT*16]
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int c = lane & 15, g = lane >> 4;
   const int nthreads = a.W * 64;
   const int ngroups = (a.ntiles + a.tg - 1) / a.tg;
   int grp = blockIdx.x;
@@ -168,24 +209,47 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   {
     const u32x4* first = chunk(grp * a.tg, 0);
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = __builtin_nontemporal_load(first + ks * 64);
+    for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load(first + ks * 64);
   }
 
-  bf16x8 bhi[MT][KSTEPS], blo[MT][KSTEPS];
-  float ssq[MT];
+  // activation fragments of the current K slice; loaded by hand too and awaited in full (they and the
+  // first weight chunk are all needed before the first MFMA)
+  u32x4 bhi[MT][KSTEPS], blo[MT][KSTEPS];
+  auto load_act = [&](int slice) {
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
-  if (a.P == 1) load_act_frags<MT, KSTEPS>(a, w, c, g, bhi, blo, ssq);
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        bhi[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 0, lane));
+        blo[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 1, lane));
+      }
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        wait_younger<0>(bhi[mt][ks]);
+        wait_younger<0>(blo[mt][ks]);
+      }
+  };
+  if (a.P == 1) load_act(w);
+
+  // fused norm: rstd per row from the producer's partial sums of squares, added in index order
+  if (a.ssq_in != nullptr) {
+    for (int row = w; row < MT * 16; row += a.W) {
+      float q = 0.f;
+      if (row < a.m)
+        for (int j = lane; j < a.ssq_parts; j += 64) q += a.ssq_in[(size_t)row * a.ssq_stride + j];
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+      if (lane == 0) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+    }
+  }
 
   for (; grp < ngroups; grp += gridDim.x) {
     const int t0 = grp * a.tg;
     const int nt_g = min(a.tg, a.ntiles - t0);
-    if (a.P > 1) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) ssq[mt] = 0.f;
-    }
     for (int p = 0; p < a.P; ++p) {
-      if (a.P > 1) load_act_frags<MT, KSTEPS>(a, p * a.W + w, c, g, bhi, blo, ssq);
+      if (a.P > 1) load_act(p * a.W + w);
       for (int t = 0; t < nt_g; ++t) {
         const u32x4* nxt = nullptr;
         if (t + 1 < nt_g) nxt = chunk(t0 + t + 1, p);
@@ -194,16 +258,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
         f32x4 acc[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-          const bf16x8 av = as_bf16x8(af[ks]);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[mt][ks], acc[mt], 0, 0, 0);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[mt][ks], acc[mt], 0, 0, 0);
-          }
-          if (nxt != nullptr) af[ks] = __builtin_nontemporal_load(nxt + ks * 64);
-        }
+        if (nxt != nullptr)
+          chunk_mfma<MT, KSTEPS, true>(af, bhi, blo, acc, nxt);
+        else
+          chunk_mfma<MT, KSTEPS, false>(af, bhi, blo, acc, nxt);
         // this wave's running sum over its phases lives in its own LDS slot
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -212,31 +270,26 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
         }
       }
     }
-    if (a.gain != nullptr && g == 0) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) ssq_lds[w * MT * 16 + mt * 16 + c] = ssq[mt];
-    }
     __syncthreads();
-    // add the W partial tiles and finish each (row pair, activation row)
-    const int npairs = nt_g * MT * 128;
-    const float inv_k = 1.0f / (float)a.K;
-    for (int e = tid; e < npairs; e += nthreads) {
-      const int tt = e / (MT * 128), rem = e % (MT * 128), mt = rem / 128, pr = rem % 128;
-      const int wr = pr >> 4, cc = pr & 15;
-      const int l0 = (wr >> 2) * 16 + cc, comp = wr & 3;
-      float v0 = 0.f, v1 = 0.f;
+    // one thread per (tile, activation row): add the W partial columns and finish
+    const int ncols = nt_g * MT * 16;
+    for (int e = tid; e < ncols; e += nthreads) {
+      const int tt = e / (MT * 16), rem = e % (MT * 16), mt = rem >> 4, cc = rem & 15;
+      const int row = mt * 16 + cc;
+      if (row >= a.m) continue;
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = 0.f;
       for (int ww = 0; ww < a.W; ++ww) {
-        const float* rp = (const float*)(red + ((size_t)(tt * a.W + ww) * MT + mt) * 64);
-        v0 += rp[l0 * 4 + comp];
-        v1 += rp[(l0 + 32) * 4 + comp];
+        const f32x4* rp = red + ((size_t)(tt * a.W + ww) * MT + mt) * 64 + cc;
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const f32x4 x = rp[gg * 16];  // weight rows gg*4 .. gg*4+3
+          v[gg * 4 + 0] += x[0]; v[gg * 4 + 1] += x[1]; v[gg * 4 + 2] += x[2]; v[gg * 4 + 3] += x[3];
+        }
       }
-      float rstd = 1.0f;
-      if (a.gain != nullptr) {
-        float q = 0.f;
-        for (int ww = 0; ww < a.W; ++ww) q += ssq_lds[ww * MT * 16 + mt * 16 + cc];
-        rstd = 1.0f / sqrtf(q * inv_k + a.eps);
-      }
-      epilogue_pair(a, t0 + tt, wr, mt * 16 + cc, v0, v1, rstd);
+      const float rstd = a.ssq_in != nullptr ? rstd_lds[row] : 1.0f;
+      epilogue_column(a, t0 + tt, row, v, rstd);
     }
     __syncthreads();  // red is free again
   }
@@ -258,18 +311,11 @@ int device_cu_count() {
   return n_cu;
 }
 
-GemmPlan plan_gemm(int N, int K, int n_cu) {
-  GemmPlan p{};
+static void shape_for(int N, int K, int m, int n_cu, GemmPlan& p) {
   p.K = K;
   p.N = N;
   p.ntiles = (N + 15) / 16;
-  (void)n_cu;
-  return p;
-}
-
-static void shape_for(const GemmPlan& base, int m, int n_cu, GemmPlan& p) {
-  p = base;
-  const int slices = base.K / (m <= 16 ? 512 : 256);
+  const int slices = K / (m <= 16 ? 512 : 256);
   int W = 1;
   for (int cand = 8; cand >= 1; --cand)
     if (slices % cand == 0) { W = cand; break; }
@@ -294,17 +340,21 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   const int n_cu = device_cu_count();
   if (n_cu <= 0) return hipErrorUnknown;
   const int slice = c.m <= 16 ? 512 : 256;
-  if (c.m < 1 || c.m > kMaxRows || c.plan.K % slice != 0 || (c.lda & 3) != 0) return hipErrorInvalidValue;
+  if (c.m < 1 || c.m > kMaxRows || c.K % slice != 0) return hipErrorInvalidValue;
   GemmPlan p;
-  shape_for(c.plan, c.m, n_cu, p);
+  shape_for(c.N, c.K, c.m, n_cu, p);
   GemmArgs a{};
   a.wp = (const u32x4*)c.wp;
-  a.act = c.act;
-  a.gain = c.gain;
+  a.actp = (const u32x4*)c.actp;
+  a.ssq_in = c.ssq_in;
+  a.ssq_parts = c.ssq_parts;
+  a.ssq_stride = c.ssq_stride;
   a.out = c.out;
+  a.outp = (u32x4*)c.outp;
+  a.gain_next = c.gain_next;
+  a.ssq_out = c.ssq_out;
   a.rope_cs = c.rope_cs;
   a.kv = c.kv;
-  a.lda = c.lda;
   a.m = c.m;
   a.K = p.K;
   a.N = p.N;
@@ -320,7 +370,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.n_q_heads = c.n_q_heads;
   a.eps = c.eps;
   const int mt = c.m <= 16 ? 1 : 2;
-  const size_t lds = ((size_t)p.tg * p.W * mt * 64 * 4 + (size_t)p.W * mt * 16) * sizeof(float);
+  const size_t lds = ((size_t)p.tg * p.W * mt * 64 * 4 + 32) * sizeof(float);
   if (mt == 1)
     gemm_bf16_kernel<1, 16><<<p.grid, p.W * 64, lds, st>>>(a);
   else

@@ -10,11 +10,35 @@ namespace pipesd {
 template <typename T>
 __global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, int m, int start_pos, int d, int half,
                                   const double* __restrict__ theta, float* __restrict__ xres,
-                                  float* __restrict__ rope_cs) {
+                                  float* __restrict__ rope_cs, const float* __restrict__ gain, uint4* xpk,
+                                  float* __restrict__ ssq_out, int ssq_stride) {
+  __shared__ float red[4];
   const int r = blockIdx.x;
   if (r >= m) return;
   const size_t base = (size_t)toks.tok[r] * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) xres[(size_t)r * d + i] = load_elem(emb, base + i);
+  float sq = 0.f;
+  for (int j = threadIdx.x; j < d / 8; j += blockDim.x) {
+    float v[8], y[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      v[i] = load_elem(emb, base + j * 8 + i);
+      xres[(size_t)r * d + j * 8 + i] = v[i];
+      sq = fmaf(v[i], v[i], sq);
+    }
+    if (xpk != nullptr) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) y[i] = v[i] * gain[j * 8 + i];
+      store_act8(xpk, r, j * 8, y);
+    }
+  }
+  for (int i = (d / 8) * 8 + threadIdx.x; i < d; i += blockDim.x) xres[(size_t)r * d + i] = load_elem(emb, base + i);
+  if (ssq_out != nullptr) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0) ssq_out[(size_t)r * ssq_stride] = (red[0] + red[1]) + (red[2] + red[3]);
+  }
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
     const double ang = (double)(start_pos + r) * theta[i];
     rope_cs[((size_t)r * half + i) * 2 + 0] = (float)cos(ang);
@@ -23,13 +47,15 @@ __global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, int
 }
 
 hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, int m, int start_pos, int d_model,
-                             int head_dim, const double* theta, float* xres, float* rope_cs, hipStream_t st) {
+                             int head_dim, const double* theta, float* xres, float* rope_cs, const float* gain,
+                             void* xpk, float* ssq_out, int ssq_stride, hipStream_t st) {
   if (dtype == PIPESD_F32)
     setup_rows_kernel<float><<<m, 256, 0, st>>>((const float*)tok_emb, toks, m, start_pos, d_model, head_dim / 2,
-                                                theta, xres, rope_cs);
+                                                theta, xres, rope_cs, nullptr, nullptr, nullptr, 0);
   else
     setup_rows_kernel<uint16_t><<<m, 256, 0, st>>>((const uint16_t*)tok_emb, toks, m, start_pos, d_model,
-                                                   head_dim / 2, theta, xres, rope_cs);
+                                                   head_dim / 2, theta, xres, rope_cs, gain, (uint4*)xpk, ssq_out,
+                                                   ssq_stride);
   return hipGetLastError();
 }
 

@@ -166,3 +166,30 @@ def test_pool_exhaustion_changes_nothing(nav):
     assert kv.length(0) == 40 and kv.seq_blocks(0) == 3
     a, n = kv.nav_verify(0, d[:8])                    # 39 + 9 = 48 fits
     assert 0 <= a <= 8
+
+
+def test_llama_1b_workload(nav):
+    """Config 'llama-1b' in full: 16 layers, d 2048, 32/8 heads x 64, FFN 8192, vocab 32000, bf16;
+    1024-token prefix prefilled by each side on its own, k = 8, q = softmax(target logits + 0.5 N)."""
+    wl = I.WORKLOADS["llama-1b"]
+    shape, seed = wl["shape"], wl["seed"]
+    oseq, model, kv = _both(nav, shape, seed, wl["prefix"], n_blocks=80, max_len=wl["prefix"] + 64)
+    for r in range(2):
+        d, q = drafts_from_oracle(oseq, wl["k"], wl["sigma"], seed + I.SEED_NOISE + 10 * r,
+                                  seed + I.SEED_DRAFT_U + 10 * r)
+        u = I.make_uniforms(wl["k"] + 1, seed + I.SEED_VERIFY_U + 10 * r)
+        err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
+        print(f"llama-1b round {r}: err {err:.2e} accepted {a}/{wl['k']}", flush=True)
+
+
+@pytest.mark.parametrize("k", [8, 16])
+def test_llama_8b_width_truncated_to_two_layers(nav, k):
+    """The 8B shape at full width, vocabulary and context (every per-layer launch has the shape the
+    benchmark times) with 2 of its 32 layers, so that the checker can prefill 2048 tokens."""
+    wl = I.WORKLOADS["llama-8b"]
+    shape, seed = wl["shape"].truncated(2), wl["seed"]
+    oseq, model, kv = _both(nav, shape, seed, wl["prefix"], n_blocks=136, max_len=wl["prefix"] + 64)
+    d, q = drafts_from_oracle(oseq, k, wl["sigma"], seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U)
+    u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U)
+    err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
+    print(f"llama-8b-L2 k={k}: err {err:.2e} accepted {a}/{k}", flush=True)
