@@ -484,7 +484,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   for (int r = 0; r < rows; ++r) rt.tok[r] = row_tokens[r];
   const int chunk = attn_chunk_tokens(c.dtype);
   const int nsplit = attn_nsplit(start_pos + rows, chunk);
-  int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 2));
+  int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 4));
   if (rc) return rc;
   HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
                             c.dtype == PIPESD_BF16 ? m->attn_norm[0] : nullptr, m->xpk, m->ssq, m->ssq_stride, st));

@@ -10,6 +10,7 @@
 namespace pipesd {
 
 constexpr int kAttnThreads = 256;
+constexpr int kPartPad = 4;  // a partial row is [head_dim values, max, sum, 2 unused] so that rows stay 16-byte aligned
 constexpr int kAttnChunkMax = 32;
 
 template <typename T>
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
         ps[tid * chunk + t] = p;
         l += p;
       }
-      float* o = part + (((size_t)head * m + tid) * nsplit + split) * (h + 2);
+      float* o = part + (((size_t)head * m + tid) * nsplit + split) * (h + kPartPad);
       o[h] = mx;
       o[h + 1] = l;
     }
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
       const int r = i / h, e = i % h;
       float acc = 0.f;
       for (int t = 0; t < nt; ++t) acc = fmaf(ps[r * chunk + t], vs[t * hp + e], acc);
-      part[(((size_t)head * m + r) * nsplit + split) * (h + 2) + e] = acc;
+      part[(((size_t)head * m + r) * nsplit + split) * (h + kPartPad) + e] = acc;
     }
   }
 }
@@ -90,13 +91,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
 // ------------------------------------------------------------------------------------------------
 // bf16 cache: the same computation on the matrix cores.
 //
-// Workgroup (kv_head, split) = 4 waves x 32 tokens.  A wave loads its 32 tokens' keys (two
-// [16 tok][h] blocks, A operand of S^T = K Q^T) and values (two [h][16 tok] blocks, A operand of
-// O^T = V^T P) once into registers, straight from the paged cache in MFMA operand layout, then
-// walks the 16-row tiles of the query rows that share the KV head.  Queries and probabilities are
-// fed as bf16 hi + lo pairs so only the cache itself is bf16.  The scores of one query row sit in
-// the four lanes {c, c+16, c+32, c+48}, so the softmax statistics take two cross-lane steps.
-// The four waves' (max, sum, O) are merged through LDS and written as one partial per split.
+// A wave loads 32 tokens' keys (two [16 tok][h] blocks, A operand of S^T = K Q^T) and values (two
+// [h][16 tok] blocks, A operand of O^T = V^T P) straight from the paged cache in MFMA operand
+// layout.  Queries and probabilities are fed as bf16 hi + lo pairs so only the cache itself is
+// bf16.  The scores of one query row sit in the four lanes {c, c+16, c+32, c+48}, so the softmax
+// statistics take two cross-lane steps.
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(4))) unsigned au32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned au32x2;
@@ -115,16 +114,20 @@ __device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf
   lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
 }
 
-constexpr int kAttnWaves = 4;
+constexpr int kAttnWaves = 8;
 constexpr int kAttnWgTokens = kAttnWaves * 32;
 
+// Workgroup (kv_head, split) = 8 waves x 32 tokens.  A wave loads its 32 tokens' keys and values once
+// into registers, then walks the 16-row tiles of the query rows that share the KV head; per tile
+// the eight waves' (max, sum, O) are merged pairwise through LDS and written as the split's
+// partial; a second small kernel merges the splits.
 template <int HD>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float* __restrict__ q, KvView kv, int layer,
                                                                     int m, int start_pos, int n_q_heads, int nsplit,
                                                                     float* __restrict__ part) {
   constexpr int KSQ = HD / 32, HT = HD / 16, ROW = HD + 4;
-  __shared__ float o_lds[kAttnWaves][16][ROW];
-  __shared__ float m_lds[kAttnWaves][16], l_lds[kAttnWaves][16];
+  __shared__ float o_lds[kAttnWaves / 2][16][ROW];
+  __shared__ float m_lds[kAttnWaves / 2][16], l_lds[kAttnWaves / 2][16];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int kvh = blockIdx.x, split = blockIdx.y;
@@ -142,8 +145,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int tb = tok0 + tt * 16;
-      const bool blk_ok = tb < total;
-      const int blk = blk_ok ? kv.table[tb / kBlockTokens] : 0;
+      const int blk = tb < total ? kv.table[tb / kBlockTokens] : 0;
       const int64_t base = (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
       const bool tok_ok = tb + c < total;
 #pragma unroll
@@ -152,7 +154,6 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
         if (tok_ok) v = *(const au32x4*)(pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8);
         kf[tt][s] = __builtin_bit_cast(bf16x8, v);
       }
-      // values: element row e = j*16 + c, tokens g*4 .. g*4+3 of this block
       const int nvalid = min(4, max(0, total - (tb + g * 4)));
       const unsigned long long keep = nvalid >= 4 ? ~0ull : ((1ull << (16 * nvalid)) - 1ull);
 #pragma unroll
@@ -207,87 +208,132 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
         sc[tt * 4 + i] = (row_ok && t <= pos_q) ? acc[i] * scale : -INFINITY;
       }
     }
-    float mx = sc[0];
+    float m_run = sc[0];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sc[i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float pv[8], l = 0.f;
+    for (int i = 1; i < 8; ++i) m_run = fmaxf(m_run, sc[i]);
+    m_run = fmaxf(m_run, __shfl_xor(m_run, 16, 64));
+    m_run = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+    float pv[8], l_run = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - mx);
-      l += pv[i];
+      pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - m_run);
+      l_run += pv[i];
     }
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
     bf16x8 phi, plo;
     split_hi_lo8(pv, phi, plo);
+    f32x4 o[HT];
 #pragma unroll
     for (int j = 0; j < HT; ++j) {
-      f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], phi, o, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], plo, o, 0, 0, 0);
-      *(f32x4*)&o_lds[w][c][j * 16 + g * 4] = o;  // O[query c][element j*16 + g*4 + i]
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], phi, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], plo, acc, 0, 0, 0);
+      o[j] = acc;  // O[query c][element j*16 + g*4 + i]
     }
-    if (g == 0) {
-      m_lds[w][c] = mx;
-      l_lds[w][c] = l;
-    }
-    __syncthreads();
-    // merge the four waves and write the split's partial
-    {
-      const int cc = tid >> 4, seg = tid & 15;
-      const int row = qt * 16 + cc;
-      if (row < R) {
-        float M = m_lds[0][cc];
+    // merge the eight waves pairwise through LDS: (4..7 -> 0..3), (2,3 -> 0,1), (1 -> 0)
 #pragma unroll
-        for (int ww = 1; ww < kAttnWaves; ++ww) M = fmaxf(M, m_lds[ww][cc]);
-        float wgt[kAttnWaves], L = 0.f;
+    for (int span = kAttnWaves / 2; span >= 1; span >>= 1) {
+      if (w >= span && w < 2 * span) {
 #pragma unroll
-        for (int ww = 0; ww < kAttnWaves; ++ww) {
-          const float mw = m_lds[ww][cc];
-          wgt[ww] = (mw == -INFINITY) ? 0.f : expf(mw - M);
-          L += l_lds[ww][cc] * wgt[ww];
-        }
-        const int hq = kvh * group + row / m, rq = row % m;
-        float* dst = part + (((size_t)hq * m + rq) * nsplit + split) * (HD + 2);
-#pragma unroll
-        for (int x = 0; x < HD / 16; ++x) {
-          const int e = seg * (HD / 16) + x;
-          float acc = 0.f;
-#pragma unroll
-          for (int ww = 0; ww < kAttnWaves; ++ww) acc += o_lds[ww][cc][e] * wgt[ww];
-          dst[e] = acc;
-        }
-        if (seg == 0) {
-          dst[HD] = M;
-          dst[HD + 1] = L;
+        for (int j = 0; j < HT; ++j) *(f32x4*)&o_lds[w - span][c][j * 16 + g * 4] = o[j];
+        if (g == 0) {
+          m_lds[w - span][c] = m_run;
+          l_lds[w - span][c] = l_run;
         }
       }
+      __syncthreads();
+      if (w < span) {
+        const float mp = m_lds[w][c], lp = l_lds[w][c];
+        const float nm = fmaxf(m_run, mp);
+        const float so = (m_run == -INFINITY) ? 0.f : expf(m_run - nm);
+        const float sp = (mp == -INFINITY) ? 0.f : expf(mp - nm);
+        l_run = l_run * so + lp * sp;
+        m_run = nm;
+#pragma unroll
+        for (int j = 0; j < HT; ++j) {
+          const f32x4 op = *(const f32x4*)&o_lds[w][c][j * 16 + g * 4];
+          o[j] = o[j] * so + op * sp;
+        }
+      }
+      __syncthreads();
     }
-    __syncthreads();
+    if (w == 0 && row_ok) {
+      float* dst = part + (((size_t)head * m + r) * nsplit + split) * (HD + kPartPad);
+#pragma unroll
+      for (int j = 0; j < HT; ++j) *(f32x4*)(dst + j * 16 + g * 4) = o[j];
+      if (g == 0) *(f32x4*)(dst + HD) = f32x4{m_run, l_run, 0.f, 0.f};
+    }
   }
 }
 
+
+// Merge the splits of one (row, head) for the bf16 path: one thread per 8 consecutive elements, all
+// of a batch's loads issued before any is used; the result is written packed for the O projection.
+__global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* __restrict__ part, int m, int n_q_heads,
+                                                              int h, int nsplit, uint4* outp) {
+  constexpr int BATCH = 9;
+  const int segs = h / 8;
+  const int gt = blockIdx.x * blockDim.x + threadIdx.x;
+  const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
+  if (pair >= m * n_q_heads) return;
+  const int head = pair / m, r = pair % m;
+  const float* p = part + (size_t)pair * nsplit * (h + kPartPad);
+  float M = -INFINITY, L = 0.f, acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int s0 = 0; s0 < nsplit; s0 += BATCH) {
+    f32x4 ml[BATCH], oa[BATCH], ob[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const float* ps = p + (size_t)min(s0 + j, nsplit - 1) * (h + kPartPad);
+      ml[j] = *(const f32x4*)(ps + h);
+      oa[j] = *(const f32x4*)(ps + e0);
+      ob[j] = *(const f32x4*)(ps + e0 + 4);
+    }
+    float bm = M;
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j)
+      if (s0 + j < nsplit) bm = fmaxf(bm, ml[j][0]);
+    if (bm == -INFINITY) continue;
+    const float so = (M == -INFINITY) ? 0.f : expf(M - bm);
+    L *= so;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= so;
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const float wgt = (s0 + j < nsplit && ml[j][0] != -INFINITY) ? expf(ml[j][0] - bm) : 0.f;
+      L += ml[j][1] * wgt;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[i] += oa[j][i] * wgt;
+        acc[i + 4] += ob[j][i] * wgt;
+      }
+    }
+    M = bm;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] /= L;
+  store_act8(outp, r, head * h + e0, acc);
+}
+
 // merge the splits of one (row, head): o = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s, splits taken
-// in index order.  h/8 threads per (row, head), 8 consecutive elements each; the result goes out as
-// fp32 or, for the next GEMM, packed (ActPack).
-template <bool PACKED>
+// in index order.  h/8 threads per (row, head), 8 consecutive elements each (fp32 cache path).
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ part, int m, int n_q_heads, int h,
-                                                           int nsplit, float* __restrict__ out, uint4* outp) {
+                                                           int nsplit, float* __restrict__ out) {
   const int tpp = h / 8;  // threads per pair
   const int gt = blockIdx.x * blockDim.x + threadIdx.x;
   const int pair = gt / tpp, e0 = (gt % tpp) * 8;  // pair = head * m + r
   if (pair >= m * n_q_heads) return;
   const int head = pair / m, r = pair % m;
-  const float* p = part + (size_t)pair * nsplit * (h + 2);
+  const float* p = part + (size_t)pair * nsplit * (h + kPartPad);
   float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[(size_t)s * (h + 2) + h]);
+  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[(size_t)s * (h + kPartPad) + h]);
   float L = 0.f, acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   for (int s = 0; s < nsplit; ++s) {
-    const float* ps = p + (size_t)s * (h + 2);
+    const float* ps = p + (size_t)s * (h + kPartPad);
     const float ms = ps[h];
     if (ms == -INFINITY) continue;
     const float wgt = expf(ms - M);
@@ -297,12 +343,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restri
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] /= L;
-  if (PACKED) {
-    store_act8(outp, r, head * h + e0, acc);
-  } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) out[((size_t)r * n_q_heads + head) * h + e0 + i] = acc[i];
-  }
+  for (int i = 0; i < 8; ++i) out[((size_t)r * n_q_heads + head) * h + e0 + i] = acc[i];
 }
 
 int attn_nsplit(int total_tokens, int chunk) { return (total_tokens + chunk - 1) / chunk; }
@@ -318,13 +360,13 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     attn_partial_kernel<float><<<grid, kAttnThreads, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads,
                                                                 c.chunk, nsplit, c.part);
   } else {
-    if (c.chunk != kAttnWgTokens) return hipErrorInvalidValue;
-    dim3 grid(c.kv.n_kv_heads, nsplit);
+    const int nsp = attn_nsplit(total, kAttnWgTokens);
+    dim3 grid(c.kv.n_kv_heads, nsp);
     if (h == 128)
-      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, 0, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsplit,
+      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, 0, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
                                                               c.part);
     else if (h == 64)
-      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, 0, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsplit,
+      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, 0, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
                                                              c.part);
     else
       return hipErrorInvalidValue;
@@ -333,11 +375,10 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
   if (e != hipSuccess) return e;
   const int threads = c.m * c.n_q_heads * (h / 8);
   if (c.dtype == PIPESD_F32)
-    attn_combine_kernel<false><<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, c.out,
-                                                                      nullptr);
+    attn_combine_kernel<<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, c.out);
   else
-    attn_combine_kernel<true><<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, nullptr,
-                                                                     (uint4*)c.outp);
+    attn_merge_packed_kernel<<<(threads + 63) / 64, 64, 0, st>>>(c.part, c.m, c.n_q_heads, h,
+                                                                 attn_nsplit(total, kAttnWgTokens), (uint4*)c.outp);
   return hipGetLastError();
 }
 
