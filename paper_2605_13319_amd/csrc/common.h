@@ -50,10 +50,12 @@ __device__ __forceinline__ int64_t v_index(const KvView& kv, int layer, int pos,
 
 // ActPack: activations handed from one kernel to the next GEMM, already in the B-operand layout of
 // the 16x16x32 bf16 MFMA and split into a bf16 hi + lo pair.  For a consumer with K columns the
-// buffer is uint4[K/32][2 row tiles][hi, lo][64 lanes]; lane g*16 + (row % 16) of k-step ks holds
-// columns ks*32 + g*8 .. +7 of row (row tile)*16 + row % 16.
-__device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int lane) {
-  return (((size_t)kstep * 2 + mt) * 2 + hl) * 64 + lane;
+// buffer is uint4[K/32][2 row tiles][hi, lo][16 rows][4 column groups]: entry (c, g) of k-step ks
+// holds columns ks*32 + g*8 .. +7 of row (row tile)*16 + c and is what MFMA lane g*16 + c consumes.
+// A row's 64 bytes are contiguous, so a pass with m < 16 rows touches only the first m*64 bytes of
+// each 1 KB fragment.
+__device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int c, int g) {
+  return (((size_t)kstep * 2 + mt) * 2 + hl) * 64 + c * 4 + g;
 }
 inline size_t act_pack_bytes(int K) { return (size_t)(K / 32) * 2 * 2 * 64 * 16; }
 
@@ -68,9 +70,9 @@ __device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const fl
     h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
     l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
   }
-  const int lane = ((k0 & 31) >> 3) * 16 + (row & 15);
-  buf[act_index(k0 >> 5, row >> 4, 0, lane)] = make_uint4(h[0], h[1], h[2], h[3]);
-  buf[act_index(k0 >> 5, row >> 4, 1, lane)] = make_uint4(l[0], l[1], l[2], l[3]);
+  const int g = (k0 & 31) >> 3, c = row & 15;
+  buf[act_index(k0 >> 5, row >> 4, 0, c, g)] = make_uint4(h[0], h[1], h[2], h[3]);
+  buf[act_index(k0 >> 5, row >> 4, 1, c, g)] = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // ---------------------------------------------------------------------------------------------

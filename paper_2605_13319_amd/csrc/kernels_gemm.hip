@@ -82,97 +82,108 @@ __device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bh
   }
 }
 
-// finish one (n-tile t, activation row `row`): v[i] is the dot product with weight row i of the tile
-__device__ __forceinline__ void epilogue_column(const GemmArgs& a, int t, int row, const float (&v)[16], float rstd) {
+__device__ __forceinline__ f32x4 shfl4(f32x4 v, int src) {
+  return f32x4{__shfl(v[0], src, 64), __shfl(v[1], src, 64), __shfl(v[2], src, 64), __shfl(v[3], src, 64)};
+}
+
+// Finish one n-tile with a whole wave: lane (gg = lane/16, cc = lane%16) holds the dot products of
+// activation row `row` with weight rows gg*4 .. gg*4+3 of tile t.  Partner rows (i, i+8) sit 32 lanes
+// apart and the two halves of an 8-column group 16 lanes apart, so pairs are joined by shuffles.
+// Every lane of the wave must call this (rows beyond the pass only skip the stores).
+__device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row, int lane, f32x4 v, float rstd) {
+  const int gg = lane >> 4;
+  const bool live = row < a.m;
   switch (a.epi) {
     case EPI_STORE: {
-      float* o = a.out + (size_t)row * a.ldo + t * 16;
+      if (!live) break;
+      float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
       if (t * 16 + 16 <= a.N && (a.ldo & 3) == 0) {
-#pragma unroll
-        for (int i = 0; i < 16; i += 4)
-          *(float4*)(o + i) = make_float4(v[i] * rstd, v[i + 1] * rstd, v[i + 2] * rstd, v[i + 3] * rstd);
+        *(float4*)o = make_float4(v[0] * rstd, v[1] * rstd, v[2] * rstd, v[3] * rstd);
       } else {
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (t * 16 + i < a.N) o[i] = v[i] * rstd;
+        for (int i = 0; i < 4; ++i)
+          if (t * 16 + gg * 4 + i < a.N) o[i] = v[i] * rstd;
       }
       break;
     }
     case EPI_RESID: {
-      float* o = a.out + (size_t)row * a.ldo + t * 16;
-      float x[16], sq = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; i += 4) {
-        const float4 old = *(const float4*)(o + i);
-        x[i] = old.x + v[i]; x[i + 1] = old.y + v[i + 1]; x[i + 2] = old.z + v[i + 2]; x[i + 3] = old.w + v[i + 3];
-        *(float4*)(o + i) = make_float4(x[i], x[i + 1], x[i + 2], x[i + 3]);
+      float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
+      f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        const float4 old = *(const float4*)o;
+        x = f32x4{old.x + v[0], old.y + v[1], old.z + v[2], old.w + v[3]};
+        *(float4*)o = make_float4(x[0], x[1], x[2], x[3]);
       }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sq = fmaf(x[i], x[i], sq);
-      a.ssq_out[(size_t)row * a.ssq_stride + t] = sq;
-      const float* gn = a.gain_next + t * 16;
-      float y0[8], y1[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        y0[i] = x[i] * gn[i];
-        y1[i] = x[i + 8] * gn[i + 8];
+      float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+      sq += __shfl_xor(sq, 16, 64);
+      sq += __shfl_xor(sq, 32, 64);
+      const float4 gn = *(const float4*)(a.gain_next + t * 16 + gg * 4);
+      const f32x4 y = f32x4{x[0] * gn.x, x[1] * gn.y, x[2] * gn.z, x[3] * gn.w};
+      const f32x4 hi4 = shfl4(y, lane + 16);  // columns +4..+7 of the 8-column group
+      if (live && (gg & 1) == 0) {
+        const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        store_act8((uint4*)a.outp, row, t * 16 + gg * 4, y8);
+        if (gg == 0) a.ssq_out[(size_t)row * a.ssq_stride + t] = sq;
       }
-      store_act8((uint4*)a.outp, row, t * 16, y0);
-      store_act8((uint4*)a.outp, row, t * 16 + 8, y1);
       break;
     }
     case EPI_SWIGLU: {
-      float y[8];
+      const f32x4 up = shfl4(v, lane + 32);
+      f32x4 y;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float gt = v[i] * rstd, up = v[i + 8] * rstd;
-        y[i] = (gt / (1.0f + expf(-gt))) * up;
+      for (int i = 0; i < 4; ++i) {
+        const float gt = v[i] * rstd;
+        y[i] = (gt / (1.0f + expf(-gt))) * (up[i] * rstd);
       }
-      store_act8((uint4*)a.outp, row, t * 8, y);
+      const f32x4 hi4 = shfl4(y, lane + 16);
+      if (live && gg == 0) {
+        const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        store_act8((uint4*)a.outp, row, t * 8, y8);
+      }
       break;
     }
     case EPI_QKV: {
+      const f32x4 x1 = shfl4(v, lane + 32);
+      if (!live || gg >= 2) break;
       const int h = a.kv.head_dim, half = h >> 1, hpt = h >> 4;
-      const int hd = t / hpt, i0 = (t % hpt) * 8;
-      float r0[8], r1[8];
+      const int hd = t / hpt, i0 = (t % hpt) * 8 + gg * 4;
+      float r0[4], r1[4];
       if (hd < a.n_q_heads + a.kv.n_kv_heads) {
         const float* cs = a.rope_cs + ((size_t)row * half + i0) * 2;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float x0 = v[i] * rstd, x1 = v[i + 8] * rstd, c = cs[2 * i], s = cs[2 * i + 1];
-          r0[i] = x0 * c - x1 * s;
-          r1[i] = x1 * c + x0 * s;
+        for (int i = 0; i < 4; ++i) {
+          const float p0 = v[i] * rstd, p1 = x1[i] * rstd, c = cs[2 * i], sn = cs[2 * i + 1];
+          r0[i] = p0 * c - p1 * sn;
+          r1[i] = p1 * c + p0 * sn;
         }
       } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 4; ++i) {
           r0[i] = v[i] * rstd;
-          r1[i] = v[i + 8] * rstd;
+          r1[i] = x1[i] * rstd;
         }
       }
       if (hd < a.n_q_heads) {
         float* o = a.out + (size_t)row * a.ldo + hd * h + i0;
         *(float4*)o = make_float4(r0[0], r0[1], r0[2], r0[3]);
-        *(float4*)(o + 4) = make_float4(r0[4], r0[5], r0[6], r0[7]);
         *(float4*)(o + half) = make_float4(r1[0], r1[1], r1[2], r1[3]);
-        *(float4*)(o + half + 4) = make_float4(r1[4], r1[5], r1[6], r1[7]);
       } else {
         uint16_t* pool = (uint16_t*)a.kv.pool;
         const int pos = a.start_pos + row;
         if (hd < a.n_q_heads + a.kv.n_kv_heads) {
           const int kvh = hd - a.n_q_heads;
-          uint16_t b0[8], b1[8];
+          uint16_t b0[4], b1[4];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+          for (int i = 0; i < 4; ++i) {
             b0[i] = f32_to_bf16_bits(r0[i]);
             b1[i] = f32_to_bf16_bits(r1[i]);
           }
-          *(uint4*)(pool + k_index(a.kv, a.layer, pos, kvh, i0)) = *(const uint4*)b0;
-          *(uint4*)(pool + k_index(a.kv, a.layer, pos, kvh, i0 + half)) = *(const uint4*)b1;
+          *(uint2*)(pool + k_index(a.kv, a.layer, pos, kvh, i0)) = *(const uint2*)b0;
+          *(uint2*)(pool + k_index(a.kv, a.layer, pos, kvh, i0 + half)) = *(const uint2*)b1;
         } else {
           const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+          for (int i = 0; i < 4; ++i) {
             pool[v_index(a.kv, a.layer, pos, kvh, i0 + i)] = f32_to_bf16_bits(r0[i]);
             pool[v_index(a.kv, a.layer, pos, kvh, i0 + half + i)] = f32_to_bf16_bits(r1[i]);
           }
@@ -214,14 +225,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
 
   // activation fragments of the current K slice; loaded by hand too and awaited in full (they and the
   // first weight chunk are all needed before the first MFMA)
+  // (lanes whose row is not part of the pass load nothing: their MFMA columns are never stored)
   u32x4 bhi[MT][KSTEPS], blo[MT][KSTEPS];
+  const int bc = lane & 15, bg = lane >> 4;
   auto load_act = [&](int slice) {
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        bhi[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 0, lane));
-        blo[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 1, lane));
+        if (mt * 16 + bc < a.m) {
+          bhi[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 0, bc, bg));
+          blo[mt][ks] = cached_load(a.actp + act_index(slice * KSTEPS + ks, mt, 1, bc, bg));
+        }
       }
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
@@ -271,25 +286,15 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
       }
     }
     __syncthreads();
-    // one thread per (tile, activation row): add the W partial columns and finish
-    const int ncols = nt_g * MT * 16;
-    for (int e = tid; e < ncols; e += nthreads) {
-      const int tt = e / (MT * 16), rem = e % (MT * 16), mt = rem >> 4, cc = rem & 15;
-      const int row = mt * 16 + cc;
-      if (row >= a.m) continue;
-      float v[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] = 0.f;
-      for (int ww = 0; ww < a.W; ++ww) {
-        const f32x4* rp = red + ((size_t)(tt * a.W + ww) * MT + mt) * 64 + cc;
-#pragma unroll
-        for (int gg = 0; gg < 4; ++gg) {
-          const f32x4 x = rp[gg * 16];  // weight rows gg*4 .. gg*4+3
-          v[gg * 4 + 0] += x[0]; v[gg * 4 + 1] += x[1]; v[gg * 4 + 2] += x[2]; v[gg * 4 + 3] += x[3];
-        }
-      }
-      const float rstd = a.ssq_in != nullptr ? rstd_lds[row] : 1.0f;
-      epilogue_column(a, t0 + tt, row, v, rstd);
+    // one lane per 4 tile rows x 1 activation row: add the W partial tiles, then finish with the wave
+    const int nquads = nt_g * MT * 64;
+    for (int e = tid; e < nquads; e += nthreads) {
+      const int tt = e / (MT * 64), rem = e % (MT * 64), mt = rem >> 6, l = rem & 63;
+      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int ww = 0; ww < a.W; ++ww) v += red[((size_t)(tt * a.W + ww) * MT + mt) * 64 + l];
+      const int row = mt * 16 + (l & 15);
+      const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[row] : 1.0f;
+      epilogue_quad(a, t0 + tt, row, l, v, rstd);
     }
     __syncthreads();  // red is free again
   }
