@@ -1,0 +1,437 @@
+// Device code of the skinny bf16 GEMM, shared by the per-GEMM kernel and the fused layer kernel.
+//
+// y[m][N] = act[m][K] * W[N][K]^T with m = k + 1 <= 32 rows (the QKV / O / SwiGLU-FFN / LM-head
+// products of the target forward, Sec. 2.2).  The pass is bound by streaming W once from HBM, so
+// everything is arranged around that stream:
+//  * W is re-tiled once, at model creation, into the order the matrix cores consume it: tile
+//    (n-tile of 16 weight rows, k-step of 32 columns) is 1 KB, lane l holding row l%16, columns
+//    8*(l/16)..+7.  A wave's load instruction then reads 1 KB contiguous and the data lands directly
+//    in MFMA operand registers: no LDS pass, no barrier in the main loop.
+//  * W is the A operand (16 weight rows x 32 k), the activations are the B operand (32 k x 16 rows).
+//    Activations travel between kernels already in B-operand layout as a bf16 hi + lo pair (ActPack
+//    in common.h): the producing epilogue splits each value once, every consuming wave just loads
+//    registers.  Two MFMAs per weight fragment keep 16 significand bits of the activations; the
+//    matrix cores idle otherwise.
+//  * K is cut into W * P slices of KSTEPS*32 columns; a team of W waves takes slices p*W + w,
+//    p = 0..P-1, one phase after the other, for a group of tg n-tiles, each wave keeping its running
+//    16x16 sums in its own LDS slots; after the last phase the team adds them in a fixed order.
+//    Nothing crosses teams: no global partials, no floating-point atomics; results are
+//    bit-reproducible and independent of how groups are dealt to teams.
+//  * RMSNorm is fused: the producer stores x * gain and per-tile sums of x^2; the consumer scales the
+//    finished tile by rstd per row.
+//  * Epilogues: plain store (logits), residual add (+ packed, gained copy for the next GEMM),
+//    SiLU(gate)*up (packed), or rotary + query buffer / paged KV-cache append.  Rows 8..15 of a
+//    weight tile are the partners of rows 0..7 (other half of the head for the rotary pair; the
+//    up-projection row for a gate row) so a pair is finished inside one wave.
+//
+// CO ("coherent") selects how activations cross workgroups.  false: plain loads and stores; the
+// kernel boundary makes them visible.  true: inside one long-running kernel, every such store is
+// written through (sc1) and every such load fetched past the chiplet's L2 (sc1), ordered by a
+// device-wide barrier; weights, gains and rotary tables are immutable and always read plainly.
+#pragma once
+
+#include "common.h"
+
+namespace pipesd {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+struct GemmArgs {
+  const u32x4* wp;
+  const u32x4* actp;      // packed activations (ActPack, K columns)
+  const float* ssq_in;    // fused norm: [row][ssq_stride] partial sums of x^2, or nullptr
+  int ssq_parts, ssq_stride;
+  float* out;             // STORE: logits; RESID: residual stream; QKV: query buffer
+  u32x4* outp;            // RESID / SWIGLU: packed output for the next GEMM
+  const float* gain_next; // RESID: gain applied to the packed copy
+  float* ssq_out;         // RESID: [row][ssq_stride] per-tile sums of x_new^2
+  const float* rope_cs;
+  KvView kv;
+  int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
+  float eps;
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// ---- hand-issued loads -------------------------------------------------------------------------
+// The weight stream is issued and awaited by hand: the loads are opaque to the compiler's wait-count
+// bookkeeping, and each use is preceded by an explicit s_waitcnt tied to the register it releases.
+// Vector memory loads return in order, so "at most N younger loads outstanding" is exact; the
+// compiler would otherwise join the with-next and without-next paths into vmcnt(0) and drain the
+// pipeline at every chunk.  Stores are never issued by hand without trailing wait states: the
+// hardware reads store data for a few cycles after issue and only the compiler tracks that.
+__device__ __forceinline__ u32x4 stream_load(const u32x4* p) {
+  u32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
+  return v;
+}
+template <bool CO>
+__device__ __forceinline__ u32x4 act_load(const u32x4* p) {
+  u32x4 v;
+  if constexpr (CO)
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p));
+  else
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_younger(u32x4& v) {
+  asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N));
+}
+
+// ---- accesses to data other workgroups wrote or will read -----------------------------------------
+template <bool CO>
+struct Xwg {
+  static __device__ __forceinline__ f32x4 ld4(const float* p) {
+    if constexpr (CO) {
+      f32x4 v;
+      asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+      return v;
+    } else {
+      return *(const f32x4*)p;
+    }
+  }
+  static __device__ __forceinline__ float ld1(const float* p) {
+    if constexpr (CO) {
+      float v;
+      asm volatile("global_load_dword %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+      return v;
+    } else {
+      return *p;
+    }
+  }
+  static __device__ __forceinline__ void st4(void* p, u32x4 v) {
+    if constexpr (CO)
+      asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
+    else
+      *(u32x4*)p = v;
+  }
+  static __device__ __forceinline__ void st4f(float* p, f32x4 v) { st4(p, __builtin_bit_cast(u32x4, v)); }
+  static __device__ __forceinline__ void st2(void* p, u32x2 v) {
+    if constexpr (CO)
+      asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
+    else
+      *(u32x2*)p = v;
+  }
+  static __device__ __forceinline__ void st1(float* p, float v) {
+    if constexpr (CO)
+      asm volatile("global_store_dword %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
+    else
+      *p = v;
+  }
+  static __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
+    if constexpr (CO) {
+      const unsigned w = v;
+      asm volatile("global_store_short %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(w) : "memory");
+    } else {
+      *p = v;
+    }
+  }
+  // all of this thread's stores have been acknowledged (call before signalling other workgroups)
+  static __device__ __forceinline__ void drain() {
+    if constexpr (CO) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+};
+
+// split 8 consecutive columns k0..k0+7 (k0 % 8 == 0) of `row` into hi + lo and store them (ActPack)
+template <bool CO>
+__device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const float (&v)[8]) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
+    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
+    h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+  }
+  const int g = (k0 & 31) >> 3, c = row & 15;
+  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 0, c, g), u32x4{h[0], h[1], h[2], h[3]});
+  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 1, c, g), u32x4{l[0], l[1], l[2], l[3]});
+}
+
+// one chunk = KSTEPS weight fragments of one n-tile against this wave's activation fragments; while
+// fragment ks is multiplied, fragment ks of the next chunk is requested into the same registers
+template <int MT, int KSTEPS, bool HAS_NEXT, int KS = 0>
+__device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bhi)[MT][KSTEPS],
+                                           const u32x4 (&blo)[MT][KSTEPS], f32x4 (&acc)[MT], const u32x4* nxt) {
+  if constexpr (KS < KSTEPS) {
+    wait_younger<HAS_NEXT ? KSTEPS - 1 : KSTEPS - 1 - KS>(af[KS]);
+    const bf16x8 av = as_bf16x8(af[KS]);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bhi[mt][KS]), acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(blo[mt][KS]), acc[mt], 0, 0, 0);
+    }
+    if constexpr (HAS_NEXT) af[KS] = stream_load(nxt + KS * 64);
+    chunk_mfma<MT, KSTEPS, HAS_NEXT, KS + 1>(af, bhi, blo, acc, nxt);
+  }
+}
+
+__device__ __forceinline__ f32x4 shfl4(f32x4 v, int src) {
+  return f32x4{__shfl(v[0], src, 64), __shfl(v[1], src, 64), __shfl(v[2], src, 64), __shfl(v[3], src, 64)};
+}
+
+// Finish one n-tile with a whole wave: lane (gg = lane/16, cc = lane%16) holds the dot products of
+// activation row `row` with weight rows gg*4 .. gg*4+3 of tile t.  Partner rows (i, i+8) sit 32 lanes
+// apart and the two halves of an 8-column group 16 lanes apart, so pairs are joined by shuffles.
+// Every lane of the wave must call this (rows beyond the pass only skip the stores).
+template <bool CO>
+__device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row, int lane, f32x4 v, float rstd) {
+  const int gg = lane >> 4;
+  const bool live = row < a.m;
+  switch (a.epi) {
+    case EPI_STORE: {  // logits: read by later kernels only
+      if (!live) break;
+      float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
+      if (t * 16 + 16 <= a.N && (a.ldo & 3) == 0) {
+        *(float4*)o = make_float4(v[0] * rstd, v[1] * rstd, v[2] * rstd, v[3] * rstd);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (t * 16 + gg * 4 + i < a.N) o[i] = v[i] * rstd;
+      }
+      break;
+    }
+    case EPI_RESID: {
+      float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
+      f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (live) {
+        const f32x4 old = Xwg<CO>::ld4(o);
+        x = old + v;
+        Xwg<CO>::st4f(o, x);
+      }
+      float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
+      sq += __shfl_xor(sq, 16, 64);
+      sq += __shfl_xor(sq, 32, 64);
+      const float4 gn = *(const float4*)(a.gain_next + t * 16 + gg * 4);
+      const f32x4 y = f32x4{x[0] * gn.x, x[1] * gn.y, x[2] * gn.z, x[3] * gn.w};
+      const f32x4 hi4 = shfl4(y, lane + 16);  // columns +4..+7 of the 8-column group
+      if (live && (gg & 1) == 0) {
+        const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        store_act8x<CO>(a.outp, row, t * 16 + gg * 4, y8);
+        if (gg == 0) Xwg<CO>::st1(a.ssq_out + (size_t)row * a.ssq_stride + t, sq);
+      }
+      break;
+    }
+    case EPI_SWIGLU: {
+      const f32x4 up = shfl4(v, lane + 32);
+      f32x4 y;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float gt = v[i] * rstd;
+        y[i] = (gt / (1.0f + expf(-gt))) * (up[i] * rstd);
+      }
+      const f32x4 hi4 = shfl4(y, lane + 16);
+      if (live && gg == 0) {
+        const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        store_act8x<CO>(a.outp, row, t * 8, y8);
+      }
+      break;
+    }
+    case EPI_QKV: {
+      const f32x4 x1 = shfl4(v, lane + 32);
+      if (!live || gg >= 2) break;
+      const int h = a.kv.head_dim, half = h >> 1, hpt = h >> 4;
+      const int hd = t / hpt, i0 = (t % hpt) * 8 + gg * 4;
+      f32x4 r0, r1;
+      if (hd < a.n_q_heads + a.kv.n_kv_heads) {
+        const float* cs = a.rope_cs + ((size_t)row * half + i0) * 2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float p0 = v[i] * rstd, p1 = x1[i] * rstd, c = cs[2 * i], sn = cs[2 * i + 1];
+          r0[i] = p0 * c - p1 * sn;
+          r1[i] = p1 * c + p0 * sn;
+        }
+      } else {
+        r0 = v * rstd;
+        r1 = x1 * rstd;
+      }
+      if (hd < a.n_q_heads) {
+        float* o = a.out + (size_t)row * a.ldo + hd * h + i0;
+        Xwg<CO>::st4f(o, r0);
+        Xwg<CO>::st4f(o + half, r1);
+      } else {
+        uint16_t* pool = (uint16_t*)a.kv.pool;
+        const int pos = a.start_pos + row;
+        uint16_t b0[4], b1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          b0[i] = f32_to_bf16_bits(r0[i]);
+          b1[i] = f32_to_bf16_bits(r1[i]);
+        }
+        if (hd < a.n_q_heads + a.kv.n_kv_heads) {
+          const int kvh = hd - a.n_q_heads;
+          Xwg<CO>::st2(pool + k_index(a.kv, a.layer, pos, kvh, i0),
+                       u32x2{(unsigned)b0[0] | ((unsigned)b0[1] << 16), (unsigned)b0[2] | ((unsigned)b0[3] << 16)});
+          Xwg<CO>::st2(pool + k_index(a.kv, a.layer, pos, kvh, i0 + half),
+                       u32x2{(unsigned)b1[0] | ((unsigned)b1[1] << 16), (unsigned)b1[2] | ((unsigned)b1[3] << 16)});
+        } else {
+          const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            Xwg<CO>::st_u16(pool + v_index(a.kv, a.layer, pos, kvh, i0 + i), b0[i]);
+            Xwg<CO>::st_u16(pool + v_index(a.kv, a.layer, pos, kvh, i0 + half + i), b1[i]);
+          }
+        }
+      }
+      break;
+    }
+  }
+}
+
+// A team = W consecutive waves of a workgroup.  `team` / `nteams` number the teams over the whole
+// grid, `wt` is the wave's index in its team (waves with active == false belong to no team but must
+// still take part in the workgroup barriers), `tl` the team's index inside the workgroup (selects
+// its LDS area), `nwaves_wg` the workgroup's wave count.
+struct TeamPos {
+  int team, nteams, wt, tl;
+  bool active;
+};
+
+template <int KSTEPS>
+__device__ __forceinline__ const u32x4* gemm_chunk_ptr(const GemmArgs& a, int lane, int wt, int tile, int p) {
+  return a.wp + lane + ((size_t)tile * a.kst + (size_t)(p * a.W + wt) * KSTEPS) * 64;
+}
+
+// request the first weight chunk of this wave (it does not depend on the activations, so it can be
+// issued before whatever still separates the wave from the GEMM: a prologue, or a device-wide barrier)
+template <int KSTEPS>
+__device__ __forceinline__ void gemm_prefetch(const GemmArgs& a, const TeamPos& tp, int lane, u32x4 (&af)[KSTEPS]) {
+  const int ngroups = (a.ntiles + a.tg - 1) / a.tg;
+  if (!tp.active || tp.team >= ngroups) return;
+  const u32x4* first = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, tp.team * a.tg, 0);
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load(first + ks * 64);
+}
+
+// floats of LDS one workgroup needs: reduce slots of all its teams + rstd per row
+__host__ __device__ inline size_t gemm_lds_floats(int tg, int W, int MT, int teams_per_wg) {
+  return (size_t)teams_per_wg * tg * W * MT * 64 * 4 + 32;
+}
+
+// The GEMM proper.  `af` must hold the in-flight first chunk (gemm_prefetch).  All waves of the
+// workgroup must call this together (it contains workgroup barriers).
+template <int MT, int KSTEPS, bool CO>
+__device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, int teams_per_wg, int nwaves_wg,
+                                          float* lds, u32x4 (&af)[KSTEPS]) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  f32x4* red = (f32x4*)lds + (size_t)tp.tl * a.tg * a.W * MT * 64;        // [tg][W][MT][64]
+  float* rstd_lds = lds + (size_t)teams_per_wg * a.tg * a.W * MT * 64 * 4;  // [MT*16]
+  const int ngroups = (a.ntiles + a.tg - 1) / a.tg;
+  const int iters = (ngroups + tp.nteams - 1) / tp.nteams;
+  const int bc = lane & 15, bg = lane >> 4;
+
+  // activation fragments of the current K slice, awaited in full (they and the first weight chunk
+  // are all needed before the first MFMA); lanes whose row is not part of the pass load nothing:
+  // their MFMA columns are never stored
+  u32x4 bhi[MT][KSTEPS], blo[MT][KSTEPS];
+  auto load_act = [&](int slice) {
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        if (mt * 16 + bc < a.m) {
+          bhi[mt][ks] = act_load<CO>(a.actp + act_index(slice * KSTEPS + ks, mt, 0, bc, bg));
+          blo[mt][ks] = act_load<CO>(a.actp + act_index(slice * KSTEPS + ks, mt, 1, bc, bg));
+        }
+      }
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        wait_younger<0>(bhi[mt][ks]);
+        wait_younger<0>(blo[mt][ks]);
+      }
+  };
+  const bool working = tp.active && tp.team < ngroups;
+  if (working && a.P == 1) load_act(tp.wt);
+
+  // fused norm: rstd per row from the producer's partial sums of squares, added in index order
+  if (a.ssq_in != nullptr) {
+    if constexpr (CO) {
+      // 8 waves; wave w takes rows w and w + 8; up to 4 partial sums per lane and row (the host
+      // checks ssq_parts <= 256), all requested before any is used
+      float part[2][4];
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+        for (int j4 = 0; j4 < 4; ++j4) {
+          const int row = w + 8 * r2, j = lane + 64 * j4;
+          part[r2][j4] = 0.f;
+          if (row < MT * 16 && row < a.m && j < a.ssq_parts)
+            asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[r2][j4])
+                         : "v"(a.ssq_in + (size_t)row * a.ssq_stride + j));
+        }
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+        for (int j4 = 0; j4 < 4; ++j4) asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[r2][j4]));
+#pragma unroll
+      for (int r2 = 0; r2 < 2; ++r2) {
+        const int row = w + 8 * r2;
+        float q = (part[r2][0] + part[r2][1]) + (part[r2][2] + part[r2][3]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        if (lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+      }
+    } else {
+      for (int row = w; row < MT * 16; row += nwaves_wg) {
+        float q = 0.f;
+        if (row < a.m)
+          for (int j = lane; j < a.ssq_parts; j += 64) q += a.ssq_in[(size_t)row * a.ssq_stride + j];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        if (lane == 0) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+      }
+    }
+  }
+
+  for (int it = 0; it < iters; ++it) {
+    const int grp = tp.team + it * tp.nteams;
+    const bool on = tp.active && grp < ngroups;
+    const int t0 = grp * a.tg;
+    const int nt_g = on ? min(a.tg, a.ntiles - t0) : 0;
+    if (on) {
+      for (int p = 0; p < a.P; ++p) {
+        if (a.P > 1) load_act(p * a.W + tp.wt);
+        for (int t = 0; t < nt_g; ++t) {
+          const u32x4* nxt = nullptr;
+          if (t + 1 < nt_g) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0 + t + 1, p);
+          else if (p + 1 < a.P) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0, p + 1);
+          else if (grp + tp.nteams < ngroups) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, (grp + tp.nteams) * a.tg, 0);
+          f32x4 acc[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (nxt != nullptr)
+            chunk_mfma<MT, KSTEPS, true>(af, bhi, blo, acc, nxt);
+          else
+            chunk_mfma<MT, KSTEPS, false>(af, bhi, blo, acc, nxt);
+          // this wave's running sum over its phases lives in its own LDS slot
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            f32x4* slot = red + ((size_t)(t * a.W + tp.wt) * MT + mt) * 64 + lane;
+            *slot = (p == 0) ? acc[mt] : (*slot + acc[mt]);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // one lane per 4 tile rows x 1 activation row: add the W partial tiles, then finish with the wave
+    if (on) {
+      const int nquads = nt_g * MT * 64;
+      for (int e = tp.wt * 64 + lane; e < nquads; e += a.W * 64) {
+        const int tt = e / (MT * 64), rem = e % (MT * 64), mt = rem >> 6, l = rem & 63;
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ww = 0; ww < a.W; ++ww) v += red[((size_t)(tt * a.W + ww) * MT + mt) * 64 + l];
+        const int row = mt * 16 + (l & 15);
+        const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[row] : 1.0f;
+        epilogue_quad<CO>(a, t0 + tt, row, l, v, rstd);
+      }
+    }
+    __syncthreads();  // red is free again
+  }
+}
+
+}  // namespace pipesd
