@@ -160,12 +160,22 @@ int pipesd_spec_accept(const float *p, const float *q, const int32_t *draft_toke
 int pipesd_kv_read(const pipesd_model *model, const pipesd_kv *kv, int32_t seq, int32_t layer,
                    int32_t pos, float *k_out, float *v_out);
 
+/* Launch strategy of the layer stack.  By default every projection and every attention step is a
+ * kernel launch of its own.  After pipesd_model_set_fused(model, 1) a bf16 pass of up to 16 rows
+ * runs all decoder layers in ONE cooperative kernel instead (device-wide barriers between the
+ * projections, weights requested ahead of each barrier); passes it does not take keep the per-
+ * projection launches.  Both run the same device code on the same tiles in the same order and give
+ * bit-identical results.  pipesd_model_fused_launches counts the fused launches so far.
+ * PIPESD_PROF_GEMM_* classes time nothing while the fused kernel is in use (PIPESD_PROF_LAYERS does). */
+int pipesd_model_set_fused(pipesd_model *model, int32_t on);
+int pipesd_model_fused_launches(const pipesd_model *model, int64_t *n);
+
 /* Per-kernel timing for roofline accounting: when enabled, every launch of the selected kernel
  * class is bracketed by HIP events on its stream.  pipesd_profile_read waits for them and returns
  * the number of launches and their summed duration since the last read. */
 enum { PIPESD_PROF_OFF = 0, PIPESD_PROF_GEMM_QKV = 1, PIPESD_PROF_GEMM_O = 2, PIPESD_PROF_GEMM_GATEUP = 3,
        PIPESD_PROF_GEMM_DOWN = 4, PIPESD_PROF_GEMM_LMHEAD = 5, PIPESD_PROF_ATTN = 6, PIPESD_PROF_VERIFY = 7,
-       PIPESD_PROF_ALL_GEMM = 8 };
+       PIPESD_PROF_ALL_GEMM = 8, PIPESD_PROF_LAYERS = 9 };
 int pipesd_profile_select(pipesd_model *model, int32_t kernel_class);
 int pipesd_profile_read(pipesd_model *model, int32_t *n_launches, double *total_ms);
 

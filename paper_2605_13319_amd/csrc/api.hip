@@ -57,6 +57,11 @@ struct pipesd_model {
   int32_t* result_dev = nullptr;
   int32_t* result_host = nullptr;  // pinned
   std::vector<void*> owned;
+  // fused layer kernel (bf16, passes of up to 16 rows)
+  void* layer_weights_dev = nullptr;
+  unsigned* bar = nullptr;
+  bool fused_enabled = false;  // opt-in until it beats the per-projection launches
+  int64_t fused_launches = 0;
   // kernel timing
   int prof_class = PIPESD_PROF_OFF;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
@@ -214,6 +219,19 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     HIP_TRY(hipMemset(m->gpk, 0, act_pack_bytes(F)));
     m->ssq_stride = d / 16;
     if ((rc = dev_alloc(m, (void**)&m->ssq, R * m->ssq_stride * 4))) return rc;
+    std::vector<const void*> lw((size_t)L * 6);
+    for (int l = 0; l < L; ++l) {
+      lw[l * 6 + 0] = m->wqkv[l];
+      lw[l * 6 + 1] = m->wo[l];
+      lw[l * 6 + 2] = m->wgu[l];
+      lw[l * 6 + 3] = m->wdown[l];
+      lw[l * 6 + 4] = m->attn_norm[l];
+      lw[l * 6 + 5] = m->ffn_norm[l];
+    }
+    if ((rc = dev_alloc(m, &m->layer_weights_dev, lw.size() * sizeof(void*)))) return rc;
+    HIP_TRY(hipMemcpy(m->layer_weights_dev, lw.data(), lw.size() * sizeof(void*), hipMemcpyHostToDevice));
+    if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
+    HIP_TRY(hipMemset(m->bar, 0, 4096));
   }
   HIP_TRY(hipHostMalloc((void**)&m->result_host, 64, hipHostMallocDefault));
   HIP_TRY(hipDeviceSynchronize());
@@ -362,8 +380,20 @@ extern "C" const char* pipesd_strerror(int status) {
 // ---------------------------------------------------------------------------------------------
 // kernel timing
 // ---------------------------------------------------------------------------------------------
+extern "C" int pipesd_model_set_fused(pipesd_model* model, int32_t on) {
+  if (!model) return PIPESD_EINVAL;
+  model->fused_enabled = on != 0;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_model_fused_launches(const pipesd_model* model, int64_t* n) {
+  if (!model || !n) return PIPESD_EINVAL;
+  *n = model->fused_launches;
+  return PIPESD_OK;
+}
+
 extern "C" int pipesd_profile_select(pipesd_model* model, int32_t kernel_class) {
-  if (!model || kernel_class < PIPESD_PROF_OFF || kernel_class > PIPESD_PROF_ALL_GEMM) return PIPESD_EINVAL;
+  if (!model || kernel_class < PIPESD_PROF_OFF || kernel_class > PIPESD_PROF_LAYERS) return PIPESD_EINVAL;
   model->prof_class = kernel_class;
   model->prof_used = 0;
   return PIPESD_OK;
@@ -489,7 +519,40 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
                             c.dtype == PIPESD_BF16 ? m->attn_norm[0] : nullptr, m->xpk, m->ssq, m->ssq_stride, st));
   int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
-  for (int l = 0; l < c.n_layers; ++l) {
+  bool fused = false;
+  if (c.dtype == PIPESD_BF16 && m->fused_enabled) {
+    LayersCall lc{};
+    lc.layer_weights = m->layer_weights_dev;
+    lc.final_norm = m->final_norm;
+    lc.n_layers = c.n_layers;
+    lc.m = rows;
+    lc.start_pos = start_pos;
+    lc.n_q_heads = c.n_q_heads;
+    lc.head_dim = c.head_dim;
+    lc.d_model = d;
+    lc.q_dim = qd;
+    lc.d_ffn = F;
+    lc.eps = c.rms_eps;
+    lc.kv = view;
+    lc.rope_cs = m->rope_cs;
+    lc.xpk = m->xpk;
+    lc.apk = m->apk;
+    lc.gpk = m->gpk;
+    lc.xres = m->xres;
+    lc.qbuf = m->qbuf;
+    lc.ssq = m->ssq;
+    lc.attn_part = m->attn_part;
+    lc.ssq_stride = m->ssq_stride;
+    lc.bar = m->bar;
+    if (layers_fused_supported(lc)) {
+      ProfScope ps(m, PIPESD_PROF_LAYERS, st);
+      HIP_TRY(launch_layers(lc, st));
+      ++m->fused_launches;
+      fused = true;
+      norm_parts = d / 16;
+    }
+  }
+  for (int l = 0; l < (fused ? 0 : c.n_layers); ++l) {
     AttnCall at{};
     at.dtype = c.dtype;
     at.q = m->qbuf;
@@ -587,6 +650,18 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   return PIPESD_OK;
 }
 
+// The fused layer kernel raises a sticky flag if one of its device-wide barriers timed out.
+static hipError_t read_layers_flag(pipesd_model* m, hipStream_t st) {
+  m->result_host[2] = 0;
+  if (!m->bar) return hipSuccess;
+  return hipMemcpyAsync(m->result_host + 2, m->bar + kLayersErrWord, 4, hipMemcpyDeviceToHost, st);
+}
+static bool layers_flag_raised(pipesd_model* m) {
+  if (m->result_host[2] == 0) return false;
+  (void)hipMemset(m->bar + kLayersErrWord, 0, 4);
+  return true;
+}
+
 static bool compute_ready(const pipesd_model* m, const pipesd_kv* kv) {
   return m && kv && kv->model == m && m->on_device && kv->pool && kv->table_dev;
 }
@@ -680,10 +755,15 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
                                             model->result_dev, st);
   }
   if (e == hipSuccess) e = hipMemcpyAsync(model->result_host, model->result_dev, 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = read_layers_flag(model, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
     release_beyond(kv, s, lp - 1);
     return hip_fail(e, "verify step");
+  }
+  if (layers_flag_raised(model)) {
+    release_beyond(kv, s, lp - 1);
+    return hip_fail(hipErrorLaunchFailure, "device-wide barrier of the fused layer kernel timed out");
   }
   const int32_t a = model->result_host[0], nxt = model->result_host[1];
   if (a < 0 || a > k || nxt < 0 || nxt >= model->cfg.vocab) {
@@ -714,8 +794,11 @@ extern "C" int pipesd_forward_logits(pipesd_model* model, pipesd_kv* kv, int32_t
   if (rc) return rc;
   hipError_t e = hipMemcpyAsync(logits_out, model->logits, (size_t)(n_extra + 1) * model->cfg.vocab * 4,
                                 hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = read_layers_flag(model, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   release_beyond(kv, s, lp - 1);
+  if (e == hipSuccess && layers_flag_raised(model))
+    return hip_fail(hipErrorLaunchFailure, "device-wide barrier of the fused layer kernel timed out");
   return e == hipSuccess ? PIPESD_OK : hip_fail(e, "logits copy");
 }
 

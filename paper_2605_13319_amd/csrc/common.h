@@ -135,6 +135,24 @@ struct PackSrc {
 hipError_t launch_pack_bf16(const PackSrc& s, int n_src, int K, int mode, int pair_span, void* dst, int ntiles,
                             hipStream_t st);
 
+// ---- all decoder layers of a pass in one cooperative kernel (bf16, up to 16 rows) ----
+struct LayersCall {
+  const void* layer_weights;  // device array of per-layer {wqkv, wo, wgu, wdown, attn_norm, ffn_norm} pointers
+  const float* final_norm;
+  int n_layers, m, start_pos, n_q_heads, head_dim, d_model, q_dim, d_ffn;
+  float eps;
+  KvView kv;
+  const float* rope_cs;
+  void *xpk, *apk, *gpk;  // packed activations
+  float *xres, *qbuf, *ssq, *attn_part;
+  int ssq_stride;
+  unsigned* bar;  // >= 4 KB of device memory for the barrier counters and the error flag (last word used:
+                  // bar[32 * 9]); read the flag back after the kernel
+};
+bool layers_fused_supported(const LayersCall& c);
+hipError_t launch_layers(const LayersCall& c, hipStream_t st);
+constexpr int kLayersErrWord = 32 * 9;
+
 // ---- attention over the paged cache (both dtypes) ----
 struct AttnCall {
   int dtype;

@@ -1,0 +1,298 @@
+// Device code of the bf16-cache attention of a NAV pass, shared by the per-layer attention kernels
+// and the fused layer kernel.  (Masked self-attention of a decoder-only layer, Sec. 2.1; row r sees
+// key positions 0..pos_r.)
+//
+// A wave loads 32 tokens' keys (two [16 tok][h] blocks, A operand of S^T = K Q^T) and values (two
+// [h][16 tok] blocks, A operand of O^T = V^T P) straight from the paged cache in MFMA operand
+// layout.  Queries and probabilities are fed as bf16 hi + lo pairs so only the cache itself is
+// bf16.  The scores of one query row sit in the four lanes {c, c+16, c+32, c+48}, so the softmax
+// statistics take two cross-lane steps.
+//
+// CO as in device_gemm.h: when the queries, the new cache rows and the partials were written by
+// other workgroups of the same kernel, they are fetched with device-coherent loads.
+#pragma once
+
+#include "device_gemm.h"
+
+namespace pipesd {
+
+constexpr int kPartPad = 4;  // a partial row is [head_dim values, max, sum, 2 unused] so that rows stay 16-byte aligned
+constexpr int kAttnWaves = 8;
+constexpr int kAttnWgTokens = kAttnWaves * 32;
+
+typedef __attribute__((ext_vector_type(4))) unsigned au32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned au32x2;
+
+__device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf16x8& lo) {
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
+    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
+    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
+    h[i] = (unsigned)h0 | ((unsigned)h1 << 16);
+    l[i] = (unsigned)l0 | ((unsigned)l1 << 16);
+  }
+  hi = __builtin_bit_cast(bf16x8, au32x4{h[0], h[1], h[2], h[3]});
+  lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
+}
+
+// issue-only coherent loads and the wait that releases their registers
+__device__ __forceinline__ au32x4 co_load16(const void* p) {
+  au32x4 v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p));
+  return v;
+}
+__device__ __forceinline__ au32x2 co_load8(const void* p) {
+  au32x2 v;
+  asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(v) : "v"(p));
+  return v;
+}
+__device__ __forceinline__ void co_wait(au32x4& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)); }
+__device__ __forceinline__ void co_wait(au32x2& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)); }
+
+constexpr size_t attn_lds_floats(int hd) { return (size_t)(kAttnWaves / 2) * 16 * (hd + 4) + 2 * (kAttnWaves / 2) * 16; }
+
+// Task (kv_head, split) = 8 waves x 32 tokens.  A wave loads its 32 tokens' keys and values once
+// into registers, then walks the 16-row tiles of the query rows that share the KV head; per tile
+// the eight waves' (max, sum, O) are merged pairwise through LDS and written as the split's
+// partial.  All 8 waves of the workgroup must call this together.
+template <int HD, bool CO>
+__device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int layer, int m, int start_pos,
+                                          int n_q_heads, int nsplit, float* part, int kvh, int split, float* lds) {
+  constexpr int KSQ = HD / 32, HT = HD / 16, ROW = HD + 4;
+  float(*o_lds)[16][ROW] = (float(*)[16][ROW])lds;
+  float(*m_lds)[16] = (float(*)[16])(lds + (size_t)(kAttnWaves / 2) * 16 * ROW);
+  float(*l_lds)[16] = m_lds + kAttnWaves / 2;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int group = n_q_heads / kv.n_kv_heads;
+  const int R = group * m, NQ = (R + 15) / 16;
+  const int total = start_pos + m;
+  const int tok0 = split * kAttnWgTokens + w * 32;
+  const uint16_t* pool = (const uint16_t*)kv.pool;
+  const float scale = 1.0f / sqrtf((float)HD);
+
+  // keys and values of this wave's 32 tokens; tokens at or beyond `total` read as zero
+  bf16x8 kf[2][KSQ], vf[HT];
+  {
+    au32x4 kraw[2][KSQ];
+    au32x2 vlo[HT], vhi[HT];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tb = tok0 + tt * 16;
+      const int blk = kv.table[tb < total ? tb / kBlockTokens : 0];
+      const int64_t base = (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) {
+        const uint16_t* kp = pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8;
+        if constexpr (CO) kraw[tt][s] = co_load16(kp); else kraw[tt][s] = *(const au32x4*)kp;
+      }
+#pragma unroll
+      for (int j = 0; j < HT; ++j) {
+        const uint16_t* vp = pool + base + kv.v_offset + ((int64_t)kvh * HD + j * 16 + c) * kBlockTokens + g * 4;
+        au32x2 v;
+        if constexpr (CO) v = co_load8(vp); else v = *(const au32x2*)vp;
+        if (tt == 0) vlo[j] = v; else vhi[j] = v;
+      }
+    }
+    if constexpr (CO) {
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) co_wait(kraw[tt][s]);
+#pragma unroll
+      for (int j = 0; j < HT; ++j) { co_wait(vlo[j]); co_wait(vhi[j]); }
+    }
+    unsigned long long keep[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int tb = tok0 + tt * 16;
+      const bool tok_ok = tb + c < total;
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s)
+        kf[tt][s] = __builtin_bit_cast(bf16x8, tok_ok ? kraw[tt][s] : au32x4{0u, 0u, 0u, 0u});
+      const int nvalid = min(4, max(0, total - (tb + g * 4)));
+      keep[tt] = nvalid >= 4 ? ~0ull : ((1ull << (16 * nvalid)) - 1ull);
+    }
+#pragma unroll
+    for (int j = 0; j < HT; ++j)
+      vf[j] = __builtin_bit_cast(bf16x8, au32x4{vlo[j].x & (unsigned)keep[0], vlo[j].y & (unsigned)(keep[0] >> 32),
+                                                vhi[j].x & (unsigned)keep[1], vhi[j].y & (unsigned)(keep[1] >> 32)});
+  }
+
+  for (int qt = 0; qt < NQ; ++qt) {
+    const int rr = qt * 16 + c;
+    const bool row_ok = rr < R;
+    const int gq = row_ok ? rr / m : 0, r = row_ok ? rr % m : 0;
+    const int head = kvh * group + gq;
+    bf16x8 qhi[KSQ], qlo[KSQ];
+    {
+      au32x4 qa[KSQ], qb[KSQ];
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) {
+        const float* qp = q + ((size_t)r * n_q_heads + head) * HD + s * 32 + g * 8;
+        if constexpr (CO) { qa[s] = co_load16(qp); qb[s] = co_load16(qp + 4); }
+        else { qa[s] = *(const au32x4*)qp; qb[s] = *(const au32x4*)(qp + 4); }
+      }
+      if constexpr (CO) {
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) { co_wait(qa[s]); co_wait(qb[s]); }
+      }
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) {
+        // (whole-vector casts: a bit cast of one vector element reads element 0 with this compiler)
+        const f32x4 fa = __builtin_bit_cast(f32x4, qa[s]), fb = __builtin_bit_cast(f32x4, qb[s]);
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[i] = row_ok ? fa[i] : 0.f;
+          v[i + 4] = row_ok ? fb[i] : 0.f;
+        }
+        split_hi_lo8(v, qhi[s], qlo[s]);
+      }
+    }
+    // scores of query row c against tokens tok0 + tt*16 + g*4 + i
+    float sc[8];
+    const int pos_q = start_pos + r;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < KSQ; ++s) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qhi[s], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qlo[s], acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int t = tok0 + tt * 16 + g * 4 + i;
+        sc[tt * 4 + i] = (row_ok && t <= pos_q) ? acc[i] * scale : -INFINITY;
+      }
+    }
+    float m_run = sc[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) m_run = fmaxf(m_run, sc[i]);
+    m_run = fmaxf(m_run, __shfl_xor(m_run, 16, 64));
+    m_run = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+    float pv[8], l_run = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - m_run);
+      l_run += pv[i];
+    }
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    bf16x8 phi, plo;
+    split_hi_lo8(pv, phi, plo);
+    f32x4 o[HT];
+#pragma unroll
+    for (int j = 0; j < HT; ++j) {
+      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], phi, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], plo, acc, 0, 0, 0);
+      o[j] = acc;  // O[query c][element j*16 + g*4 + i]
+    }
+    // merge the eight waves pairwise through LDS: (4..7 -> 0..3), (2,3 -> 0,1), (1 -> 0)
+#pragma unroll
+    for (int span = kAttnWaves / 2; span >= 1; span >>= 1) {
+      if (w >= span && w < 2 * span) {
+#pragma unroll
+        for (int j = 0; j < HT; ++j) *(f32x4*)&o_lds[w - span][c][j * 16 + g * 4] = o[j];
+        if (g == 0) {
+          m_lds[w - span][c] = m_run;
+          l_lds[w - span][c] = l_run;
+        }
+      }
+      __syncthreads();
+      if (w < span) {
+        const float mp = m_lds[w][c], lp = l_lds[w][c];
+        const float nm = fmaxf(m_run, mp);
+        const float so = (m_run == -INFINITY) ? 0.f : expf(m_run - nm);
+        const float sp = (mp == -INFINITY) ? 0.f : expf(mp - nm);
+        l_run = l_run * so + lp * sp;
+        m_run = nm;
+#pragma unroll
+        for (int j = 0; j < HT; ++j) {
+          const f32x4 op = *(const f32x4*)&o_lds[w][c][j * 16 + g * 4];
+          o[j] = o[j] * so + op * sp;
+        }
+      }
+      __syncthreads();
+    }
+    if (w == 0 && row_ok) {
+      float* dst = part + (((size_t)head * m + r) * nsplit + split) * (HD + kPartPad);
+#pragma unroll
+      for (int j = 0; j < HT; ++j) Xwg<CO>::st4f(dst + j * 16 + g * 4, o[j]);
+      if (g == 0) Xwg<CO>::st4f(dst + HD, f32x4{m_run, l_run, 0.f, 0.f});
+    }
+  }
+}
+
+// Merge the splits of one (row, head): one thread per 8 consecutive elements, all of a batch's loads
+// issued before any is used; the result is written packed for the O projection.  `gt` numbers the
+// threads over all (pair, segment) tasks.
+template <bool CO>
+__device__ __forceinline__ void attn_merge_thread(const float* part, int m, int n_q_heads, int h, int nsplit,
+                                                  u32x4* outp, int gt) {
+  constexpr int BATCH = 9;
+  const int segs = h / 8;
+  const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
+  if (pair >= m * n_q_heads) return;
+  const int head = pair / m, r = pair % m;
+  const float* p = part + (size_t)pair * nsplit * (h + kPartPad);
+  float M = -INFINITY, L = 0.f, acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int s0 = 0; s0 < nsplit; s0 += BATCH) {
+    au32x4 mlr[BATCH], oar[BATCH], obr[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const float* ps = p + (size_t)min(s0 + j, nsplit - 1) * (h + kPartPad);
+      if constexpr (CO) {
+        mlr[j] = co_load16(ps + h);
+        oar[j] = co_load16(ps + e0);
+        obr[j] = co_load16(ps + e0 + 4);
+      } else {
+        mlr[j] = *(const au32x4*)(ps + h);
+        oar[j] = *(const au32x4*)(ps + e0);
+        obr[j] = *(const au32x4*)(ps + e0 + 4);
+      }
+    }
+    if constexpr (CO) {
+#pragma unroll
+      for (int j = 0; j < BATCH; ++j) { co_wait(mlr[j]); co_wait(oar[j]); co_wait(obr[j]); }
+    }
+    f32x4 ml[BATCH], oa[BATCH], ob[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      ml[j] = __builtin_bit_cast(f32x4, mlr[j]);
+      oa[j] = __builtin_bit_cast(f32x4, oar[j]);
+      ob[j] = __builtin_bit_cast(f32x4, obr[j]);
+    }
+    float bm = M;
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j)
+      if (s0 + j < nsplit) bm = fmaxf(bm, ml[j][0]);
+    if (bm == -INFINITY) continue;
+    const float so = (M == -INFINITY) ? 0.f : expf(M - bm);
+    L *= so;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] *= so;
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const float wgt = (s0 + j < nsplit && ml[j][0] != -INFINITY) ? expf(ml[j][0] - bm) : 0.f;
+      L += ml[j][1] * wgt;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc[i] += oa[j][i] * wgt;
+        acc[i + 4] += ob[j][i] * wgt;
+      }
+    }
+    M = bm;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] /= L;
+  store_act8x<CO>(outp, r, head * h + e0, acc);
+}
+
+}  // namespace pipesd

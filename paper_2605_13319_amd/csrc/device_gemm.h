@@ -371,7 +371,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
 #pragma unroll
       for (int r2 = 0; r2 < 2; ++r2) {
         const int row = w + 8 * r2;
-        float q = (part[r2][0] + part[r2][1]) + (part[r2][2] + part[r2][3]);
+        float q = ((part[r2][0] + part[r2][1]) + part[r2][2]) + part[r2][3];  // same order as the plain path
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
         if (lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);

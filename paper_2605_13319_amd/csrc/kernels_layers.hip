@@ -1,0 +1,257 @@
+// All decoder layers of a NAV pass in ONE cooperative kernel (bf16 models, passes of up to 16 rows).
+//
+// Launching one kernel per projection costs ~6 us of launch gap, pipeline ramp and tail for each of
+// the ~160 dependent steps of a pass, during which HBM idles.  Here one workgroup per compute unit
+// stays resident for the whole layer stack and the steps are separated by a device-wide barrier
+// instead.  What that buys: every wave requests the first weight chunk of the next projection
+// BEFORE it enters the barrier (weights depend on nothing), so the HBM stream keeps running while
+// the workgroups synchronise and while the small activation tensors make their way across.
+//
+// Cross-workgroup traffic (ActPack buffers, residual stream, queries, new cache rows, attention
+// partials, sums of squares) is written through and read past the chiplet L2s (sc1, see
+// device_gemm.h), so the barrier needs no cache write-back or invalidate: measured on MI355X,
+// 2.3 us per barrier against 14-17 us with fences and ~2.5 us for a kernel boundary.
+//
+// The barrier is a monotone counter per group of workgroups plus one top counter; a waiter gives up
+// after a bounded number of polls, raises an error flag and every workgroup leaves the kernel, so a
+// lost workgroup can never hang the device.
+#include "device_attn.h"
+
+namespace pipesd {
+
+struct LayerWeights {
+  const u32x4 *wqkv, *wo, *wgu, *wdown;
+  const float *attn_norm, *ffn_norm;
+};
+
+struct LayersArgs {
+  const LayerWeights* lw;  // device array [n_layers]
+  const float* final_norm;
+  int n_layers;
+  GemmArgs gemm[4];  // QKV, O, gate/up, down; per-layer fields (wp, gain_next, layer) are filled in on the device
+  float* attn_part;
+  int nsplit, head_dim;
+  unsigned* bar;  // [0]: top counter; [32 * (1 + g)]: counter of group g = workgroup % 8; zeroed before launch
+  int* err;       // set to 1 if a barrier timed out
+};
+
+constexpr unsigned kBarGroups = 8;
+constexpr unsigned kBarMaxPolls = 2000000u;  // x ~0.1-0.2 us per poll: a fraction of a second
+
+// Workgroup barrier without memory fences: in-flight (hand-issued) weight loads must stay in flight.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Device-wide barrier.  The caller has drained its stores (Xwg<true>::drain) before requesting the
+// next weights.  Returns false (to every thread of the workgroup) if it timed out or another
+// workgroup reported an error.
+__device__ __forceinline__ bool grid_sync(unsigned* bar, int* err, unsigned& gen, int* fail_lds) {
+  ++gen;
+  wg_barrier();
+  if (threadIdx.x == 0) {
+    int fail = 0;
+    const unsigned grp = blockIdx.x % kBarGroups, per = gridDim.x / kBarGroups;
+    unsigned* gc = bar + 32 * (1 + grp);
+    const unsigned prev = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (prev == gen * per - 1u) __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned polls = 0;
+    while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gen * kBarGroups) {
+      __builtin_amdgcn_s_sleep(1);
+      if ((++polls & 1023u) == 0u) {
+        if (polls > kBarMaxPolls || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+          __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          fail = 1;
+          break;
+        }
+      }
+    }
+    *fail_lds = fail;
+  }
+  wg_barrier();
+  return *fail_lds == 0;
+}
+
+__device__ __forceinline__ TeamPos team_pos(const GemmArgs& g, int w) {
+  const int tpw = 8 / g.W;  // teams per workgroup (8 waves)
+  TeamPos tp;
+  tp.tl = w / g.W;
+  tp.wt = w % g.W;
+  tp.active = w < tpw * g.W;
+  tp.team = (int)blockIdx.x * tpw + tp.tl;
+  tp.nteams = (int)gridDim.x * tpw;
+  return tp;
+}
+
+// per-layer fields of GEMM `ph` (0 QKV, 1 O, 2 gate/up, 3 down) of layer l
+__device__ __forceinline__ void patch_layer(GemmArgs& g, const LayersArgs& a, int l, int ph) {
+  const LayerWeights lw = a.lw[l];
+  g.layer = l;
+  if (ph == 0) {
+    g.wp = lw.wqkv;
+    if (l > 0) g.ssq_parts = a.gemm[1].ntiles;  // after the first layer the sums of squares come per n-tile
+  } else if (ph == 1) {
+    g.wp = lw.wo;
+    g.gain_next = lw.ffn_norm;
+  } else if (ph == 2) {
+    g.wp = lw.wgu;
+  } else {
+    g.wp = lw.wdown;
+    g.gain_next = l + 1 < a.n_layers ? a.lw[l + 1].attn_norm : a.final_norm;
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
+  extern __shared__ float lds[];
+  __shared__ int fail_lds;
+  constexpr int KS = 16;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  unsigned gen = 0;
+  u32x4 af[KS];
+  {
+    GemmArgs g = a.gemm[0];
+    patch_layer(g, a, 0, 0);
+    gemm_prefetch<KS>(g, team_pos(g, w), lane, af);
+  }
+  const int nsteps = 4 * a.n_layers;
+  for (int step = 0; step < nsteps; ++step) {
+    const int l = step >> 2, ph = step & 3;
+    {
+      GemmArgs g = a.gemm[ph];
+      patch_layer(g, a, l, ph);
+      gemm_body<1, KS, true>(g, team_pos(g, w), 8 / g.W, 8, lds, af);
+    }
+    Xwg<true>::drain();
+    if (ph == 0) {
+      // attention over the paged cache: tasks (kv head, 256-token split), then the split merge
+      const GemmArgs& gq = a.gemm[0];
+      if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
+      const int ntasks = gq.kv.n_kv_heads * a.nsplit;
+      for (int task = blockIdx.x; task < ntasks; task += gridDim.x)
+        attn_task<HD, true>(gq.out, gq.kv, l, gq.m, gq.start_pos, gq.n_q_heads, a.nsplit, a.attn_part,
+                            task % gq.kv.n_kv_heads, task / gq.kv.n_kv_heads, lds);
+      Xwg<true>::drain();
+      if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
+      const int nmerge = gq.m * gq.n_q_heads * (HD / 8);
+      for (int gt = blockIdx.x * 512 + tid; gt < nmerge; gt += gridDim.x * 512)
+        attn_merge_thread<true>(a.attn_part, gq.m, gq.n_q_heads, HD, a.nsplit, (u32x4*)a.gemm[1].actp, gt);
+      Xwg<true>::drain();
+    }
+    if (step + 1 < nsteps) {
+      // the next projection's first weights are requested before the barrier: they depend on nothing
+      GemmArgs g = a.gemm[(step + 1) & 3];
+      patch_layer(g, a, (step + 1) >> 2, (step + 1) & 3);
+      gemm_prefetch<KS>(g, team_pos(g, w), lane, af);
+      if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+int device_cu_count();
+
+static bool team_shape(int N, int K, int grid, GemmArgs& g) {
+  if (K % 512 != 0) return false;
+  const int slices = K / 512;
+  int W = 1;
+  for (int cand = 8; cand >= 1; --cand)
+    if (slices % cand == 0) { W = cand; break; }
+  g.K = K;
+  g.N = N;
+  g.ntiles = (N + 15) / 16;
+  g.kst = K / 32;
+  g.W = W;
+  g.P = slices / W;
+  const int tpw = 8 / W, nteams = grid * tpw;
+  const int tmax = 56 / (tpw * W);  // LDS reduce area of the workgroup stays under 56 KB
+  int best_tg = 1;
+  long best_cost = -1;
+  for (int tg = 1; tg <= tmax; ++tg) {
+    const int groups = (g.ntiles + tg - 1) / tg;
+    const long rounds = (groups + nteams - 1) / nteams;
+    const long cost = rounds * tg;
+    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; best_tg = tg; }
+  }
+  g.tg = best_tg;
+  return true;
+}
+
+bool layers_fused_supported(const LayersCall& c) {
+  const int n_cu = device_cu_count();
+  if (n_cu < 8 || n_cu % 8 != 0) return false;
+  if (c.m < 1 || c.m > 16) return false;
+  if (c.head_dim != 64 && c.head_dim != 128) return false;
+  if (c.d_model % 512 || c.q_dim % 512 || c.d_ffn % 512) return false;
+  if (c.d_model / 16 > 256) return false;  // sums of squares per row are fetched 4 per lane
+  return true;
+}
+
+hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
+  if (!layers_fused_supported(c)) return hipErrorInvalidValue;
+  const int grid = device_cu_count();
+  LayersArgs a{};
+  a.lw = (const LayerWeights*)c.layer_weights;
+  a.final_norm = c.final_norm;
+  a.n_layers = c.n_layers;
+  a.attn_part = c.attn_part;
+  a.nsplit = (c.start_pos + c.m + kAttnWgTokens - 1) / kAttnWgTokens;
+  a.head_dim = c.head_dim;
+  a.bar = c.bar;
+  a.err = (int*)(c.bar + (1 + kBarGroups) * 32);
+  const int nqkv = c.q_dim + 2 * c.kv.n_kv_heads * c.head_dim;
+  GemmArgs base{};
+  base.m = c.m;
+  base.eps = c.eps;
+  base.ssq_stride = c.ssq_stride;
+  base.rope_cs = c.rope_cs;
+  base.kv = c.kv;
+  base.start_pos = c.start_pos;
+  base.n_q_heads = c.n_q_heads;
+  a.gemm[0] = base;
+  if (!team_shape(nqkv, c.d_model, grid, a.gemm[0])) return hipErrorInvalidValue;
+  a.gemm[0].actp = (const u32x4*)c.xpk;
+  a.gemm[0].ssq_in = c.ssq;
+  a.gemm[0].ssq_parts = 1;  // the row setup leaves one sum per row
+  a.gemm[0].epi = EPI_QKV;
+  a.gemm[0].out = c.qbuf;
+  a.gemm[0].ldo = c.q_dim;
+  a.gemm[1] = base;
+  if (!team_shape(c.d_model, c.q_dim, grid, a.gemm[1])) return hipErrorInvalidValue;
+  a.gemm[1].actp = (const u32x4*)c.apk;
+  a.gemm[1].epi = EPI_RESID;
+  a.gemm[1].out = c.xres;
+  a.gemm[1].ldo = c.d_model;
+  a.gemm[1].outp = (u32x4*)c.xpk;
+  a.gemm[1].ssq_out = c.ssq;
+  a.gemm[2] = base;
+  if (!team_shape(2 * c.d_ffn, c.d_model, grid, a.gemm[2])) return hipErrorInvalidValue;
+  a.gemm[2].actp = (const u32x4*)c.xpk;
+  a.gemm[2].ssq_in = c.ssq;
+  a.gemm[2].ssq_parts = c.d_model / 16;
+  a.gemm[2].epi = EPI_SWIGLU;
+  a.gemm[2].outp = (u32x4*)c.gpk;
+  a.gemm[3] = base;
+  if (!team_shape(c.d_model, c.d_ffn, grid, a.gemm[3])) return hipErrorInvalidValue;
+  a.gemm[3].actp = (const u32x4*)c.gpk;
+  a.gemm[3].epi = EPI_RESID;
+  a.gemm[3].out = c.xres;
+  a.gemm[3].ldo = c.d_model;
+  a.gemm[3].outp = (u32x4*)c.xpk;
+  a.gemm[3].ssq_out = c.ssq;
+
+  size_t lds_floats = attn_lds_floats(c.head_dim);
+  for (const GemmArgs* g : {&a.gemm[0], &a.gemm[1], &a.gemm[2], &a.gemm[3]}) {
+    const size_t f = gemm_lds_floats(g->tg, g->W, 1, 8 / g->W);
+    if (f > lds_floats) lds_floats = f;
+  }
+  size_t lds = lds_floats * sizeof(float);
+  hipError_t e = hipMemsetAsync(c.bar, 0, (1 + kBarGroups) * 32 * sizeof(unsigned), st);  // counters; the flag is sticky
+  if (e != hipSuccess) return e;
+  void* args[] = {&a};
+  if (c.head_dim == 128)
+    return hipLaunchCooperativeKernel((const void*)layers_kernel<128>, dim3(grid), dim3(512), args, lds, st);
+  return hipLaunchCooperativeKernel((const void*)layers_kernel<64>, dim3(grid), dim3(512), args, lds, st);
+}
+
+}  // namespace pipesd

@@ -23,7 +23,7 @@ _lib = C.CDLL(LIB_PATH)
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 MAX_ROWS = 32
-PROF = dict(off=0, qkv=1, o=2, gateup=3, down=4, lmhead=5, attn=6, verify=7, all_gemm=8)
+PROF = dict(off=0, qkv=1, o=2, gateup=3, down=4, lmhead=5, attn=6, verify=7, all_gemm=8, layers=9)
 
 
 class Config(C.Structure):
@@ -57,6 +57,8 @@ _SIGS = {
     "pipesd_spec_accept": (C.c_int, [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_int32, _f32p, _i32p, _i32p,
                                      C.c_void_p]),
     "pipesd_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p]),
+    "pipesd_model_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
+    "pipesd_model_fused_launches": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "pipesd_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_profile_read": (C.c_int, [C.c_void_p, _i32p, C.POINTER(C.c_double)]),
     "pipesd_strerror": (C.c_char_p, [C.c_int]),
@@ -141,6 +143,14 @@ class Model:
             self.close()
         except Exception:
             pass
+
+    def set_fused(self, on: bool) -> None:
+        _check(_lib.pipesd_model_set_fused(self.handle, 1 if on else 0), "pipesd_model_set_fused")
+
+    def fused_launches(self) -> int:
+        n = C.c_int64()
+        _check(_lib.pipesd_model_fused_launches(self.handle, C.byref(n)), "pipesd_model_fused_launches")
+        return n.value
 
     def profile_select(self, which: str) -> None:
         _check(_lib.pipesd_profile_select(self.handle, PROF[which]), "pipesd_profile_select")

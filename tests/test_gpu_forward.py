@@ -193,3 +193,101 @@ def test_llama_8b_width_truncated_to_two_layers(nav, k):
     u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U)
     err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
     print(f"llama-8b-L2 k={k}: err {err:.2e} accepted {a}/{k}", flush=True)
+
+
+@pytest.mark.parametrize("shape,prefix,k", [(SMALL_BF16, 70, 8), (SMALL_MHA, 300, 15),
+                                            (I.WORKLOADS["llama-8b"]["shape"].truncated(2), 600, 8)])
+def test_fused_layer_kernel_is_bit_identical_to_per_projection_launches(nav, shape, prefix, k):
+    """One cooperative kernel for all layers vs one kernel per projection: same device code, same
+    tiles, same order, so the logits and the cache must agree bit for bit."""
+    w = I.make_weights(shape, 77)
+    toks = I.make_tokens(prefix, shape.vocab, 78)
+    d = I.make_tokens(k, shape.vocab, 79)
+    model = nav.Model(shape, w)
+    kv = nav.KVCache(model, max_seqs=2, n_blocks=2 * ((prefix + 48) // 16 + 1))
+    model.set_fused(False)
+    kv.prefill(0, toks)
+    z_plain = kv.forward_logits(0, d)
+    assert model.fused_launches() == 0
+    model.set_fused(True)
+    kv.prefill(1, toks)
+    z_fused = kv.forward_logits(1, d)
+    assert model.fused_launches() > 0
+    np.testing.assert_array_equal(z_plain, z_fused)
+    for layer in range(shape.n_layers):
+        for pos in (0, prefix // 2, prefix - 2, prefix - 1 + k):
+            k0, v0 = kv.read_kv(0, layer, pos) if pos < prefix - 1 else (None, None)
+            if k0 is not None:
+                k1, v1 = kv.read_kv(1, layer, pos)
+                np.testing.assert_array_equal(k0, k1)
+                np.testing.assert_array_equal(v0, v1)
+    # and the whole pass, twice (the barrier counters are reset per launch)
+    q = I.make_random_probs(k, shape.vocab, 80)
+    u = I.make_uniforms(k + 1, 81)
+    r_fused = kv.nav_verify(1, d, q, u)
+    kv.rollback(1, prefix)
+    assert kv.nav_verify(1, d, q, u) == r_fused
+    model.set_fused(False)
+    assert kv.nav_verify(0, d, q, u) == r_fused
+
+
+def test_llama_8b_full_depth_against_stored_checker_values(nav):
+    """The benchmark's own workload (32 layers, 2048-token prefix, k = 8) against values the CPU
+    checker computed once for the same seeds (tests/golden/make_llama8b_golden.py writes them)."""
+    import json
+    import os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "llama8b_nav.json")))
+    wl = I.WORKLOADS["llama-8b"]
+    shape, seed, prefix, k = wl["shape"], wl["seed"], wl["prefix"], wl["k"]
+    assert (g["prefix"], g["k"], g["seed"]) == (prefix, k, seed)
+    w = I.make_weights(shape, seed + I.SEED_WEIGHTS, threads=16)
+    model = nav.Model(shape, w)
+    del w
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=(prefix + 48) // 16 + 1)
+    kv.prefill(0, I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX))
+    # pass A: logits at sampled positions, argmax, token matching
+    a_ref = g["pass_a"]
+    d = np.array(a_ref["drafts"], dtype=np.int32)
+    z = kv.forward_logits(0, d)
+    worst = 0.0
+    for smp in a_ref["samples"]:
+        got = z[smp["row"], smp["idx"]]
+        worst = max(worst, float(np.abs(got - np.array(smp["val"], dtype=np.float32)).max()))
+    print(f"llama-8b full depth: sampled logits max-abs err {worst:.2e}", flush=True)
+    assert worst <= TOL_BF16
+    for r in range(k + 1):
+        if a_ref["row_top2_gap"][r] > 2 * TOL_BF16:
+            assert int(np.argmax(z[r])) == a_ref["row_argmax"][r]
+    if min(a_ref["row_top2_gap"][:a_ref["accepted_len"] + 1]) > 2 * TOL_BF16:
+        assert kv.nav_verify(0, d) == (a_ref["accepted_len"], a_ref["next_token"])
+        kv.rollback(0, prefix)
+    # pass B: stochastic rule with draft distributions that ignore the target
+    b_ref = g["pass_b"]
+    d2, q2 = I.make_independent_drafts(k, shape.vocab, seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U,
+                                       scale=b_ref["draft_scale"])
+    u2 = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U)
+    np.testing.assert_allclose(u2, np.array(b_ref["uniforms"], dtype=np.float32))
+    a, n = kv.nav_verify(0, d2, q2, u2)
+    if a != b_ref["accepted_len"]:
+        i = min(a, b_ref["accepted_len"])
+        assert abs(min(1.0, b_ref["ratios"][i]) - b_ref["uniforms"][i]) < 1e-3
+    else:
+        print(f"pass B: accepted {a}, next {n} (checker {b_ref['next_token']})", flush=True)
+    assert kv.length(0) == prefix + a + 1
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_bf16_row_block_equals_shorter_row_blocks(nav, fused):
+    """k + 1 rows in one pass give the logits of the same rows run as shorter passes (the pass is a
+    causal forward): rows of a 9-row pass vs the last rows of 1..8-row passes, and a 17-row pass."""
+    shape = SMALL_BF16
+    w = I.make_weights(shape, 31)
+    model = nav.Model(shape, w)
+    model.set_fused(fused)
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=24)
+    kv.prefill(0, I.make_tokens(100, shape.vocab, 32))
+    d = I.make_tokens(16, shape.vocab, 33)
+    z16 = kv.forward_logits(0, d)
+    for n in (0, 1, 3, 8, 12):
+        zn = kv.forward_logits(0, d[:n])
+        assert float(np.abs(zn - z16[:n + 1]).max()) < 2e-3, n
