@@ -178,6 +178,12 @@ enum { PIPESD_PROF_OFF = 0, PIPESD_PROF_GEMM_QKV = 1, PIPESD_PROF_GEMM_O = 2, PI
        PIPESD_PROF_ALL_GEMM = 8, PIPESD_PROF_LAYERS = 9 };
 int pipesd_profile_select(pipesd_model *model, int32_t kernel_class);
 int pipesd_profile_read(pipesd_model *model, int32_t *n_launches, double *total_ms);
+/* While PIPESD_PROF_LAYERS is selected the fused layer kernel also records a device clock at the
+ * start of each of its 4*n_layers steps (QKV + attention, O, gate/up, down per layer).  Copies the
+ * step durations of the most recent fused launch, in microseconds, into host array us_out (at most
+ * `cap` values) and sets *n_steps to 4*n_layers (0 if no fused launch was recorded).  Synchronises
+ * the device. */
+int pipesd_profile_read_steps(pipesd_model *model, double *us_out, int32_t cap, int32_t *n_steps);
 
 const char *pipesd_strerror(int status);
 /* Text of the HIP call that made this thread's most recent call return PIPESD_EHIP ("" if none). */

@@ -47,9 +47,7 @@ struct pipesd_model {
   float *xres = nullptr, *hbuf = nullptr, *qkv = nullptr, *qbuf = nullptr, *attn_out = nullptr, *gu = nullptr,
         *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
   unsigned* counters = nullptr;
-  void *xpk = nullptr, *apk = nullptr, *gpk = nullptr;  // packed activations feeding the bf16 GEMMs
-  float* ssq = nullptr;                                  // [rows][ssq_stride] partial sums of x^2
-  int ssq_stride = 0;
+  ActArena arena{};  // bf16 path: per-layer activation buffers
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
   float* row_stats = nullptr;
@@ -60,6 +58,8 @@ struct pipesd_model {
   // fused layer kernel (bf16, passes of up to 16 rows)
   void* layer_weights_dev = nullptr;
   unsigned* bar = nullptr;
+  unsigned long long* step_clock = nullptr;  // [4 * n_layers + 1] clocks of the last fused launch
+  bool steps_recorded = false;
   bool fused_enabled = false;  // opt-in until it beats the per-projection launches
   int64_t fused_launches = 0;
   // kernel timing
@@ -211,14 +211,10 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
   if (c.dtype == PIPESD_BF16) {
     if (device_cu_count() <= 0) return PIPESD_EHIP;
-    if ((rc = dev_alloc(m, &m->xpk, act_pack_bytes(d)))) return rc;
-    if ((rc = dev_alloc(m, &m->apk, act_pack_bytes(qd)))) return rc;
-    if ((rc = dev_alloc(m, &m->gpk, act_pack_bytes(F)))) return rc;
-    HIP_TRY(hipMemset(m->xpk, 0, act_pack_bytes(d)));
-    HIP_TRY(hipMemset(m->apk, 0, act_pack_bytes(qd)));
-    HIP_TRY(hipMemset(m->gpk, 0, act_pack_bytes(F)));
-    m->ssq_stride = d / 16;
-    if ((rc = dev_alloc(m, (void**)&m->ssq, R * m->ssq_stride * 4))) return rc;
+    const size_t arena_bytes = act_arena_layout(m->arena, L, d, qd, F);
+    if ((rc = dev_alloc(m, (void**)&m->arena.base, arena_bytes))) return rc;
+    HIP_TRY(hipMemset(m->arena.base, 0, arena_bytes));
+    if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
     std::vector<const void*> lw((size_t)L * 6);
     for (int l = 0; l < L; ++l) {
       lw[l * 6 + 0] = m->wqkv[l];
@@ -414,6 +410,23 @@ extern "C" int pipesd_profile_read(pipesd_model* model, int32_t* n_launches, dou
   return PIPESD_OK;
 }
 
+extern "C" int pipesd_profile_read_steps(pipesd_model* model, double* us_out, int32_t cap, int32_t* n_steps) {
+  if (!model || !us_out || !n_steps || cap < 0) return PIPESD_EINVAL;
+  *n_steps = 0;
+  if (!model->step_clock || !model->steps_recorded) return PIPESD_OK;
+  const int n = 4 * model->cfg.n_layers;
+  std::vector<unsigned long long> clk((size_t)n + 1);
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(clk.data(), model->step_clock, clk.size() * 8, hipMemcpyDeviceToHost));
+  int dev = 0, khz = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+  if (khz <= 0) return PIPESD_EHIP;
+  for (int i = 0; i < n && i < cap; ++i) us_out[i] = (double)(clk[i + 1] - clk[i]) * 1e3 / (double)khz;
+  *n_steps = n;
+  return PIPESD_OK;
+}
+
 namespace {
 struct ProfScope {
   pipesd_model* m;
@@ -487,17 +500,17 @@ static int ensure_attn_scratch(pipesd_model* m, size_t floats) {
   return PIPESD_OK;
 }
 
-static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int rows, const void* actp, bool norm,
-                          int norm_parts, int epi) {
+static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int rows, const void* actp,
+                          const float* ssq_in, int norm_parts, int epi) {
   GemmCall c{};
   c.wp = wp;
   c.N = N;
   c.K = K;
   c.m = rows;
   c.actp = actp;
-  c.ssq_in = norm ? m->ssq : nullptr;
+  c.ssq_in = ssq_in;
   c.ssq_parts = norm_parts;
-  c.ssq_stride = m->ssq_stride;
+  c.ssq_stride = m->arena.ssq_stride;
   c.eps = m->cfg.rms_eps;
   c.epi = epi;
   c.rope_cs = m->rope_cs;
@@ -514,10 +527,16 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   for (int r = 0; r < rows; ++r) rt.tok[r] = row_tokens[r];
   const int chunk = attn_chunk_tokens(c.dtype);
   const int nsplit = attn_nsplit(start_pos + rows, chunk);
-  int rc = ensure_attn_scratch(m, (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 4));
+  const bool bf = c.dtype == PIPESD_BF16;
+  const size_t part_floats = (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 4);
+  int rc = ensure_attn_scratch(m, part_floats * (bf ? c.n_layers : 1));
   if (rc) return rc;
-  HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, m->xres, m->rope_cs,
-                            c.dtype == PIPESD_BF16 ? m->attn_norm[0] : nullptr, m->xpk, m->ssq, m->ssq_stride, st));
+  ActArena& ar = m->arena;
+  ar.part = m->attn_part;
+  ar.part_stride = bf ? part_floats : 0;
+  HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, bf ? ar.ra(0) : m->xres,
+                            m->rope_cs, bf ? m->attn_norm[0] : nullptr, bf ? ar.xa(0) : nullptr, bf ? ar.sa(0) : nullptr,
+                            ar.ssq_stride, st));
   int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
   bool fused = false;
   if (c.dtype == PIPESD_BF16 && m->fused_enabled) {
@@ -535,18 +554,13 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     lc.eps = c.rms_eps;
     lc.kv = view;
     lc.rope_cs = m->rope_cs;
-    lc.xpk = m->xpk;
-    lc.apk = m->apk;
-    lc.gpk = m->gpk;
-    lc.xres = m->xres;
-    lc.qbuf = m->qbuf;
-    lc.ssq = m->ssq;
-    lc.attn_part = m->attn_part;
-    lc.ssq_stride = m->ssq_stride;
+    lc.arena = ar;
     lc.bar = m->bar;
+    lc.step_clock = m->prof_class == PIPESD_PROF_LAYERS ? m->step_clock : nullptr;
     if (layers_fused_supported(lc)) {
       ProfScope ps(m, PIPESD_PROF_LAYERS, st);
       HIP_TRY(launch_layers(lc, st));
+      if (lc.step_clock) m->steps_recorded = true;
       ++m->fused_launches;
       fused = true;
       norm_parts = d / 16;
@@ -555,16 +569,16 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   for (int l = 0; l < (fused ? 0 : c.n_layers); ++l) {
     AttnCall at{};
     at.dtype = c.dtype;
-    at.q = m->qbuf;
+    at.q = bf ? ar.q(l) : m->qbuf;
     at.kv = view;
     at.layer = l;
     at.m = rows;
     at.start_pos = start_pos;
     at.n_q_heads = c.n_q_heads;
     at.chunk = chunk;
-    at.part = m->attn_part;
+    at.part = ar.partials(l);
     at.out = m->attn_out;
-    at.outp = m->apk;
+    at.outp = bf ? ar.ap(l) : nullptr;
     if (c.dtype == PIPESD_F32) {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
@@ -593,8 +607,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     } else {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
-        GemmCall g = gemm_call(m, m->wqkv[l], nqkv, d, rows, m->xpk, true, norm_parts, EPI_QKV);
-        g.out = m->qbuf;
+        GemmCall g = gemm_call(m, m->wqkv[l], nqkv, d, rows, ar.xa(l), ar.sa(l), norm_parts, EPI_QKV);
+        g.out = ar.q(l);
         g.ldo = qd;
         g.kv = view;
         g.layer = l;
@@ -608,29 +622,31 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_O, st);
-        GemmCall g = gemm_call(m, m->wo[l], d, qd, rows, m->apk, false, 0, EPI_RESID);
-        g.out = m->xres;
+        GemmCall g = gemm_call(m, m->wo[l], d, qd, rows, ar.ap(l), nullptr, 0, EPI_RESID);
+        g.res_in = ar.ra(l);
+        g.out = ar.rb(l);
         g.ldo = d;
-        g.outp = m->xpk;
+        g.outp = ar.xb(l);
         g.gain_next = m->ffn_norm[l];
-        g.ssq_out = m->ssq;
+        g.ssq_out = ar.sb(l);
         HIP_TRY(launch_gemm_bf16(g, st));
         norm_parts = d / 16;
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_GATEUP, st);
-        GemmCall g = gemm_call(m, m->wgu[l], 2 * F, d, rows, m->xpk, true, norm_parts, EPI_SWIGLU);
-        g.outp = m->gpk;
+        GemmCall g = gemm_call(m, m->wgu[l], 2 * F, d, rows, ar.xb(l), ar.sb(l), norm_parts, EPI_SWIGLU);
+        g.outp = ar.gp(l);
         HIP_TRY(launch_gemm_bf16(g, st));
       }
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_DOWN, st);
-        GemmCall g = gemm_call(m, m->wdown[l], d, F, rows, m->gpk, false, 0, EPI_RESID);
-        g.out = m->xres;
+        GemmCall g = gemm_call(m, m->wdown[l], d, F, rows, ar.gp(l), nullptr, 0, EPI_RESID);
+        g.res_in = ar.rb(l);
+        g.out = ar.ra(l + 1);
         g.ldo = d;
-        g.outp = m->xpk;
+        g.outp = ar.xa(l + 1);
         g.gain_next = l + 1 < c.n_layers ? m->attn_norm[l + 1] : m->final_norm;
-        g.ssq_out = m->ssq;
+        g.ssq_out = ar.sa(l + 1);
         HIP_TRY(launch_gemm_bf16(g, st));
       }
     }
@@ -641,7 +657,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
       HIP_TRY(launch_rmsnorm_rows(m->xres, m->final_norm, c.rms_eps, rows, d, m->hbuf, st));
       HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->lm_head, V, d, rows, m->logits, V, 0, st));
     } else {
-      GemmCall g = gemm_call(m, m->lm_head, V, d, rows, m->xpk, true, norm_parts, EPI_STORE);
+      GemmCall g = gemm_call(m, m->lm_head, V, d, rows, ar.xa(c.n_layers), ar.sa(c.n_layers), norm_parts, EPI_STORE);
       g.out = m->logits;
       g.ldo = V;
       HIP_TRY(launch_gemm_bf16(g, st));

@@ -113,7 +113,8 @@ struct GemmCall {
   int ssq_parts, ssq_stride;
   float eps;
   int epi;
-  float* out;         // STORE: [m][ldo] logits; RESID: residual stream [m][ldo]; QKV: query buffer [m][ldo]
+  float* out;         // STORE: [m][ldo] logits; RESID: new residual stream [m][ldo]; QKV: query buffer [m][ldo]
+  const float* res_in;  // RESID: residual stream the product is added to (may be `out`)
   int ldo;
   void* outp;         // RESID: packed x_new * gain_next; SWIGLU: packed silu(gate)*up
   const float* gain_next;
@@ -135,6 +136,33 @@ struct PackSrc {
 hipError_t launch_pack_bf16(const PackSrc& s, int n_src, int K, int mode, int pair_span, void* dst, int ntiles,
                             hipStream_t st);
 
+// ---- activation buffers of the bf16 path ----
+// Every tensor that one step of a pass hands to the next has its own buffer PER LAYER, so within a
+// pass no address is written twice and none is read before it is written.  The per-projection
+// launches do not need that; the all-layers kernel does: its workgroups may then read what other
+// workgroups wrote with ordinary cached loads, because a cache can hold no older copy of a line.
+// Index l = 0..n_layers-1, and n_layers for the tensors entering the LM head.
+struct ActArena {
+  char* base;
+  size_t off_xa, off_xb, off_ap, off_gp, off_ra, off_rb, off_q, off_sa, off_sb;  // first instance of each kind
+  size_t x_bytes, ap_bytes, gp_bytes, r_bytes, q_bytes, s_bytes;                // distance between layers
+  float* part;          // attention partials
+  size_t part_stride;   // floats between layers
+  int ssq_stride;       // floats per row of a sums-of-squares buffer
+
+  __host__ __device__ void* xa(int l) const { return base + off_xa + (size_t)l * x_bytes; }   // packed x*gain into QKV of layer l / LM head
+  __host__ __device__ void* xb(int l) const { return base + off_xb + (size_t)l * x_bytes; }   // packed x*gain into gate/up
+  __host__ __device__ void* ap(int l) const { return base + off_ap + (size_t)l * ap_bytes; }  // packed attention output
+  __host__ __device__ void* gp(int l) const { return base + off_gp + (size_t)l * gp_bytes; }  // packed silu(gate)*up
+  __host__ __device__ float* ra(int l) const { return (float*)(base + off_ra + (size_t)l * r_bytes); }  // residual entering layer l
+  __host__ __device__ float* rb(int l) const { return (float*)(base + off_rb + (size_t)l * r_bytes); }  // residual after attention
+  __host__ __device__ float* q(int l) const { return (float*)(base + off_q + (size_t)l * q_bytes); }    // rotated queries
+  __host__ __device__ float* sa(int l) const { return (float*)(base + off_sa + (size_t)l * s_bytes); }  // sums of squares of ra(l)
+  __host__ __device__ float* sb(int l) const { return (float*)(base + off_sb + (size_t)l * s_bytes); }  // sums of squares of rb(l)
+  __host__ __device__ float* partials(int l) const { return part + (size_t)l * part_stride; }
+};
+size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn);  // fills offsets; returns bytes
+
 // ---- all decoder layers of a pass in one cooperative kernel (bf16, up to 16 rows) ----
 struct LayersCall {
   const void* layer_weights;  // device array of per-layer {wqkv, wo, wgu, wdown, attn_norm, ffn_norm} pointers
@@ -143,11 +171,10 @@ struct LayersCall {
   float eps;
   KvView kv;
   const float* rope_cs;
-  void *xpk, *apk, *gpk;  // packed activations
-  float *xres, *qbuf, *ssq, *attn_part;
-  int ssq_stride;
+  ActArena arena;
   unsigned* bar;  // >= 4 KB of device memory for the barrier counters and the error flag (last word used:
                   // bar[32 * 9]); read the flag back after the kernel
+  unsigned long long* step_clock;  // optional [4 * n_layers + 1] device words: clock at the start of each step and at the end
 };
 bool layers_fused_supported(const LayersCall& c);
 hipError_t launch_layers(const LayersCall& c, hipStream_t st);

@@ -8,8 +8,8 @@
 // bf16.  The scores of one query row sit in the four lanes {c, c+16, c+32, c+48}, so the softmax
 // statistics take two cross-lane steps.
 //
-// CO as in device_gemm.h: when the queries, the new cache rows and the partials were written by
-// other workgroups of the same kernel, they are fetched with device-coherent loads.
+// CO as in device_gemm.h: results other workgroups of the same kernel will read (partials, packed
+// output) are written through; loads are ordinary cached loads.
 #pragma once
 
 #include "device_gemm.h"
@@ -36,20 +36,6 @@ __device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf
   hi = __builtin_bit_cast(bf16x8, au32x4{h[0], h[1], h[2], h[3]});
   lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
 }
-
-// issue-only coherent loads and the wait that releases their registers
-__device__ __forceinline__ au32x4 co_load16(const void* p) {
-  au32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p));
-  return v;
-}
-__device__ __forceinline__ au32x2 co_load8(const void* p) {
-  au32x2 v;
-  asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=v"(v) : "v"(p));
-  return v;
-}
-__device__ __forceinline__ void co_wait(au32x4& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)); }
-__device__ __forceinline__ void co_wait(au32x2& v) { asm volatile("s_waitcnt vmcnt(0)" : "+v"(v)); }
 
 constexpr size_t attn_lds_floats(int hd) { return (size_t)(kAttnWaves / 2) * 16 * (hd + 4) + 2 * (kAttnWaves / 2) * 16; }
 
@@ -86,23 +72,14 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
 #pragma unroll
       for (int s = 0; s < KSQ; ++s) {
         const uint16_t* kp = pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8;
-        if constexpr (CO) kraw[tt][s] = co_load16(kp); else kraw[tt][s] = *(const au32x4*)kp;
+        kraw[tt][s] = *(const au32x4*)kp;
       }
 #pragma unroll
       for (int j = 0; j < HT; ++j) {
         const uint16_t* vp = pool + base + kv.v_offset + ((int64_t)kvh * HD + j * 16 + c) * kBlockTokens + g * 4;
-        au32x2 v;
-        if constexpr (CO) v = co_load8(vp); else v = *(const au32x2*)vp;
+        const au32x2 v = *(const au32x2*)vp;
         if (tt == 0) vlo[j] = v; else vhi[j] = v;
       }
-    }
-    if constexpr (CO) {
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-        for (int s = 0; s < KSQ; ++s) co_wait(kraw[tt][s]);
-#pragma unroll
-      for (int j = 0; j < HT; ++j) { co_wait(vlo[j]); co_wait(vhi[j]); }
     }
     unsigned long long keep[2];
 #pragma unroll
@@ -132,12 +109,8 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
 #pragma unroll
       for (int s = 0; s < KSQ; ++s) {
         const float* qp = q + ((size_t)r * n_q_heads + head) * HD + s * 32 + g * 8;
-        if constexpr (CO) { qa[s] = co_load16(qp); qb[s] = co_load16(qp + 4); }
-        else { qa[s] = *(const au32x4*)qp; qb[s] = *(const au32x4*)(qp + 4); }
-      }
-      if constexpr (CO) {
-#pragma unroll
-        for (int s = 0; s < KSQ; ++s) { co_wait(qa[s]); co_wait(qb[s]); }
+        qa[s] = *(const au32x4*)qp;
+        qb[s] = *(const au32x4*)(qp + 4);
       }
 #pragma unroll
       for (int s = 0; s < KSQ; ++s) {
@@ -248,19 +221,9 @@ __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int 
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
       const float* ps = p + (size_t)min(s0 + j, nsplit - 1) * (h + kPartPad);
-      if constexpr (CO) {
-        mlr[j] = co_load16(ps + h);
-        oar[j] = co_load16(ps + e0);
-        obr[j] = co_load16(ps + e0 + 4);
-      } else {
-        mlr[j] = *(const au32x4*)(ps + h);
-        oar[j] = *(const au32x4*)(ps + e0);
-        obr[j] = *(const au32x4*)(ps + e0 + 4);
-      }
-    }
-    if constexpr (CO) {
-#pragma unroll
-      for (int j = 0; j < BATCH; ++j) { co_wait(mlr[j]); co_wait(oar[j]); co_wait(obr[j]); }
+      mlr[j] = *(const au32x4*)(ps + h);
+      oar[j] = *(const au32x4*)(ps + e0);
+      obr[j] = *(const au32x4*)(ps + e0 + 4);
     }
     f32x4 ml[BATCH], oa[BATCH], ob[BATCH];
 #pragma unroll

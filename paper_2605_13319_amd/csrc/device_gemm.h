@@ -24,10 +24,13 @@
 //    weight tile are the partners of rows 0..7 (other half of the head for the rotary pair; the
 //    up-projection row for a gate row) so a pair is finished inside one wave.
 //
-// CO ("coherent") selects how activations cross workgroups.  false: plain loads and stores; the
-// kernel boundary makes them visible.  true: inside one long-running kernel, every such store is
-// written through (sc1) and every such load fetched past the chiplet's L2 (sc1), ordered by a
-// device-wide barrier; weights, gains and rotary tables are immutable and always read plainly.
+// CO ("coherent") selects how results are stored for other workgroups.  false: plain stores; the
+// kernel boundary makes them visible.  true: inside one long-running kernel every such store is
+// written through to memory (sc1) and drained before the device-wide barrier that orders it with
+// its readers.  Loads are ordinary cached loads either way: the long-running kernel's buffers are
+// single-assignment within a pass (ActArena), so no cache can hold an older copy of a line, and
+// measured on MI355X a write-through store of part of a line never leaves stale neighbours behind
+// in the writer's caches.  Weights, gains and rotary tables are immutable.
 #pragma once
 
 #include "common.h"
@@ -42,7 +45,8 @@ struct GemmArgs {
   const u32x4* actp;      // packed activations (ActPack, K columns)
   const float* ssq_in;    // fused norm: [row][ssq_stride] partial sums of x^2, or nullptr
   int ssq_parts, ssq_stride;
-  float* out;             // STORE: logits; RESID: residual stream; QKV: query buffer
+  float* out;             // STORE: logits; RESID: new residual stream; QKV: query buffer
+  const float* res_in;    // RESID: residual stream the product is added to (may be `out`)
   u32x4* outp;            // RESID / SWIGLU: packed output for the next GEMM
   const float* gain_next; // RESID: gain applied to the packed copy
   float* ssq_out;         // RESID: [row][ssq_stride] per-tile sums of x_new^2
@@ -66,13 +70,9 @@ __device__ __forceinline__ u32x4 stream_load(const u32x4* p) {
   asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
   return v;
 }
-template <bool CO>
 __device__ __forceinline__ u32x4 act_load(const u32x4* p) {
   u32x4 v;
-  if constexpr (CO)
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p));
-  else
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
   return v;
 }
 template <int N>
@@ -80,27 +80,9 @@ __device__ __forceinline__ void wait_younger(u32x4& v) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N));
 }
 
-// ---- accesses to data other workgroups wrote or will read -----------------------------------------
+// ---- stores of data other workgroups will read ---------------------------------------------------
 template <bool CO>
 struct Xwg {
-  static __device__ __forceinline__ f32x4 ld4(const float* p) {
-    if constexpr (CO) {
-      f32x4 v;
-      asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
-      return v;
-    } else {
-      return *(const f32x4*)p;
-    }
-  }
-  static __device__ __forceinline__ float ld1(const float* p) {
-    if constexpr (CO) {
-      float v;
-      asm volatile("global_load_dword %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
-      return v;
-    } else {
-      return *p;
-    }
-  }
   static __device__ __forceinline__ void st4(void* p, u32x4 v) {
     if constexpr (CO)
       asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 3" ::"v"(p), "v"(v) : "memory");
@@ -195,12 +177,11 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
       break;
     }
     case EPI_RESID: {
-      float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
+      const size_t at = (size_t)row * a.ldo + t * 16 + gg * 4;
       f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
       if (live) {
-        const f32x4 old = Xwg<CO>::ld4(o);
-        x = old + v;
-        Xwg<CO>::st4f(o, x);
+        x = *(const f32x4*)(a.res_in + at) + v;
+        Xwg<CO>::st4f(a.out + at, x);
       }
       float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
       sq += __shfl_xor(sq, 16, 64);
@@ -333,8 +314,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         if (mt * 16 + bc < a.m) {
-          bhi[mt][ks] = act_load<CO>(a.actp + act_index(slice * KSTEPS + ks, mt, 0, bc, bg));
-          blo[mt][ks] = act_load<CO>(a.actp + act_index(slice * KSTEPS + ks, mt, 1, bc, bg));
+          bhi[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, 0, bc, bg));
+          blo[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, 1, bc, bg));
         }
       }
 #pragma unroll
@@ -350,41 +331,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
 
   // fused norm: rstd per row from the producer's partial sums of squares, added in index order
   if (a.ssq_in != nullptr) {
-    if constexpr (CO) {
-      // 8 waves; wave w takes rows w and w + 8; up to 4 partial sums per lane and row (the host
-      // checks ssq_parts <= 256), all requested before any is used
-      float part[2][4];
+    for (int row = w; row < MT * 16; row += nwaves_wg) {
+      float q = 0.f;
+      if (row < a.m)
+        for (int j = lane; j < a.ssq_parts; j += 64) q += a.ssq_in[(size_t)row * a.ssq_stride + j];
 #pragma unroll
-      for (int r2 = 0; r2 < 2; ++r2)
-#pragma unroll
-        for (int j4 = 0; j4 < 4; ++j4) {
-          const int row = w + 8 * r2, j = lane + 64 * j4;
-          part[r2][j4] = 0.f;
-          if (row < MT * 16 && row < a.m && j < a.ssq_parts)
-            asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[r2][j4])
-                         : "v"(a.ssq_in + (size_t)row * a.ssq_stride + j));
-        }
-#pragma unroll
-      for (int r2 = 0; r2 < 2; ++r2)
-#pragma unroll
-        for (int j4 = 0; j4 < 4; ++j4) asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[r2][j4]));
-#pragma unroll
-      for (int r2 = 0; r2 < 2; ++r2) {
-        const int row = w + 8 * r2;
-        float q = ((part[r2][0] + part[r2][1]) + part[r2][2]) + part[r2][3];  // same order as the plain path
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
-        if (lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
-      }
-    } else {
-      for (int row = w; row < MT * 16; row += nwaves_wg) {
-        float q = 0.f;
-        if (row < a.m)
-          for (int j = lane; j < a.ssq_parts; j += 64) q += a.ssq_in[(size_t)row * a.ssq_stride + j];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
-        if (lane == 0) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
-      }
+      for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+      if (lane == 0) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
     }
   }
 

@@ -71,6 +71,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.ssq_parts = c.ssq_parts;
   a.ssq_stride = c.ssq_stride;
   a.out = c.out;
+  a.res_in = c.res_in;
   a.outp = (u32x4*)c.outp;
   a.gain_next = c.gain_next;
   a.ssq_out = c.ssq_out;

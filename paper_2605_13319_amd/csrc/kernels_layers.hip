@@ -8,9 +8,10 @@
 // the workgroups synchronise and while the small activation tensors make their way across.
 //
 // Cross-workgroup traffic (ActPack buffers, residual stream, queries, new cache rows, attention
-// partials, sums of squares) is written through and read past the chiplet L2s (sc1, see
-// device_gemm.h), so the barrier needs no cache write-back or invalidate: measured on MI355X,
-// 2.3 us per barrier against 14-17 us with fences and ~2.5 us for a kernel boundary.
+// partials, sums of squares) is written through to memory (sc1 stores, see device_gemm.h) and lives
+// in per-layer buffers that are written once per pass (ActArena), so readers use ordinary cached
+// loads and the barrier needs no cache write-back or invalidate: measured on MI355X, 2.3 us per
+// barrier against 14-17 us with fences and ~2.5 us for a kernel boundary.
 //
 // The barrier is a monotone counter per group of workgroups plus one top counter; a waiter gives up
 // after a bounded number of polls, raises an error flag and every workgroup leaves the kernel, so a
@@ -28,9 +29,10 @@ struct LayersArgs {
   const LayerWeights* lw;  // device array [n_layers]
   const float* final_norm;
   int n_layers;
-  GemmArgs gemm[4];  // QKV, O, gate/up, down; per-layer fields (wp, gain_next, layer) are filled in on the device
-  float* attn_part;
+  GemmArgs gemm[4];  // QKV, O, gate/up, down; per-layer fields (weights, buffers, gains) are filled in on the device
+  ActArena arena;
   int nsplit, head_dim;
+  unsigned long long* step_clock;  // optional [4 * n_layers + 1]
   unsigned* bar;  // [0]: top counter; [32 * (1 + g)]: counter of group g = workgroup % 8; zeroed before launch
   int* err;       // set to 1 if a barrier timed out
 };
@@ -84,17 +86,34 @@ __device__ __forceinline__ TeamPos team_pos(const GemmArgs& g, int w) {
 // per-layer fields of GEMM `ph` (0 QKV, 1 O, 2 gate/up, 3 down) of layer l
 __device__ __forceinline__ void patch_layer(GemmArgs& g, const LayersArgs& a, int l, int ph) {
   const LayerWeights lw = a.lw[l];
+  const ActArena& ar = a.arena;
   g.layer = l;
   if (ph == 0) {
     g.wp = lw.wqkv;
+    g.actp = (const u32x4*)ar.xa(l);
+    g.ssq_in = ar.sa(l);
     if (l > 0) g.ssq_parts = a.gemm[1].ntiles;  // after the first layer the sums of squares come per n-tile
+    g.out = ar.q(l);
   } else if (ph == 1) {
     g.wp = lw.wo;
+    g.actp = (const u32x4*)ar.ap(l);
+    g.res_in = ar.ra(l);
+    g.out = ar.rb(l);
+    g.outp = (u32x4*)ar.xb(l);
+    g.ssq_out = ar.sb(l);
     g.gain_next = lw.ffn_norm;
   } else if (ph == 2) {
     g.wp = lw.wgu;
+    g.actp = (const u32x4*)ar.xb(l);
+    g.ssq_in = ar.sb(l);
+    g.outp = (u32x4*)ar.gp(l);
   } else {
     g.wp = lw.wdown;
+    g.actp = (const u32x4*)ar.gp(l);
+    g.res_in = ar.rb(l);
+    g.out = ar.ra(l + 1);
+    g.outp = (u32x4*)ar.xa(l + 1);
+    g.ssq_out = ar.sa(l + 1);
     g.gain_next = l + 1 < a.n_layers ? a.lw[l + 1].attn_norm : a.final_norm;
   }
 }
@@ -115,6 +134,7 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
   const int nsteps = 4 * a.n_layers;
   for (int step = 0; step < nsteps; ++step) {
     const int l = step >> 2, ph = step & 3;
+    if (a.step_clock != nullptr && blockIdx.x == 0 && tid == 0) a.step_clock[step] = wall_clock64();
     {
       GemmArgs g = a.gemm[ph];
       patch_layer(g, a, l, ph);
@@ -127,13 +147,13 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
       if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
       const int ntasks = gq.kv.n_kv_heads * a.nsplit;
       for (int task = blockIdx.x; task < ntasks; task += gridDim.x)
-        attn_task<HD, true>(gq.out, gq.kv, l, gq.m, gq.start_pos, gq.n_q_heads, a.nsplit, a.attn_part,
+        attn_task<HD, true>(a.arena.q(l), gq.kv, l, gq.m, gq.start_pos, gq.n_q_heads, a.nsplit, a.arena.partials(l),
                             task % gq.kv.n_kv_heads, task / gq.kv.n_kv_heads, lds);
       Xwg<true>::drain();
       if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
       const int nmerge = gq.m * gq.n_q_heads * (HD / 8);
       for (int gt = blockIdx.x * 512 + tid; gt < nmerge; gt += gridDim.x * 512)
-        attn_merge_thread<true>(a.attn_part, gq.m, gq.n_q_heads, HD, a.nsplit, (u32x4*)a.gemm[1].actp, gt);
+        attn_merge_thread<true>(a.arena.partials(l), gq.m, gq.n_q_heads, HD, a.nsplit, (u32x4*)a.arena.ap(l), gt);
       Xwg<true>::drain();
     }
     if (step + 1 < nsteps) {
@@ -144,12 +164,35 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
       if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
     }
   }
+  if (a.step_clock != nullptr && blockIdx.x == 0 && tid == 0) a.step_clock[nsteps] = wall_clock64();
 }
 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 int device_cu_count();
+
+size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn) {
+  const size_t L = (size_t)n_layers, R = kMaxRows;
+  a.x_bytes = act_pack_bytes(d_model);
+  a.ap_bytes = act_pack_bytes(q_dim);
+  a.gp_bytes = act_pack_bytes(d_ffn);
+  a.r_bytes = R * d_model * sizeof(float);
+  a.q_bytes = R * q_dim * sizeof(float);
+  a.ssq_stride = d_model / 16;
+  a.s_bytes = (R * a.ssq_stride * sizeof(float) + 255) / 256 * 256;
+  size_t off = 0;
+  a.off_xa = off; off += (L + 1) * a.x_bytes;
+  a.off_xb = off; off += L * a.x_bytes;
+  a.off_ap = off; off += L * a.ap_bytes;
+  a.off_gp = off; off += L * a.gp_bytes;
+  a.off_ra = off; off += (L + 1) * a.r_bytes;
+  a.off_rb = off; off += L * a.r_bytes;
+  a.off_q = off; off += L * a.q_bytes;
+  a.off_sa = off; off += (L + 1) * a.s_bytes;
+  a.off_sb = off; off += L * a.s_bytes;
+  return off;
+}
 
 static bool team_shape(int N, int K, int grid, GemmArgs& g) {
   if (K % 512 != 0) return false;
@@ -194,7 +237,8 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   a.lw = (const LayerWeights*)c.layer_weights;
   a.final_norm = c.final_norm;
   a.n_layers = c.n_layers;
-  a.attn_part = c.attn_part;
+  a.arena = c.arena;
+  a.step_clock = c.step_clock;
   a.nsplit = (c.start_pos + c.m + kAttnWgTokens - 1) / kAttnWgTokens;
   a.head_dim = c.head_dim;
   a.bar = c.bar;
@@ -203,42 +247,28 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   GemmArgs base{};
   base.m = c.m;
   base.eps = c.eps;
-  base.ssq_stride = c.ssq_stride;
+  base.ssq_stride = c.arena.ssq_stride;
   base.rope_cs = c.rope_cs;
   base.kv = c.kv;
   base.start_pos = c.start_pos;
   base.n_q_heads = c.n_q_heads;
   a.gemm[0] = base;
   if (!team_shape(nqkv, c.d_model, grid, a.gemm[0])) return hipErrorInvalidValue;
-  a.gemm[0].actp = (const u32x4*)c.xpk;
-  a.gemm[0].ssq_in = c.ssq;
   a.gemm[0].ssq_parts = 1;  // the row setup leaves one sum per row
   a.gemm[0].epi = EPI_QKV;
-  a.gemm[0].out = c.qbuf;
   a.gemm[0].ldo = c.q_dim;
   a.gemm[1] = base;
   if (!team_shape(c.d_model, c.q_dim, grid, a.gemm[1])) return hipErrorInvalidValue;
-  a.gemm[1].actp = (const u32x4*)c.apk;
   a.gemm[1].epi = EPI_RESID;
-  a.gemm[1].out = c.xres;
   a.gemm[1].ldo = c.d_model;
-  a.gemm[1].outp = (u32x4*)c.xpk;
-  a.gemm[1].ssq_out = c.ssq;
   a.gemm[2] = base;
   if (!team_shape(2 * c.d_ffn, c.d_model, grid, a.gemm[2])) return hipErrorInvalidValue;
-  a.gemm[2].actp = (const u32x4*)c.xpk;
-  a.gemm[2].ssq_in = c.ssq;
   a.gemm[2].ssq_parts = c.d_model / 16;
   a.gemm[2].epi = EPI_SWIGLU;
-  a.gemm[2].outp = (u32x4*)c.gpk;
   a.gemm[3] = base;
   if (!team_shape(c.d_model, c.d_ffn, grid, a.gemm[3])) return hipErrorInvalidValue;
-  a.gemm[3].actp = (const u32x4*)c.gpk;
   a.gemm[3].epi = EPI_RESID;
-  a.gemm[3].out = c.xres;
   a.gemm[3].ldo = c.d_model;
-  a.gemm[3].outp = (u32x4*)c.xpk;
-  a.gemm[3].ssq_out = c.ssq;
 
   size_t lds_floats = attn_lds_floats(c.head_dim);
   for (const GemmArgs* g : {&a.gemm[0], &a.gemm[1], &a.gemm[2], &a.gemm[3]}) {
