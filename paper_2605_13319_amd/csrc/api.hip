@@ -56,7 +56,7 @@ struct pipesd_model {
   int32_t* result_host = nullptr;  // pinned
   std::vector<void*> owned;
   // fused layer kernel (bf16, passes of up to 16 rows)
-  void* layer_weights_dev = nullptr;
+  LayerSlabs slabs{};
   unsigned* bar = nullptr;
   unsigned long long* step_clock = nullptr;  // [4 * n_layers + 1] clocks of the last fused launch
   bool steps_recorded = false;
@@ -158,9 +158,32 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     PackSrc ps{{(const uint16_t*)w->lm_head, nullptr, nullptr}, {V, 0, 0}};
     HIP_TRY(launch_pack_bf16(ps, 1, d, PACK_PLAIN, 0, m->lm_head, nt, nullptr));
   }
+  // bf16: one slab per kind of tensor, layer l at l * (bytes of one layer), so that device code
+  // reaches a layer's weights by arithmetic instead of through a pointer table
+  LayerSlabs& sl = m->slabs;
+  if (c.dtype == PIPESD_BF16) {
+    sl.qkv_bytes = (size_t)nqkv * d * e;
+    sl.o_bytes = (size_t)d * qd * e;
+    sl.gu_bytes = (size_t)2 * F * d * e;
+    sl.down_bytes = (size_t)d * F * e;
+    sl.norm_bytes = (size_t)d * 4;
+    if ((rc = dev_alloc(m, (void**)&sl.wqkv, sl.qkv_bytes * L))) return rc;
+    if ((rc = dev_alloc(m, (void**)&sl.wo, sl.o_bytes * L))) return rc;
+    if ((rc = dev_alloc(m, (void**)&sl.wgu, sl.gu_bytes * L))) return rc;
+    if ((rc = dev_alloc(m, (void**)&sl.wdown, sl.down_bytes * L))) return rc;
+    if ((rc = dev_alloc(m, (void**)&sl.attn_norm, sl.norm_bytes * L))) return rc;
+    if ((rc = dev_alloc(m, (void**)&sl.ffn_norm, sl.norm_bytes * L))) return rc;
+  }
   for (int l = 0; l < L; ++l) {
-    if ((rc = copy_dev(m, (void**)&m->attn_norm[l], w->attn_norm[l], (size_t)d * 4))) return rc;
-    if ((rc = copy_dev(m, (void**)&m->ffn_norm[l], w->ffn_norm[l], (size_t)d * 4))) return rc;
+    if (c.dtype == PIPESD_BF16) {
+      m->attn_norm[l] = (float*)(sl.attn_norm + l * sl.norm_bytes);
+      m->ffn_norm[l] = (float*)(sl.ffn_norm + l * sl.norm_bytes);
+      HIP_TRY(hipMemcpy(m->attn_norm[l], w->attn_norm[l], sl.norm_bytes, hipMemcpyDeviceToDevice));
+      HIP_TRY(hipMemcpy(m->ffn_norm[l], w->ffn_norm[l], sl.norm_bytes, hipMemcpyDeviceToDevice));
+    } else {
+      if ((rc = copy_dev(m, (void**)&m->attn_norm[l], w->attn_norm[l], (size_t)d * 4))) return rc;
+      if ((rc = copy_dev(m, (void**)&m->ffn_norm[l], w->ffn_norm[l], (size_t)d * 4))) return rc;
+    }
     if (c.dtype == PIPESD_F32) {
       if ((rc = dev_alloc(m, &m->wqkv[l], (size_t)nqkv * d * e))) return rc;
       char* p = (char*)m->wqkv[l];
@@ -174,16 +197,16 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
       HIP_TRY(hipMemcpy(p + (size_t)F * d * e, w->w_up[l], (size_t)F * d * e, hipMemcpyDeviceToDevice));
       if ((rc = copy_dev(m, &m->wdown[l], w->w_down[l], (size_t)d * F * e))) return rc;
     } else {
-      if ((rc = dev_alloc(m, &m->wqkv[l], (size_t)nqkv * d * e))) return rc;
+      m->wqkv[l] = sl.wqkv + l * sl.qkv_bytes;
+      m->wo[l] = sl.wo + l * sl.o_bytes;
+      m->wgu[l] = sl.wgu + l * sl.gu_bytes;
+      m->wdown[l] = sl.wdown + l * sl.down_bytes;
       PackSrc pq{{(const uint16_t*)w->wq[l], (const uint16_t*)w->wk[l], (const uint16_t*)w->wv[l]}, {qd, kvd, kvd}};
       HIP_TRY(launch_pack_bf16(pq, 3, d, PACK_HALVES, c.head_dim / 2, m->wqkv[l], nqkv / 16, nullptr));
-      if ((rc = dev_alloc(m, &m->wo[l], (size_t)d * qd * e))) return rc;
       PackSrc po{{(const uint16_t*)w->wo[l], nullptr, nullptr}, {d, 0, 0}};
       HIP_TRY(launch_pack_bf16(po, 1, qd, PACK_PLAIN, 0, m->wo[l], d / 16, nullptr));
-      if ((rc = dev_alloc(m, &m->wgu[l], (size_t)2 * F * d * e))) return rc;
       PackSrc pg{{(const uint16_t*)w->w_gate[l], (const uint16_t*)w->w_up[l], nullptr}, {F, F, 0}};
       HIP_TRY(launch_pack_bf16(pg, 2, d, PACK_HALVES, F, m->wgu[l], 2 * F / 16, nullptr));
-      if ((rc = dev_alloc(m, &m->wdown[l], (size_t)d * F * e))) return rc;
       PackSrc pd{{(const uint16_t*)w->w_down[l], nullptr, nullptr}, {d, 0, 0}};
       HIP_TRY(launch_pack_bf16(pd, 1, F, PACK_PLAIN, 0, m->wdown[l], d / 16, nullptr));
     }
@@ -215,17 +238,6 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     if ((rc = dev_alloc(m, (void**)&m->arena.base, arena_bytes))) return rc;
     HIP_TRY(hipMemset(m->arena.base, 0, arena_bytes));
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
-    std::vector<const void*> lw((size_t)L * 6);
-    for (int l = 0; l < L; ++l) {
-      lw[l * 6 + 0] = m->wqkv[l];
-      lw[l * 6 + 1] = m->wo[l];
-      lw[l * 6 + 2] = m->wgu[l];
-      lw[l * 6 + 3] = m->wdown[l];
-      lw[l * 6 + 4] = m->attn_norm[l];
-      lw[l * 6 + 5] = m->ffn_norm[l];
-    }
-    if ((rc = dev_alloc(m, &m->layer_weights_dev, lw.size() * sizeof(void*)))) return rc;
-    HIP_TRY(hipMemcpy(m->layer_weights_dev, lw.data(), lw.size() * sizeof(void*), hipMemcpyHostToDevice));
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
     HIP_TRY(hipMemset(m->bar, 0, 4096));
   }
@@ -541,7 +553,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
   bool fused = false;
   if (c.dtype == PIPESD_BF16 && m->fused_enabled) {
     LayersCall lc{};
-    lc.layer_weights = m->layer_weights_dev;
+    lc.slabs = m->slabs;
     lc.final_norm = m->final_norm;
     lc.n_layers = c.n_layers;
     lc.m = rows;

@@ -164,8 +164,12 @@ struct ActArena {
 size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn);  // fills offsets; returns bytes
 
 // ---- all decoder layers of a pass in one cooperative kernel (bf16, up to 16 rows) ----
+struct LayerSlabs {  // bf16 models: layer l of each tensor kind sits at base + l * bytes
+  char *wqkv, *wo, *wgu, *wdown, *attn_norm, *ffn_norm;
+  size_t qkv_bytes, o_bytes, gu_bytes, down_bytes, norm_bytes;
+};
 struct LayersCall {
-  const void* layer_weights;  // device array of per-layer {wqkv, wo, wgu, wdown, attn_norm, ffn_norm} pointers
+  LayerSlabs slabs;
   const float* final_norm;
   int n_layers, m, start_pos, n_q_heads, head_dim, d_model, q_dim, d_ffn;
   float eps;

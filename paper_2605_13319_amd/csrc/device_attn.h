@@ -37,50 +37,63 @@ __device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf
   lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
 }
 
-constexpr size_t attn_lds_floats(int hd) { return (size_t)(kAttnWaves / 2) * 16 * (hd + 4) + 2 * (kAttnWaves / 2) * 16; }
+constexpr size_t attn_lds_floats(int hd) { return (size_t)kAttnWaves * 16 * (hd + 4) + 2 * kAttnWaves * 16; }
 
-// Task (kv_head, split) = 8 waves x 32 tokens.  A wave loads its 32 tokens' keys and values once
-// into registers, then walks the 16-row tiles of the query rows that share the KV head; per tile
-// the eight waves' (max, sum, O) are merged pairwise through LDS and written as the split's
-// partial.  All 8 waves of the workgroup must call this together.
+// Task (kv_head, split, query tile) = 8 waves x 32 tokens against 16 of the query rows that share
+// the KV head (row rr of the head group is head kvh*group + rr/m, pass row rr%m).  Everything the
+// task needs is requested up front (its keys, values and queries), each wave computes its 32
+// tokens' (max, sum, O), and after ONE workgroup barrier the eight results are merged by all 512
+// threads, waves in index order, and written as the split's partial.  All 8 waves of the workgroup
+// must call this together; the caller separates two calls on the same LDS by a barrier.
 template <int HD, bool CO>
 __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int layer, int m, int start_pos,
-                                          int n_q_heads, int nsplit, float* part, int kvh, int split, float* lds) {
+                                          int n_q_heads, int nsplit, float* part, int kvh, int split, int qt,
+                                          float* lds) {
   constexpr int KSQ = HD / 32, HT = HD / 16, ROW = HD + 4;
   float(*o_lds)[16][ROW] = (float(*)[16][ROW])lds;
-  float(*m_lds)[16] = (float(*)[16])(lds + (size_t)(kAttnWaves / 2) * 16 * ROW);
-  float(*l_lds)[16] = m_lds + kAttnWaves / 2;
+  float(*m_lds)[16] = (float(*)[16])(lds + (size_t)kAttnWaves * 16 * ROW);
+  float(*l_lds)[16] = m_lds + kAttnWaves;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int group = n_q_heads / kv.n_kv_heads;
-  const int R = group * m, NQ = (R + 15) / 16;
+  const int R = group * m;
   const int total = start_pos + m;
   const int tok0 = split * kAttnWgTokens + w * 32;
   const uint16_t* pool = (const uint16_t*)kv.pool;
   const float scale = 1.0f / sqrtf((float)HD);
 
-  // keys and values of this wave's 32 tokens; tokens at or beyond `total` read as zero
+  // ---- requests: keys and values of this wave's 32 tokens, queries of row tile qt ----
+  au32x4 kraw[2][KSQ];
+  au32x2 vlo[HT], vhi[HT];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int tb = tok0 + tt * 16;
+    const int blk = kv.table[tb < total ? tb / kBlockTokens : 0];
+    const int64_t base = (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
+#pragma unroll
+    for (int s = 0; s < KSQ; ++s)
+      kraw[tt][s] = *(const au32x4*)(pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8);
+#pragma unroll
+    for (int j = 0; j < HT; ++j) {
+      const au32x2 v = *(const au32x2*)(pool + base + kv.v_offset + ((int64_t)kvh * HD + j * 16 + c) * kBlockTokens + g * 4);
+      if (tt == 0) vlo[j] = v; else vhi[j] = v;
+    }
+  }
+  const int rr = qt * 16 + c;
+  const bool row_ok = rr < R;
+  const int gq = row_ok ? rr / m : 0, r = row_ok ? rr % m : 0;
+  const int head = kvh * group + gq;
+  au32x4 qa[KSQ], qb[KSQ];
+#pragma unroll
+  for (int s = 0; s < KSQ; ++s) {
+    const float* qp = q + ((size_t)r * n_q_heads + head) * HD + s * 32 + g * 8;
+    qa[s] = *(const au32x4*)qp;
+    qb[s] = *(const au32x4*)(qp + 4);
+  }
+
+  // ---- operands: tokens at or beyond `total` read as zero ----
   bf16x8 kf[2][KSQ], vf[HT];
   {
-    au32x4 kraw[2][KSQ];
-    au32x2 vlo[HT], vhi[HT];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int tb = tok0 + tt * 16;
-      const int blk = kv.table[tb < total ? tb / kBlockTokens : 0];
-      const int64_t base = (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
-#pragma unroll
-      for (int s = 0; s < KSQ; ++s) {
-        const uint16_t* kp = pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8;
-        kraw[tt][s] = *(const au32x4*)kp;
-      }
-#pragma unroll
-      for (int j = 0; j < HT; ++j) {
-        const uint16_t* vp = pool + base + kv.v_offset + ((int64_t)kvh * HD + j * 16 + c) * kBlockTokens + g * 4;
-        const au32x2 v = *(const au32x2*)vp;
-        if (tt == 0) vlo[j] = v; else vhi[j] = v;
-      }
-    }
     unsigned long long keep[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -97,106 +110,87 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
       vf[j] = __builtin_bit_cast(bf16x8, au32x4{vlo[j].x & (unsigned)keep[0], vlo[j].y & (unsigned)(keep[0] >> 32),
                                                 vhi[j].x & (unsigned)keep[1], vhi[j].y & (unsigned)(keep[1] >> 32)});
   }
+  bf16x8 qhi[KSQ], qlo[KSQ];
+#pragma unroll
+  for (int s = 0; s < KSQ; ++s) {
+    // (whole-vector casts: a bit cast of one vector element reads element 0 with this compiler)
+    const f32x4 fa = __builtin_bit_cast(f32x4, qa[s]), fb = __builtin_bit_cast(f32x4, qb[s]);
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[i] = row_ok ? fa[i] : 0.f;
+      v[i + 4] = row_ok ? fb[i] : 0.f;
+    }
+    split_hi_lo8(v, qhi[s], qlo[s]);
+  }
 
-  for (int qt = 0; qt < NQ; ++qt) {
-    const int rr = qt * 16 + c;
-    const bool row_ok = rr < R;
-    const int gq = row_ok ? rr / m : 0, r = row_ok ? rr % m : 0;
-    const int head = kvh * group + gq;
-    bf16x8 qhi[KSQ], qlo[KSQ];
-    {
-      au32x4 qa[KSQ], qb[KSQ];
+  // ---- scores of query row c against tokens tok0 + tt*16 + g*4 + i ----
+  float sc[8];
+  const int pos_q = start_pos + r;
 #pragma unroll
-      for (int s = 0; s < KSQ; ++s) {
-        const float* qp = q + ((size_t)r * n_q_heads + head) * HD + s * 32 + g * 8;
-        qa[s] = *(const au32x4*)qp;
-        qb[s] = *(const au32x4*)(qp + 4);
-      }
+  for (int tt = 0; tt < 2; ++tt) {
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < KSQ; ++s) {
-        // (whole-vector casts: a bit cast of one vector element reads element 0 with this compiler)
-        const f32x4 fa = __builtin_bit_cast(f32x4, qa[s]), fb = __builtin_bit_cast(f32x4, qb[s]);
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          v[i] = row_ok ? fa[i] : 0.f;
-          v[i + 4] = row_ok ? fb[i] : 0.f;
-        }
-        split_hi_lo8(v, qhi[s], qlo[s]);
-      }
+    for (int s = 0; s < KSQ; ++s) {
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qhi[s], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qlo[s], acc, 0, 0, 0);
     }
-    // scores of query row c against tokens tok0 + tt*16 + g*4 + i
-    float sc[8];
-    const int pos_q = start_pos + r;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < KSQ; ++s) {
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qhi[s], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qlo[s], acc, 0, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int t = tok0 + tt * 16 + g * 4 + i;
-        sc[tt * 4 + i] = (row_ok && t <= pos_q) ? acc[i] * scale : -INFINITY;
-      }
+    for (int i = 0; i < 4; ++i) {
+      const int t = tok0 + tt * 16 + g * 4 + i;
+      sc[tt * 4 + i] = (row_ok && t <= pos_q) ? acc[i] * scale : -INFINITY;
     }
-    float m_run = sc[0];
+  }
+  float m_run = sc[0];
 #pragma unroll
-    for (int i = 1; i < 8; ++i) m_run = fmaxf(m_run, sc[i]);
-    m_run = fmaxf(m_run, __shfl_xor(m_run, 16, 64));
-    m_run = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
-    float pv[8], l_run = 0.f;
+  for (int i = 1; i < 8; ++i) m_run = fmaxf(m_run, sc[i]);
+  m_run = fmaxf(m_run, __shfl_xor(m_run, 16, 64));
+  m_run = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+  float pv[8], l_run = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - m_run);
-      l_run += pv[i];
+  for (int i = 0; i < 8; ++i) {
+    pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - m_run);
+    l_run += pv[i];
+  }
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+  bf16x8 phi, plo;
+  split_hi_lo8(pv, phi, plo);
+#pragma unroll
+  for (int j = 0; j < HT; ++j) {
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], phi, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], plo, acc, 0, 0, 0);
+    *(f32x4*)&o_lds[w][c][j * 16 + g * 4] = acc;  // O[query c][element j*16 + g*4 + i]
+  }
+  if (g == 0) {
+    m_lds[w][c] = m_run;
+    l_lds[w][c] = l_run;
+  }
+  __syncthreads();
+
+  // ---- merge of the eight waves: thread -> (query row, 4 consecutive elements), waves in index order ----
+  constexpr int TPR = HD / 4;  // threads per row: all 512 threads for h = 128, the first 256 for h = 64
+  const int mr = tid / TPR, e0 = (tid % TPR) * 4;
+  if (mr < 16) {
+    float M = m_lds[0][mr];
+#pragma unroll
+    for (int ww = 1; ww < kAttnWaves; ++ww) M = fmaxf(M, m_lds[ww][mr]);
+    float L = 0.f;
+    f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ww = 0; ww < kAttnWaves; ++ww) {
+      const float mw = m_lds[ww][mr];
+      const float sw = (mw == -INFINITY) ? 0.f : expf(mw - M);
+      L += l_lds[ww][mr] * sw;
+      o += *(const f32x4*)&o_lds[ww][mr][e0] * sw;
     }
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    bf16x8 phi, plo;
-    split_hi_lo8(pv, phi, plo);
-    f32x4 o[HT];
-#pragma unroll
-    for (int j = 0; j < HT; ++j) {
-      f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], phi, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[j], plo, acc, 0, 0, 0);
-      o[j] = acc;  // O[query c][element j*16 + g*4 + i]
-    }
-    // merge the eight waves pairwise through LDS: (4..7 -> 0..3), (2,3 -> 0,1), (1 -> 0)
-#pragma unroll
-    for (int span = kAttnWaves / 2; span >= 1; span >>= 1) {
-      if (w >= span && w < 2 * span) {
-#pragma unroll
-        for (int j = 0; j < HT; ++j) *(f32x4*)&o_lds[w - span][c][j * 16 + g * 4] = o[j];
-        if (g == 0) {
-          m_lds[w - span][c] = m_run;
-          l_lds[w - span][c] = l_run;
-        }
-      }
-      __syncthreads();
-      if (w < span) {
-        const float mp = m_lds[w][c], lp = l_lds[w][c];
-        const float nm = fmaxf(m_run, mp);
-        const float so = (m_run == -INFINITY) ? 0.f : expf(m_run - nm);
-        const float sp = (mp == -INFINITY) ? 0.f : expf(mp - nm);
-        l_run = l_run * so + lp * sp;
-        m_run = nm;
-#pragma unroll
-        for (int j = 0; j < HT; ++j) {
-          const f32x4 op = *(const f32x4*)&o_lds[w][c][j * 16 + g * 4];
-          o[j] = o[j] * so + op * sp;
-        }
-      }
-      __syncthreads();
-    }
-    if (w == 0 && row_ok) {
-      float* dst = part + (((size_t)head * m + r) * nsplit + split) * (HD + kPartPad);
-#pragma unroll
-      for (int j = 0; j < HT; ++j) Xwg<CO>::st4f(dst + j * 16 + g * 4, o[j]);
-      if (g == 0) Xwg<CO>::st4f(dst + HD, f32x4{m_run, l_run, 0.f, 0.f});
+    const int rr2 = qt * 16 + mr;
+    if (rr2 < R) {
+      const int head2 = kvh * group + rr2 / m, r2 = rr2 % m;
+      float* dst = part + (((size_t)head2 * m + r2) * nsplit + split) * (HD + kPartPad);
+      Xwg<CO>::st4f(dst + e0, o);
+      if (e0 == 0) Xwg<CO>::st4f(dst + HD, f32x4{M, L, 0.f, 0.f});
     }
   }
 }

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
                                                                     int start_pos, int n_q_heads, int nsplit,
                                                                     float* part) {
   extern __shared__ float lds[];
-  attn_task<HD, false>(q, kv, layer, m, start_pos, n_q_heads, nsplit, part, blockIdx.x, blockIdx.y, lds);
+  attn_task<HD, false>(q, kv, layer, m, start_pos, n_q_heads, nsplit, part, blockIdx.x, blockIdx.y, blockIdx.z, lds);
 }
 
 __global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* part, int m, int n_q_heads, int h,
@@ -147,15 +147,26 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
                                                                 c.chunk, nsplit, c.part);
   } else {
     const int nsp = attn_nsplit(total, kAttnWgTokens);
-    dim3 grid(c.kv.n_kv_heads, nsp);
+    const int group = c.n_q_heads / c.kv.n_kv_heads;
+    dim3 grid(c.kv.n_kv_heads, nsp, (group * c.m + 15) / 16);
+    if (h != 128 && h != 64) return hipErrorInvalidValue;
+    const size_t lds = attn_lds_floats(h) * sizeof(float);
+    static bool lds_allowed = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+    if (!lds_allowed) {
+      hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)(attn_lds_floats(128) * sizeof(float)));
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)attn_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(attn_lds_floats(64) * sizeof(float)));
+      if (e != hipSuccess) return e;
+      lds_allowed = true;
+    }
     if (h == 128)
-      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, attn_lds_floats(128) * sizeof(float), st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
-                                                              c.part);
-    else if (h == 64)
-      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, attn_lds_floats(64) * sizeof(float), st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
-                                                             c.part);
+      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
+                                                                c.part);
     else
-      return hipErrorInvalidValue;
+      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
+                                                               c.part);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -20,13 +20,8 @@
 
 namespace pipesd {
 
-struct LayerWeights {
-  const u32x4 *wqkv, *wo, *wgu, *wdown;
-  const float *attn_norm, *ffn_norm;
-};
-
 struct LayersArgs {
-  const LayerWeights* lw;  // device array [n_layers]
+  LayerSlabs sl;
   const float* final_norm;
   int n_layers;
   GemmArgs gemm[4];  // QKV, O, gate/up, down; per-layer fields (weights, buffers, gains) are filled in on the device
@@ -43,18 +38,24 @@ constexpr unsigned kBarMaxPolls = 2000000u;  // x ~0.1-0.2 us per poll: a fracti
 // Workgroup barrier without memory fences: in-flight (hand-issued) weight loads must stay in flight.
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// Device-wide barrier.  The caller has drained its stores (Xwg<true>::drain) before requesting the
-// next weights.  Returns false (to every thread of the workgroup) if it timed out or another
-// workgroup reported an error.
-__device__ __forceinline__ bool grid_sync(unsigned* bar, int* err, unsigned& gen, int* fail_lds) {
+// Device-wide barrier in two halves, so that work which does not depend on other workgroups (the
+// request for the next projection's first weights) can sit between "I am done" and "is everybody
+// done".  grid_arrive: every wave has drained its stores (Xwg<true>::drain) before calling.
+// grid_wait returns false (to every thread of the workgroup) if it timed out or another workgroup
+// reported an error.
+__device__ __forceinline__ void grid_arrive(unsigned* bar, unsigned& gen) {
   ++gen;
   wg_barrier();
   if (threadIdx.x == 0) {
-    int fail = 0;
     const unsigned grp = blockIdx.x % kBarGroups, per = gridDim.x / kBarGroups;
     unsigned* gc = bar + 32 * (1 + grp);
     const unsigned prev = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (prev == gen * per - 1u) __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+__device__ __forceinline__ bool grid_wait(unsigned* bar, int* err, unsigned gen, int* fail_lds) {
+  if (threadIdx.x == 0) {
+    int fail = 0;
     unsigned polls = 0;
     while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gen * kBarGroups) {
       __builtin_amdgcn_s_sleep(1);
@@ -71,6 +72,10 @@ __device__ __forceinline__ bool grid_sync(unsigned* bar, int* err, unsigned& gen
   wg_barrier();
   return *fail_lds == 0;
 }
+__device__ __forceinline__ bool grid_sync(unsigned* bar, int* err, unsigned& gen, int* fail_lds) {
+  grid_arrive(bar, gen);
+  return grid_wait(bar, err, gen, fail_lds);
+}
 
 __device__ __forceinline__ TeamPos team_pos(const GemmArgs& g, int w) {
   const int tpw = 8 / g.W;  // teams per workgroup (8 waves)
@@ -85,36 +90,36 @@ __device__ __forceinline__ TeamPos team_pos(const GemmArgs& g, int w) {
 
 // per-layer fields of GEMM `ph` (0 QKV, 1 O, 2 gate/up, 3 down) of layer l
 __device__ __forceinline__ void patch_layer(GemmArgs& g, const LayersArgs& a, int l, int ph) {
-  const LayerWeights lw = a.lw[l];
+  const LayerSlabs& sl = a.sl;
   const ActArena& ar = a.arena;
   g.layer = l;
   if (ph == 0) {
-    g.wp = lw.wqkv;
+    g.wp = (const u32x4*)(sl.wqkv + l * sl.qkv_bytes);
     g.actp = (const u32x4*)ar.xa(l);
     g.ssq_in = ar.sa(l);
     if (l > 0) g.ssq_parts = a.gemm[1].ntiles;  // after the first layer the sums of squares come per n-tile
     g.out = ar.q(l);
   } else if (ph == 1) {
-    g.wp = lw.wo;
+    g.wp = (const u32x4*)(sl.wo + l * sl.o_bytes);
     g.actp = (const u32x4*)ar.ap(l);
     g.res_in = ar.ra(l);
     g.out = ar.rb(l);
     g.outp = (u32x4*)ar.xb(l);
     g.ssq_out = ar.sb(l);
-    g.gain_next = lw.ffn_norm;
+    g.gain_next = (const float*)(sl.ffn_norm + l * sl.norm_bytes);
   } else if (ph == 2) {
-    g.wp = lw.wgu;
+    g.wp = (const u32x4*)(sl.wgu + l * sl.gu_bytes);
     g.actp = (const u32x4*)ar.xb(l);
     g.ssq_in = ar.sb(l);
     g.outp = (u32x4*)ar.gp(l);
   } else {
-    g.wp = lw.wdown;
+    g.wp = (const u32x4*)(sl.wdown + l * sl.down_bytes);
     g.actp = (const u32x4*)ar.gp(l);
     g.res_in = ar.rb(l);
     g.out = ar.ra(l + 1);
     g.outp = (u32x4*)ar.xa(l + 1);
     g.ssq_out = ar.sa(l + 1);
-    g.gain_next = l + 1 < a.n_layers ? a.lw[l + 1].attn_norm : a.final_norm;
+    g.gain_next = l + 1 < a.n_layers ? (const float*)(sl.attn_norm + (l + 1) * sl.norm_bytes) : a.final_norm;
   }
 }
 
@@ -145,10 +150,13 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
       // attention over the paged cache: tasks (kv head, 256-token split), then the split merge
       const GemmArgs& gq = a.gemm[0];
       if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
-      const int ntasks = gq.kv.n_kv_heads * a.nsplit;
-      for (int task = blockIdx.x; task < ntasks; task += gridDim.x)
+      const int nkv = gq.kv.n_kv_heads, nqt = (gq.n_q_heads / nkv * gq.m + 15) / 16;
+      const int ntasks = nkv * a.nsplit * nqt;
+      for (int task = blockIdx.x; task < ntasks; task += gridDim.x) {
         attn_task<HD, true>(a.arena.q(l), gq.kv, l, gq.m, gq.start_pos, gq.n_q_heads, a.nsplit, a.arena.partials(l),
-                            task % gq.kv.n_kv_heads, task / gq.kv.n_kv_heads, lds);
+                            task % nkv, (task / nkv) % a.nsplit, task / (nkv * a.nsplit), lds);
+        __syncthreads();  // the task's LDS is free again
+      }
       Xwg<true>::drain();
       if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
       const int nmerge = gq.m * gq.n_q_heads * (HD / 8);
@@ -158,10 +166,11 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
     }
     if (step + 1 < nsteps) {
       // the next projection's first weights are requested before the barrier: they depend on nothing
+      grid_arrive(a.bar, gen);
       GemmArgs g = a.gemm[(step + 1) & 3];
       patch_layer(g, a, (step + 1) >> 2, (step + 1) & 3);
       gemm_prefetch<KS>(g, team_pos(g, w), lane, af);
-      if (!grid_sync(a.bar, a.err, gen, &fail_lds)) return;
+      if (!grid_wait(a.bar, a.err, gen, &fail_lds)) return;
     }
   }
   if (a.step_clock != nullptr && blockIdx.x == 0 && tid == 0) a.step_clock[nsteps] = wall_clock64();
@@ -234,7 +243,7 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   if (!layers_fused_supported(c)) return hipErrorInvalidValue;
   const int grid = device_cu_count();
   LayersArgs a{};
-  a.lw = (const LayerWeights*)c.layer_weights;
+  a.sl = c.slabs;
   a.final_norm = c.final_norm;
   a.n_layers = c.n_layers;
   a.arena = c.arena;
@@ -279,6 +288,14 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   hipError_t e = hipMemsetAsync(c.bar, 0, (1 + kBarGroups) * 32 * sizeof(unsigned), st);  // counters; the flag is sticky
   if (e != hipSuccess) return e;
   void* args[] = {&a};
+  static bool lds_allowed = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
+  if (!lds_allowed) {
+    const int cap = (int)(attn_lds_floats(128) * sizeof(float)) > 64 * 1024 ? (int)(attn_lds_floats(128) * sizeof(float)) : 64 * 1024;
+    e = hipFuncSetAttribute((const void*)layers_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)layers_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, cap);
+    if (e != hipSuccess) return e;
+    lds_allowed = true;
+  }
   if (c.head_dim == 128)
     return hipLaunchCooperativeKernel((const void*)layers_kernel<128>, dim3(grid), dim3(512), args, lds, st);
   return hipLaunchCooperativeKernel((const void*)layers_kernel<64>, dim3(grid), dim3(512), args, lds, st);
