@@ -75,6 +75,8 @@ __device__ __forceinline__ u32x4 act_load(const u32x4* p) {
   asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
   return v;
 }
+constexpr int kSsqPerLane = 8;  // sums of squares per lane and row: up to 512 producer tiles (d_model <= 8192)
+
 template <int N>
 __device__ __forceinline__ void wait_younger(u32x4& v) {
   asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(N));
@@ -159,8 +161,10 @@ __device__ __forceinline__ f32x4 shfl4(f32x4 v, int src) {
 // activation row `row` with weight rows gg*4 .. gg*4+3 of tile t.  Partner rows (i, i+8) sit 32 lanes
 // apart and the two halves of an 8-column group 16 lanes apart, so pairs are joined by shuffles.
 // Every lane of the wave must call this (rows beyond the pass only skip the stores).
+// RESID: `pre` says that pre_res / pre_gain already hold this quad's residual and gain values.
 template <bool CO>
-__device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row, int lane, f32x4 v, float rstd) {
+__device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row, int lane, f32x4 v, float rstd,
+                                              bool pre, f32x4 pre_res, f32x4 pre_gain) {
   const int gg = lane >> 4;
   const bool live = row < a.m;
   switch (a.epi) {
@@ -180,14 +184,14 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
       const size_t at = (size_t)row * a.ldo + t * 16 + gg * 4;
       f32x4 x = f32x4{0.f, 0.f, 0.f, 0.f};
       if (live) {
-        x = *(const f32x4*)(a.res_in + at) + v;
+        x = (pre ? pre_res : *(const f32x4*)(a.res_in + at)) + v;
         Xwg<CO>::st4f(a.out + at, x);
       }
       float sq = x[0] * x[0] + x[1] * x[1] + x[2] * x[2] + x[3] * x[3];
       sq += __shfl_xor(sq, 16, 64);
       sq += __shfl_xor(sq, 32, 64);
-      const float4 gn = *(const float4*)(a.gain_next + t * 16 + gg * 4);
-      const f32x4 y = f32x4{x[0] * gn.x, x[1] * gn.y, x[2] * gn.z, x[3] * gn.w};
+      const f32x4 gn = pre ? pre_gain : *(const f32x4*)(a.gain_next + t * 16 + gg * 4);
+      const f32x4 y = x * gn;
       const f32x4 hi4 = shfl4(y, lane + 16);  // columns +4..+7 of the 8-column group
       if (live && (gg & 1) == 0) {
         const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
@@ -304,20 +308,18 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
   const int iters = (ngroups + tp.nteams - 1) / tp.nteams;
   const int bc = lane & 15, bg = lane >> 4;
 
-  // activation fragments of the current K slice, awaited in full (they and the first weight chunk
-  // are all needed before the first MFMA); lanes whose row is not part of the pass load nothing:
-  // their MFMA columns are never stored
+  // activation fragments of the current K slice (hi halves, then lo halves), awaited in full: they
+  // and the first weight chunk are all needed before the first MFMA.  Lanes whose row is not part
+  // of the pass load nothing: their MFMA columns are never stored.
   u32x4 bhi[MT][KSTEPS], blo[MT][KSTEPS];
-  auto load_act = [&](int slice) {
+  auto request_act = [&](int slice, int hl, u32x4 (&b)[MT][KSTEPS]) {
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        if (mt * 16 + bc < a.m) {
-          bhi[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, 0, bc, bg));
-          blo[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, 1, bc, bg));
-        }
-      }
+      for (int mt = 0; mt < MT; ++mt)
+        if (mt * 16 + bc < a.m) b[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, hl, bc, bg));
+  };
+  auto await_act = [&]() {
 #pragma unroll
     for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
@@ -326,29 +328,85 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         wait_younger<0>(blo[mt][ks]);
       }
   };
+  // Fused norm: rstd per row from the producer's partial sums of squares, added in index order.  A
+  // wave takes two rows at a time, up to kSsqPerLane partial sums per lane and row (the host checks
+  // ssq_parts <= 64 * kSsqPerLane).  Everything the GEMM needs from the step before it is requested
+  // in one go so that it arrives within one memory latency: the sums, the first quad's residual and
+  // gain values (residual epilogue), the activation fragments.  Request and wait of the hand-issued
+  // loads stay on one straight code path: a join of two paths would let the compiler copy registers
+  // whose data is still on its way.
   const bool working = tp.active && tp.team < ngroups;
-  if (working && a.P == 1) load_act(tp.wt);
-
-  // fused norm: rstd per row from the producer's partial sums of squares, added in index order
-  if (a.ssq_in != nullptr) {
-    for (int row = w; row < MT * 16; row += nwaves_wg) {
-      float q = 0.f;
-      if (row < a.m)
-        for (int j = lane; j < a.ssq_parts; j += 64) q += a.ssq_in[(size_t)row * a.ssq_stride + j];
+  const bool norm = a.ssq_in != nullptr;
+  float part[2][kSsqPerLane];
+  auto ssq_request = [&](int row0) {
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+      for (int j4 = 0; j4 < kSsqPerLane; ++j4) {
+        const int row = row0 + r2 * nwaves_wg, j = lane + 64 * j4;
+        part[r2][j4] = 0.f;
+        // ("+v": the load lands in the very register that holds the zero of the lanes that skip it)
+        if (norm && row < MT * 16 && row < a.m && j < a.ssq_parts)
+          asm volatile("global_load_dword %0, %1, off" : "+v"(part[r2][j4])
+                       : "v"(a.ssq_in + (size_t)row * a.ssq_stride + j));
+      }
+  };
+  auto ssq_finish = [&](int row0) {
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+      for (int j4 = 0; j4 < kSsqPerLane; ++j4) asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[r2][j4]));
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2) {
+      const int row = row0 + r2 * nwaves_wg;
+      float q = part[r2][0];
+#pragma unroll
+      for (int j4 = 1; j4 < kSsqPerLane; ++j4) q += part[r2][j4];
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
-      if (lane == 0) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+      if (norm && lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+    }
+  };
+  // residual epilogue: residual and gain values of the first quad this lane will finish
+  // (ordinary loads: the compiler's own wait precedes whatever it does with the registers)
+  f32x4 pre_res = f32x4{0.f, 0.f, 0.f, 0.f}, pre_gain = pre_res;
+  bool have_pre = false;
+  if (working && a.epi == EPI_RESID) {
+    const int t0 = tp.team * a.tg, e_first = tp.wt * 64 + lane;
+    if (e_first < min(a.tg, a.ntiles - t0) * MT * 64) {
+      const int tt = e_first / (MT * 64), rem = e_first % (MT * 64), l = rem & 63;
+      const int row = (rem >> 6) * 16 + (l & 15), col = (t0 + tt) * 16 + (l >> 4) * 4;
+      if (row < a.m) pre_res = *(const f32x4*)(a.res_in + (size_t)row * a.ldo + col);
+      pre_gain = *(const f32x4*)(a.gain_next + col);
+      have_pre = true;
     }
   }
-
+  ssq_request(w);
+  if (working && a.P == 1) {
+    request_act(tp.wt, 0, bhi);
+    request_act(tp.wt, 1, blo);
+    await_act();
+  }
+  ssq_finish(w);
+  if (norm)
+    for (int row0 = w + 2 * nwaves_wg; row0 < MT * 16; row0 += 2 * nwaves_wg) {
+      ssq_request(row0);
+      ssq_finish(row0);
+    }
   for (int it = 0; it < iters; ++it) {
     const int grp = tp.team + it * tp.nteams;
     const bool on = tp.active && grp < ngroups;
     const int t0 = grp * a.tg;
     const int nt_g = on ? min(a.tg, a.ntiles - t0) : 0;
+    const int e_first = tp.wt * 64 + lane;
+    const bool pre = it == 0 && have_pre;
     if (on) {
       for (int p = 0; p < a.P; ++p) {
-        if (a.P > 1) load_act(p * a.W + tp.wt);
+        if (a.P > 1) {
+          request_act(p * a.W + tp.wt, 0, bhi);
+          request_act(p * a.W + tp.wt, 1, blo);
+          await_act();
+        }
         for (int t = 0; t < nt_g; ++t) {
           const u32x4* nxt = nullptr;
           if (t + 1 < nt_g) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0 + t + 1, p);
@@ -374,13 +432,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
     // one lane per 4 tile rows x 1 activation row: add the W partial tiles, then finish with the wave
     if (on) {
       const int nquads = nt_g * MT * 64;
-      for (int e = tp.wt * 64 + lane; e < nquads; e += a.W * 64) {
+      for (int e = e_first; e < nquads; e += a.W * 64) {
         const int tt = e / (MT * 64), rem = e % (MT * 64), mt = rem >> 6, l = rem & 63;
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int ww = 0; ww < a.W; ++ww) v += red[((size_t)(tt * a.W + ww) * MT + mt) * 64 + l];
         const int row = mt * 16 + (l & 15);
         const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[row] : 1.0f;
-        epilogue_quad<CO>(a, t0 + tt, row, l, v, rstd);
+        epilogue_quad<CO>(a, t0 + tt, row, l, v, rstd, pre && e == e_first, pre_res, pre_gain);
       }
     }
     __syncthreads();  // red is free again
