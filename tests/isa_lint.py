@@ -1,0 +1,109 @@
+"""Lint of a gfx950 ISA listing (hipcc -S) of the library's own kernels.
+
+The weight stream and the activation fragments are loaded by hand-issued (inline asm) loads whose
+completion the compiler does not track.  Between such a load and the s_waitcnt that releases it no
+compiler-generated instruction may touch the destination registers: a copy or a spill there moves
+data that has not arrived yet.  Forward dataflow over basic blocks; the state is the ordered tuple
+of in-flight hand-issued load destinations (oldest first); at joins the longest state wins (states
+from different paths are almost always equal, or one is empty).
+"""
+import re, sys
+def regs(tok):
+    tok = tok.strip()
+    m = re.match(r'v\[(\d+):(\d+)\]', tok)
+    if m: return frozenset(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.match(r'v(\d+)$', tok)
+    if m: return frozenset({int(m.group(1))})
+    return frozenset()
+def parse_function(lines):
+    # returns blocks: list of dict(label, instrs=[(lineno, in_asm, op, rest)], succ=[labels or '+1'])
+    blocks = []; cur = {'label': None, 'ins': [], 'succ': []}
+    in_asm = False
+    for no, ln in lines:
+        if 'ASMSTART' in ln: in_asm = True; continue
+        if 'ASMEND' in ln: in_asm = False; continue
+        s = ln.strip()
+        if not s or s.startswith(';'): continue
+        m = re.match(r'(\.LBB\d+_\d+):', s)
+        if m:
+            if cur['ins'] or cur['label']:
+                if not cur['succ_final']: cur['succ'].append('+1')
+                blocks.append(cur)
+            cur = {'label': m.group(1), 'ins': [], 'succ': []}
+            cur['succ_final'] = False
+            continue
+        if s.startswith('.'): continue
+        cur.setdefault('succ_final', False)
+        t = s.split(None, 1); op = t[0]; rest = t[1].split(';')[0] if len(t) > 1 else ''
+        cur['ins'].append((no, in_asm, op, rest))
+        if op == 's_branch':
+            cur['succ'].append(rest.strip()); cur['succ_final'] = True
+            blocks.append(cur); cur = {'label': None, 'ins': [], 'succ': [], 'succ_final': False}
+        elif op.startswith('s_cbranch'):
+            cur['succ'].append(rest.strip()); cur['succ'].append('+1'); cur['succ_final'] = True
+            blocks.append(cur); cur = {'label': None, 'ins': [], 'succ': [], 'succ_final': False}
+        elif op in ('s_endpgm', 's_setpc_b64'):
+            cur['succ_final'] = True
+            blocks.append(cur); cur = {'label': None, 'ins': [], 'succ': [], 'succ_final': False}
+    if cur['ins'] or cur['label']:
+        blocks.append(cur)
+    return blocks
+def transfer(state, blk, report):
+    st = list(state)
+    for no, in_asm, op, rest in blk['ins']:
+        if op.startswith('s_waitcnt'):
+            mm = re.search(r'vmcnt\((\d+)\)', rest)
+            if mm:
+                n = int(mm.group(1))
+                if n < len(st): st = st[len(st) - n:] if n > 0 else []
+            continue
+        if in_asm and re.match(r'global_load_dword', op):
+            st.append((regs(rest.split(',')[0]), no)); continue
+        if in_asm: continue
+        touched = frozenset()
+        for o in rest.split(','): touched |= regs(o)
+        for d, l in st:
+            if touched & d:
+                report.add((no, op + ' ' + rest.strip(), l)); break
+        # compiler-issued vector memory loads also occupy vmcnt slots: counting them would only make the
+        # hand-issued waits look weaker than they are, so they are ignored here
+    return tuple(st)
+def check(path):
+    raw = open(path).read().split('\n')
+    # split into functions at non-local labels
+    funcs = []; cur = []; name = None
+    for i, ln in enumerate(raw):
+        m = re.match(r'^([A-Za-z_][\w$.]*):', ln)
+        if m and not ln.startswith('.L'):
+            if cur: funcs.append((name, cur))
+            name = m.group(1); cur = []
+        cur.append((i + 1, ln))
+    if cur: funcs.append((name, cur))
+    total = 0
+    for name, lines in funcs:
+        if name is None: continue
+        blocks = parse_function(lines)
+        if not blocks: continue
+        idx = {b['label']: k for k, b in enumerate(blocks) if b['label']}
+        instate = {0: ()}
+        work = [0]; report = set(); iters = 0
+        while work and iters < 20000:
+            iters += 1
+            k = work.pop()
+            out = transfer(instate[k], blocks[k], report)
+            for sname in blocks[k]['succ']:
+                j = k + 1 if sname == '+1' else idx.get(sname)
+                if j is None or j >= len(blocks): continue
+                old = instate.get(j)
+                if old is None or len(out) > len(old):
+                    instate[j] = out; work.append(j)
+        for no, txt, l in sorted(report):
+            print(f"{path}:{no}: '{txt}' touches registers in flight since line {l}  [{name}]")
+        total += len(report)
+    print(path, "suspicious:", total)
+    return total
+if __name__ == "__main__":
+    rc = 0
+    for p in sys.argv[1:]:
+        rc |= 1 if check(p) else 0
+    sys.exit(rc)
