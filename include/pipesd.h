@@ -133,6 +133,22 @@ int pipesd_nav_verify(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t p
                       const int32_t *draft_tokens, int32_t k, const float *draft_probs,
                       const float *uniforms, int32_t *accepted_len, int32_t *next_token, void *stream);
 
+/* One NAV pass for each of n_seqs clients (several edge devices verified by one cloud model,
+ * Appendix I): client i = seq_ids[i] (pairwise distinct, 1 <= n_seqs <= 256) with committed length
+ * prefix_lens[i] and k_per_seq[i] drafts.  draft_tokens_concat (host) holds the clients' drafts one
+ * after the other, uniforms_concat (host) their k_i + 1 uniforms one after the other (a client's
+ * slots are skipped over but not read when it uses token matching); draft_probs_per_seq is a host
+ * array of n_seqs device pointers ([k_i][vocab] fp32 each; a NULL entry, or a NULL array, selects
+ * token matching).  Per client the computation, the result and the state afterwards are those of
+ * pipesd_nav_verify.  All arguments and the pool's free blocks are checked before anything
+ * changes: an error leaves every client as it was.  The passes run one after the other on
+ * `stream`, which is synchronised once; accepted_len and next_token are host arrays [n_seqs]. */
+int pipesd_nav_verify_batch(pipesd_model *model, pipesd_kv *kv, int32_t n_seqs, const int32_t *seq_ids,
+                            const int32_t *prefix_lens, const int32_t *k_per_seq,
+                            const int32_t *draft_tokens_concat, const float *const *draft_probs_per_seq,
+                            const float *uniforms_concat, int32_t *accepted_len, int32_t *next_token,
+                            void *stream);
+
 /* Cut client `seq` back to new_prefix_len committed tokens (1 <= new <= current, else ESTATE); the
  * last kept token becomes pending (Appendix B: buffered drafts that are no longer valid are
  * discarded and drafting restarts from the last accepted token).  Host bookkeeping only. */

@@ -32,6 +32,8 @@ extern "C" const char* pipesd_last_hip_error(void) { return g_hip_msg; }
 // ---------------------------------------------------------------------------------------------
 // handles
 // ---------------------------------------------------------------------------------------------
+constexpr int kMaxBatchResults = 256;  // decisions one batched call can return
+
 struct pipesd_model {
   pipesd_config cfg{};
   bool on_device = false;
@@ -229,7 +231,7 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   if ((rc = dev_alloc(m, (void**)&m->rope_cs, R * c.head_dim * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->row_stats, (R * 64 * 2 + 64) * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->scan_partial, 64 * 8))) return rc;
-  if ((rc = dev_alloc(m, (void**)&m->result_dev, 4 * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->result_dev, (size_t)2 * kMaxBatchResults * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->counters, (size_t)kCounterSlots * 4))) return rc;
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
   if (c.dtype == PIPESD_BF16) {
@@ -241,7 +243,7 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
     HIP_TRY(hipMemset(m->bar, 0, 4096));
   }
-  HIP_TRY(hipHostMalloc((void**)&m->result_host, 64, hipHostMallocDefault));
+  HIP_TRY(hipHostMalloc((void**)&m->result_host, (size_t)(4 + 2 * kMaxBatchResults) * 4, hipHostMallocDefault));
   HIP_TRY(hipDeviceSynchronize());
   return PIPESD_OK;
 }
@@ -737,11 +739,14 @@ static int verify_common(pipesd_model* model, pipesd_kv* kv, int32_t seq, const 
   return rc;
 }
 
-extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t prefix_len,
-                                 const int32_t* draft_tokens, int32_t k, const float* draft_probs,
-                                 const float* uniforms, int32_t* accepted_len, int32_t* next_token, void* stream) {
-  if (!model || !kv || !draft_tokens || !accepted_len || !next_token || !seq_ok(kv, seq) || kv->model != model)
-    return PIPESD_EINVAL;
+constexpr int kMaxBatch = kMaxBatchResults;  // sequences per batched call
+
+// host-side checks of one sequence's verify arguments (argument errors, then, if `state`, the
+// handles' and the sequence's state); changes nothing
+static int check_verify_args(const pipesd_model* model, const pipesd_kv* kv, int32_t seq, int32_t prefix_len,
+                             const int32_t* draft_tokens, int32_t k, const float* draft_probs, const float* uniforms,
+                             bool state = true) {
+  if (!draft_tokens || !seq_ok(kv, seq)) return PIPESD_EINVAL;
   if (k < 1 || k > kMaxRows - 1) return PIPESD_EINVAL;
   if (draft_probs && !uniforms) return PIPESD_EINVAL;
   for (int32_t i = 0; i < k; ++i)
@@ -749,15 +754,22 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
   if (draft_probs)
     for (int32_t i = 0; i <= k; ++i)
       if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return PIPESD_EINVAL;
+  if (!state) return PIPESD_OK;
   if (!compute_ready(model, kv)) return PIPESD_ESTATE;
+  const int32_t lp = (int32_t)kv->seqs[seq].text.size();
+  if (lp < 1 || prefix_len != lp) return PIPESD_ESTATE;
+  return PIPESD_OK;
+}
+
+// forward + decision + cache trim of one sequence, enqueued on `st`; the decision lands in
+// result[0..1] on the device.  On failure the sequence's block list is back to what it was.
+static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* draft_tokens, int32_t k,
+                          const float* draft_probs, const float* uniforms, int32_t* result, hipStream_t st) {
   SeqState& s = kv->seqs[seq];
   const int32_t lp = (int32_t)s.text.size();
-  if (lp < 1 || prefix_len != lp) return PIPESD_ESTATE;
-  hipStream_t st = (hipStream_t)stream;
   int32_t start = 0;
   int rc = verify_common(model, kv, seq, draft_tokens, k, &start, st);
   if (rc) return rc;
-
   VerifyCall vc{};
   vc.logits_or_p = model->logits;
   vc.q = draft_probs;
@@ -769,7 +781,7 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
   vc.row_stats = model->row_stats;
   vc.scan_partial = model->scan_partial;
   vc.counter = model->counters + (kCounterSlots - 1);
-  vc.result = model->result_dev;
+  vc.result = result;
   hipError_t e = hipSuccess;
   {
     ProfScope ps(model, PIPESD_PROF_VERIFY, st);
@@ -779,10 +791,43 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
     } else {
       e = launch_greedy_accept(vc, st);
     }
-    if (e == hipSuccess) e = launch_kv_trim(model->cfg.dtype, view_of(kv, seq), model->cfg.n_layers, start, k,
-                                            model->result_dev, st);
+    if (e == hipSuccess)
+      e = launch_kv_trim(model->cfg.dtype, view_of(kv, seq), model->cfg.n_layers, start, k, result, st);
   }
-  if (e == hipSuccess) e = hipMemcpyAsync(model->result_host, model->result_dev, 8, hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) {
+    release_beyond(kv, s, lp - 1);
+    return hip_fail(e, "verify step");
+  }
+  return PIPESD_OK;
+}
+
+// after the stream has been synchronised: book the decision of one sequence
+static int commit_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* draft_tokens, int32_t k,
+                         const int32_t* result_host, int32_t* accepted_len, int32_t* next_token) {
+  SeqState& s = kv->seqs[seq];
+  const int32_t a = result_host[0], nxt = result_host[1];
+  if (a < 0 || a > k || nxt < 0 || nxt >= model->cfg.vocab) return PIPESD_EHIP;
+  const int32_t lp = (int32_t)s.text.size();
+  s.text.insert(s.text.end(), draft_tokens, draft_tokens + a);
+  s.text.push_back(nxt);
+  release_beyond(kv, s, lp + a);
+  *accepted_len = a;
+  *next_token = nxt;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t prefix_len,
+                                 const int32_t* draft_tokens, int32_t k, const float* draft_probs,
+                                 const float* uniforms, int32_t* accepted_len, int32_t* next_token, void* stream) {
+  if (!model || !kv || !accepted_len || !next_token || kv->model != model) return PIPESD_EINVAL;
+  int rc = check_verify_args(model, kv, seq, prefix_len, draft_tokens, k, draft_probs, uniforms);
+  if (rc) return rc;
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  hipStream_t st = (hipStream_t)stream;
+  rc = enqueue_verify(model, kv, seq, draft_tokens, k, draft_probs, uniforms, model->result_dev, st);
+  if (rc) return rc;
+  hipError_t e = hipMemcpyAsync(model->result_host, model->result_dev, 8, hipMemcpyDeviceToHost, st);
   if (e == hipSuccess) e = read_layers_flag(model, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
@@ -793,16 +838,85 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
     release_beyond(kv, s, lp - 1);
     return hip_fail(hipErrorLaunchFailure, "device-wide barrier of the fused layer kernel timed out");
   }
-  const int32_t a = model->result_host[0], nxt = model->result_host[1];
-  if (a < 0 || a > k || nxt < 0 || nxt >= model->cfg.vocab) {
-    release_beyond(kv, s, lp - 1);
-    return PIPESD_EHIP;
+  rc = commit_verify(model, kv, seq, draft_tokens, k, model->result_host, accepted_len, next_token);
+  if (rc) release_beyond(kv, s, lp - 1);
+  return rc;
+}
+
+extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32_t n_seqs, const int32_t* seq_ids,
+                                       const int32_t* prefix_lens, const int32_t* k_per_seq,
+                                       const int32_t* draft_tokens_concat, const float* const* draft_probs_per_seq,
+                                       const float* uniforms_concat, int32_t* accepted_len, int32_t* next_token,
+                                       void* stream) {
+  if (!model || !kv || kv->model != model || !seq_ids || !prefix_lens || !k_per_seq || !draft_tokens_concat ||
+      !accepted_len || !next_token)
+    return PIPESD_EINVAL;
+  if (n_seqs < 1 || n_seqs > kMaxBatch) return PIPESD_EINVAL;
+  // ---- every check that can fail comes before the first change of state ----
+  std::vector<int32_t> tok_off(n_seqs), u_off(n_seqs);
+  int32_t toks = 0, us = 0;
+  int64_t blocks_needed = 0;
+  for (int32_t i = 0; i < n_seqs; ++i) {
+    if (k_per_seq[i] < 1 || k_per_seq[i] > kMaxRows - 1) return PIPESD_EINVAL;
+    tok_off[i] = toks;
+    u_off[i] = us;
+    toks += k_per_seq[i];
+    us += k_per_seq[i] + 1;
   }
-  s.text.insert(s.text.end(), draft_tokens, draft_tokens + a);
-  s.text.push_back(nxt);
-  release_beyond(kv, s, lp + a);
-  *accepted_len = a;
-  *next_token = nxt;
+  for (int pass = 0; pass < 2; ++pass)  // argument errors of every client first, then states
+    for (int32_t i = 0; i < n_seqs; ++i) {
+      for (int32_t j = 0; j < i; ++j)
+        if (seq_ids[j] == seq_ids[i]) return PIPESD_EINVAL;  // a sequence can take part once per call
+      const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
+      int rc = check_verify_args(model, kv, seq_ids[i], prefix_lens[i], draft_tokens_concat + tok_off[i], k_per_seq[i],
+                                 qi, uniforms_concat ? uniforms_concat + u_off[i] : nullptr, pass == 1);
+      if (rc) return rc;
+    }
+  for (int32_t i = 0; i < n_seqs; ++i) {
+    const SeqState& s = kv->seqs[seq_ids[i]];
+    const int64_t need = blocks_for((int32_t)s.text.size() + k_per_seq[i]);
+    if (need > (int64_t)s.blocks.size()) blocks_needed += need - (int64_t)s.blocks.size();
+  }
+  if (blocks_needed > (int64_t)kv->free_list.size()) return PIPESD_ENOMEM;
+  // ---- enqueue sequence after sequence on the one stream, then wait once ----
+  hipStream_t st = (hipStream_t)stream;
+  auto undo = [&](int32_t upto) {
+    for (int32_t i = 0; i < upto; ++i) {
+      SeqState& s = kv->seqs[seq_ids[i]];
+      release_beyond(kv, s, (int32_t)s.text.size() - 1);
+    }
+  };
+  for (int32_t i = 0; i < n_seqs; ++i) {
+    const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
+    int rc = enqueue_verify(model, kv, seq_ids[i], draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
+                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr, model->result_dev + 2 * i, st);
+    if (rc) {
+      (void)hipStreamSynchronize(st);
+      undo(i);
+      return rc;
+    }
+  }
+  hipError_t e = hipMemcpyAsync(model->result_host + 4, model->result_dev, (size_t)n_seqs * 8, hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = read_layers_flag(model, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    undo(n_seqs);
+    return hip_fail(e, "batched verify");
+  }
+  if (layers_flag_raised(model)) {
+    undo(n_seqs);
+    return hip_fail(hipErrorLaunchFailure, "device-wide barrier of the fused layer kernel timed out");
+  }
+  for (int32_t i = 0; i < n_seqs; ++i) {  // all decisions are checked before the first is booked
+    const int32_t a = model->result_host[4 + 2 * i], nxt = model->result_host[4 + 2 * i + 1];
+    if (a < 0 || a > k_per_seq[i] || nxt < 0 || nxt >= model->cfg.vocab) {
+      undo(n_seqs);
+      return PIPESD_EHIP;
+    }
+  }
+  for (int32_t i = 0; i < n_seqs; ++i)
+    (void)commit_verify(model, kv, seq_ids[i], draft_tokens_concat + tok_off[i], k_per_seq[i],
+                        model->result_host + 4 + 2 * i, accepted_len + i, next_token + i);
   return PIPESD_OK;
 }
 

@@ -49,6 +49,8 @@ _SIGS = {
     "pipesd_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_void_p]),
     "pipesd_nav_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_int32, C.c_void_p,
                                     _f32p, _i32p, _i32p, C.c_void_p]),
+    "pipesd_nav_verify_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, _i32p,
+                                          C.POINTER(C.c_void_p), _f32p, _i32p, _i32p, C.c_void_p]),
     "pipesd_kv_rollback": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "pipesd_kv_len": (C.c_int, [C.c_void_p, C.c_int32, _i32p]),
     "pipesd_kv_free_blocks": (C.c_int, [C.c_void_p, _i32p]),
@@ -232,6 +234,44 @@ class KVCache:
         _check(_lib.pipesd_nav_verify(self.model.handle, self.handle, seq, prefix_len, _ptr(d, _i32p), k, qptr,
                                       _ptr(u, _f32p), C.byref(a), C.byref(n), _stream()), "pipesd_nav_verify")
         return a.value, n.value
+
+    def nav_verify_batch(self, seqs: Sequence[int], drafts: Sequence[Sequence[int]], draft_probs=None,
+                         uniforms=None, prefix_lens: Optional[Sequence[int]] = None):
+        """One pass per client in `seqs`.  drafts[i]: the client's draft tokens; draft_probs: None, or a
+        list whose entries are torch CUDA float32 tensors [k_i][V], numpy arrays (uploaded) or None;
+        uniforms: list of k_i + 1 values per client (may be None for token-matching clients).
+        Returns (accepted_len list, next_token list)."""
+        n = len(seqs)
+        ks = _i32([len(d) for d in drafts])
+        cat = _i32([t for d in drafts for t in d])
+        keep = []
+        qarr = None
+        if draft_probs is not None:
+            qarr = (C.c_void_p * n)()
+            for i, q in enumerate(draft_probs):
+                if q is None:
+                    qarr[i] = None
+                    continue
+                t = torch.from_numpy(_f32(q)).cuda() if isinstance(q, np.ndarray) else q.contiguous()
+                assert t.dtype == torch.float32 and t.numel() == len(drafts[i]) * self.model.shape.vocab
+                keep.append(t)
+                qarr[i] = t.data_ptr()
+        ucat = None
+        if uniforms is not None:
+            flat = []
+            for i in range(n):
+                ui = uniforms[i]
+                flat.extend([0.0] * (len(drafts[i]) + 1) if ui is None else list(ui))
+            ucat = _f32(flat)
+        if prefix_lens is None:
+            prefix_lens = [self.length(s) for s in seqs]
+        ids, pl = _i32(seqs), _i32(prefix_lens)
+        a = np.full(n, -1, dtype=np.int32)
+        nx = np.full(n, -1, dtype=np.int32)
+        _check(_lib.pipesd_nav_verify_batch(self.model.handle, self.handle, n, _ptr(ids, _i32p), _ptr(pl, _i32p),
+                                            _ptr(ks, _i32p), _ptr(cat, _i32p), qarr, _ptr(ucat, _f32p),
+                                            _ptr(a, _i32p), _ptr(nx, _i32p), _stream()), "pipesd_nav_verify_batch")
+        return a.tolist(), nx.tolist()
 
     def rollback(self, seq: int, new_prefix_len: int) -> None:
         _check(_lib.pipesd_kv_rollback(self.handle, seq, new_prefix_len), "pipesd_kv_rollback")

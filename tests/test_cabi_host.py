@@ -93,6 +93,29 @@ def test_shape_only_handles_do_bookkeeping_but_refuse_compute():
                                     C.byref(a), C.byref(nx), None)
     assert rc == nav.EINVAL
     assert kv.free_blocks() == 100
+    # batched call: the same argument checks, plus distinct clients and a bounded count
+    ip = nav._i32p
+    ids = np.array([0, 1], dtype=np.int32)
+    pl = np.array([5, 5], dtype=np.int32)
+    ks = np.array([2, 2], dtype=np.int32)
+    cat = np.array([1, 2, 3, 4], dtype=np.int32)
+    out_a, out_n = np.zeros(2, dtype=np.int32), np.zeros(2, dtype=np.int32)
+
+    def batch(n, ids_, ks_, cat_):
+        return nav._lib.pipesd_nav_verify_batch(m.handle, kv.handle, n, ids_.ctypes.data_as(ip), pl.ctypes.data_as(ip),
+                                                ks_.ctypes.data_as(ip), cat_.ctypes.data_as(ip), None, None,
+                                                out_a.ctypes.data_as(ip), out_n.ctypes.data_as(ip), None)
+
+    assert batch(2, ids, ks, cat) == nav.ESTATE          # shape-only handles refuse compute
+    assert batch(0, ids, ks, cat) == nav.EINVAL
+    assert batch(257, ids, ks, cat) == nav.EINVAL
+    assert batch(2, np.array([1, 1], dtype=np.int32), ks, cat) == nav.EINVAL    # the same client twice
+    assert batch(2, np.array([0, 4], dtype=np.int32), ks, cat) == nav.EINVAL    # no such client
+    assert batch(2, ids, np.array([2, 0], dtype=np.int32), cat) == nav.EINVAL   # k out of range
+    assert batch(2, ids, ks, np.array([1, 2, 3, -1], dtype=np.int32)) == nav.EINVAL
+    assert nav._lib.pipesd_nav_verify_batch(m.handle, kv.handle, 2, None, None, None, None, None, None, None, None,
+                                            None) == nav.EINVAL
+    assert kv.free_blocks() == 100
     kv.close()
     m.close()
 

@@ -1,0 +1,119 @@
+"""Batched verification of several clients in one call (the multi-client case of Appendix I, with
+lengths and k drawn per client and per round as the dual-threshold trigger would produce them):
+per client the result and the state afterwards must be those of a single-client pass."""
+import numpy as np
+import pytest
+
+from oracle.transformer import softmax_rows
+from paper_2605_13319_amd import inputs as I
+from tests.helpers import decision_excused, drafts_from_oracle, oracle_side
+
+pytestmark = pytest.mark.gpu
+
+SMALL_BF16 = I.ModelShape("small-bf16", 3, 512, 8, 2, 64, 1024, 2048)
+
+
+@pytest.fixture(scope="module")
+def nav():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2605_13319_amd import nav as n
+    return n
+
+
+@pytest.mark.parametrize("shape_name", ["tiny", "small-bf16"])
+def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name):
+    shape = I.WORKLOADS["tiny"]["shape"] if shape_name == "tiny" else SMALL_BF16
+    w = I.make_weights(shape, 9001)
+    model = nav.Model(shape, w)
+    n_seq = 5
+    rng = np.random.default_rng(9002)
+    lens = [int(x) for x in rng.integers(17, 150, n_seq)]
+    kv_b = nav.KVCache(model, max_seqs=n_seq, n_blocks=80)
+    kv_s = nav.KVCache(model, max_seqs=n_seq, n_blocks=80)
+    for s, n in enumerate(lens):
+        toks = I.make_tokens(n, shape.vocab, 9100 + s)
+        kv_b.prefill(s, toks)
+        kv_s.prefill(s, toks)
+    for rnd in range(4):
+        ks = [int(x) for x in rng.integers(1, 17, n_seq)]
+        drafts, probs, us = [], [], []
+        for s in range(n_seq):
+            d, q = I.make_independent_drafts(ks[s], shape.vocab, 9200 + 10 * rnd + s, 9300 + 10 * rnd + s, scale=1.0)
+            drafts.append([int(t) for t in d])
+            greedy = (s == 2)  # one client uses token matching
+            probs.append(None if greedy else q)
+            us.append(None if greedy else I.make_uniforms(ks[s] + 1, 9400 + 10 * rnd + s))
+        order = [int(x) for x in rng.permutation(n_seq)]  # clients in any order
+        a_b, n_b = kv_b.nav_verify_batch(order, [drafts[s] for s in order], [probs[s] for s in order],
+                                         [us[s] for s in order])
+        for i, s in enumerate(order):
+            a, n = kv_s.nav_verify(s, drafts[s], probs[s], us[s])
+            assert (a_b[i], n_b[i]) == (a, n), (rnd, s)
+            assert kv_b.length(s) == kv_s.length(s) == lens[s] + a + 1
+            assert kv_b.seq_blocks(s) == kv_s.seq_blocks(s)
+            lens[s] += a + 1
+        assert kv_b.free_blocks() == kv_s.free_blocks()
+    # the caches hold the same values
+    for s in range(n_seq):
+        for layer in range(shape.n_layers):
+            for pos in (0, lens[s] // 2, lens[s] - 2):
+                kb, vb = kv_b.read_kv(s, layer, pos)
+                ks_, vs = kv_s.read_kv(s, layer, pos)
+                np.testing.assert_array_equal(kb, ks_)
+                np.testing.assert_array_equal(vb, vs)
+
+
+def test_batched_call_that_cannot_get_its_blocks_changes_nothing(nav):
+    shape = SMALL_BF16
+    model = nav.Model(shape, I.make_weights(shape, 9001))
+    kv = nav.KVCache(model, max_seqs=3, n_blocks=7)
+    for s, n in enumerate((31, 32, 30)):  # 2 blocks each: 6 of 7 in use; each client needs one more for 16 drafts
+        kv.prefill(s, I.make_tokens(n, shape.vocab, 9500 + s))
+    free0 = kv.free_blocks()
+    assert free0 == 1
+    d = [[1] * 16, [2] * 16, [3] * 16]
+    with pytest.raises(nav.PipesdError) as e:
+        kv.nav_verify_batch([0, 1, 2], d)
+    assert e.value.status == nav.ENOMEM
+    assert kv.free_blocks() == free0 and [kv.length(s) for s in range(3)] == [31, 32, 30]
+    a, n = kv.nav_verify_batch([1], [d[1]])  # one client alone still fits
+    assert kv.length(1) == 32 + a[0] + 1
+
+
+def test_batched_rounds_against_the_checker(nav):
+    """Four clients with their own prefixes, three rounds of k ~ U[1,16] noisy-target drafts: every
+    decision is the checker's (or excused by the end-to-end rule) and the lengths follow."""
+    shape = SMALL_BF16
+    w = I.make_weights(shape, 9601)
+    model = nav.Model(shape, w)
+    n_seq = 4
+    rng = np.random.default_rng(9602)
+    lens = [int(x) for x in rng.integers(20, 120, n_seq)]
+    kv = nav.KVCache(model, max_seqs=n_seq, n_blocks=64)
+    oseqs = []
+    for s, n in enumerate(lens):
+        toks = I.make_tokens(n, shape.vocab, 9610 + s)
+        kv.prefill(s, toks)
+        oseqs.append(oracle_side(shape, w, toks, n + 80))
+    for rnd in range(3):
+        ks = [int(x) for x in rng.integers(1, 17, n_seq)]
+        drafts, probs, us, refs, prows = [], [], [], [], []
+        for s in range(n_seq):
+            d, q = drafts_from_oracle(oseqs[s], ks[s], 0.5, 9700 + 10 * rnd + s, 9800 + 10 * rnd + s)
+            u = I.make_uniforms(ks[s] + 1, 9900 + 10 * rnd + s)
+            drafts.append([int(t) for t in d]); probs.append(q); us.append(u)
+            prows.append(softmax_rows(oseqs[s].forward_logits(d)))
+            refs.append(oseqs[s].nav_verify(d, q, u))
+        a_b, n_b = kv.nav_verify_batch(list(range(n_seq)), drafts, probs, us)
+        for s in range(n_seq):
+            a_ref, n_ref = refs[s]
+            if (a_b[s], n_b[s]) != (a_ref, n_ref):
+                assert a_b[s] != a_ref and decision_excused(prows[s], probs[s], drafts[s], us[s], a_b[s], a_ref), \
+                    f"round {rnd} client {s}: {(a_b[s], n_b[s])} vs checker {(a_ref, n_ref)}"
+                o = oseqs[s]
+                o.rollback(lens[s])
+                o.committed += drafts[s][:a_b[s]] + [n_b[s]]
+                o.cached = lens[s] + a_b[s]
+            lens[s] += a_b[s] + 1
+            assert kv.length(s) == lens[s] == oseqs[s].prefix_len
