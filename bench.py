@@ -6,14 +6,18 @@ paged KV cache, softmax, accept tests, corrected/extra-token draw, KV trim, then
 rollback to the starting prefix so every step does identical work.  Inputs (weights, prefilled
 cache, draft distributions) are resident in HBM before the timed region.
 
-Prints ONE JSON line: verified tokens/s (k / t_pass), ms per pass, the algorithmic HBM rate of the
-whole pass, a `roofline` object for the weight-streaming GEMM kernel measured with HIP events in
-the timed region, and a `cpu_baseline` object: the CPU checker timed on this host on a
-layer-truncated sample of the same workload.
+Prints ONE JSON line: verified tokens/s (k / t_pass), ms per pass (mean; median and p10/p90 beside
+it), the algorithmic HBM rate of the whole pass, a `roofline` object for the weight-streaming GEMM
+kernel measured with HIP events in the timed region (its `traffic` comes from the committed
+counter summary under profiles/ and is null once the kernel sources have changed since), and a
+`cpu_baseline` object: the CPU checker timed on this host on a layer-truncated sample of the same
+workload.
 """
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,6 +30,31 @@ HBM_PEAK_GBPS = 8000.0
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+GEMM_SOURCES = ("device_gemm.h", "kernels_gemm.hip", "common.h")
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "gemm_bf16_llama8b_k8_hbm_traffic.md")
+
+
+def gemm_sources_sha():
+    h = hashlib.sha256()
+    for fn in GEMM_SOURCES:
+        with open(os.path.join(ROOT, "paper_2605_13319_amd", "csrc", fn), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def committed_traffic(workload):
+    """HBM bytes per GEMM launch from the committed counter summary, or None if there is none for
+    this workload or the GEMM sources have changed since the counters were taken."""
+    if workload != "llama-8b" or not os.path.exists(TRAFFIC_SUMMARY):
+        return None
+    txt = open(TRAFFIC_SUMMARY).read()
+    sha = re.search(r"sources-sha256:\s*([0-9a-f]{64})", txt)
+    val = re.search(r"traffic-bytes-per-launch:\s*([0-9.eE+]+)", txt)
+    if not sha or not val or sha.group(1) != gemm_sources_sha():
+        return None
+    return float(val.group(1))
 
 
 def cpu_baseline(shape, weights, prefix, k, layers):
@@ -90,13 +119,15 @@ def cpu_baseline(shape, weights, prefix, k, layers):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama-8b")
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--prefix", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="truncate the model (debugging; not the headline)")
-    ap.add_argument("--cpu-layers", type=int, default=2)
+    ap.add_argument("--cpu-layers", type=int, default=32)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy kernel (scale for the HBM byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof", default="all_gemm", help="kernel class bracketed by HIP events")
     args = ap.parse_args()
@@ -144,19 +175,31 @@ def main():
     for _ in range(args.warmup):
         first = step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)  # one elementwise kernel (not a blit): reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     model.profile_select(args.prof)
+    per_step = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        res = step()
+        ts = time.perf_counter()
+        res = step()  # synchronises the stream: the decision is on the host when it returns
+        per_step.append(time.perf_counter() - ts)
         assert res == first, "the pass is not reproducible"
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     n_launch, kern_ms = model.profile_read()
     model.profile_select("off")
     # the same steps without event bracketing, to show what the events cost
+    per_step_plain = []
     t1 = time.perf_counter()
     for _ in range(args.steps):
+        ts = time.perf_counter()
         step()
+        per_step_plain.append(time.perf_counter() - ts)
     torch.cuda.synchronize()
     elapsed_plain = time.perf_counter() - t1
 
@@ -171,7 +214,7 @@ def main():
         avg_ms = kern_ms / n_launch
         achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": committed_traffic(args.workload) if args.layers is None else None,
                 "kernel": "gemm_bf16_kernel (all weight-streaming GEMMs of the pass)" if esz == 2 else "gemm_f32_kernel",
                 "launches_per_pass": launches_per_pass, "avg_launch_us": avg_ms * 1e3,
                 "algorithmic_bytes_per_launch": per_launch_bytes}
@@ -186,6 +229,8 @@ def main():
         "hbm_algorithmic_gbps": alg_bytes / t_pass / 1e9, "hbm_frac_of_peak": alg_bytes / t_pass / 1e9 / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_pass": alg_bytes,
         "ms_per_step_with_events": elapsed / args.steps * 1e3, "ms_per_step_plain": elapsed_plain / args.steps * 1e3,
+        "ms_per_step_median_p10_p90": [float(np.percentile(per_step_plain, q)) * 1e3 for q in (50, 10, 90)],
+        "ms_per_step_with_events_median_p10_p90": [float(np.percentile(per_step, q)) * 1e3 for q in (50, 10, 90)],
         "roofline": roof,
     }
     if not args.no_cpu_baseline:

@@ -187,7 +187,8 @@ int pipesd_model_set_fused(pipesd_model *model, int32_t on);
 int pipesd_model_fused_launches(const pipesd_model *model, int64_t *n);
 
 /* Per-kernel timing for roofline accounting: when enabled, every launch of the selected kernel
- * class is bracketed by HIP events on its stream.  pipesd_profile_read waits for them and returns
+ * class is timed with HIP events on its stream (the bf16 GEMM launches carry their own start and
+ * stop events, the other classes are bracketed by recorded events).  pipesd_profile_read waits for them and returns
  * the number of launches and their summed duration since the last read. */
 enum { PIPESD_PROF_OFF = 0, PIPESD_PROF_GEMM_QKV = 1, PIPESD_PROF_GEMM_O = 2, PIPESD_PROF_GEMM_GATEUP = 3,
        PIPESD_PROF_GEMM_DOWN = 4, PIPESD_PROF_GEMM_LMHEAD = 5, PIPESD_PROF_ATTN = 6, PIPESD_PROF_VERIFY = 7,

@@ -467,6 +467,30 @@ struct ProfScope {
     ++m->prof_used;
   }
 };
+// a GEMM launch of the selected class carries its own start / stop events instead
+struct ProfGemm {
+  pipesd_model* m;
+  bool on;
+  ProfGemm(pipesd_model* m_, int cls, GemmCall& g) : m(m_) {
+    on = m->prof_class != PIPESD_PROF_OFF &&
+         (m->prof_class == cls || (m->prof_class == PIPESD_PROF_ALL_GEMM && cls >= PIPESD_PROF_GEMM_QKV &&
+                                   cls <= PIPESD_PROF_GEMM_LMHEAD));
+    if (!on) return;
+    if (m->prof_used == m->prof_events.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        on = false;
+        return;
+      }
+      m->prof_events.emplace_back(a, b);
+    }
+    g.ev_start = m->prof_events[m->prof_used].first;
+    g.ev_stop = m->prof_events[m->prof_used].second;
+  }
+  ~ProfGemm() {
+    if (on) ++m->prof_used;
+  }
+};
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -620,8 +644,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
       }
     } else {
       {
-        ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
         GemmCall g = gemm_call(m, m->wqkv[l], nqkv, d, rows, ar.xa(l), ar.sa(l), norm_parts, EPI_QKV);
+        ProfGemm pg(m, PIPESD_PROF_GEMM_QKV, g);
         g.out = ar.q(l);
         g.ldo = qd;
         g.kv = view;
@@ -635,8 +659,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
         HIP_TRY(launch_attention(at, st));
       }
       {
-        ProfScope ps(m, PIPESD_PROF_GEMM_O, st);
         GemmCall g = gemm_call(m, m->wo[l], d, qd, rows, ar.ap(l), nullptr, 0, EPI_RESID);
+        ProfGemm pg(m, PIPESD_PROF_GEMM_O, g);
         g.res_in = ar.ra(l);
         g.out = ar.rb(l);
         g.ldo = d;
@@ -647,14 +671,14 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
         norm_parts = d / 16;
       }
       {
-        ProfScope ps(m, PIPESD_PROF_GEMM_GATEUP, st);
         GemmCall g = gemm_call(m, m->wgu[l], 2 * F, d, rows, ar.xb(l), ar.sb(l), norm_parts, EPI_SWIGLU);
+        ProfGemm pg(m, PIPESD_PROF_GEMM_GATEUP, g);
         g.outp = ar.gp(l);
         HIP_TRY(launch_gemm_bf16(g, st));
       }
       {
-        ProfScope ps(m, PIPESD_PROF_GEMM_DOWN, st);
         GemmCall g = gemm_call(m, m->wdown[l], d, F, rows, ar.gp(l), nullptr, 0, EPI_RESID);
+        ProfGemm pg(m, PIPESD_PROF_GEMM_DOWN, g);
         g.res_in = ar.rb(l);
         g.out = ar.ra(l + 1);
         g.ldo = d;
@@ -666,12 +690,13 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     }
   }
   if (want_logits) {
-    ProfScope ps(m, PIPESD_PROF_GEMM_LMHEAD, st);
     if (c.dtype == PIPESD_F32) {
+      ProfScope ps(m, PIPESD_PROF_GEMM_LMHEAD, st);
       HIP_TRY(launch_rmsnorm_rows(m->xres, m->final_norm, c.rms_eps, rows, d, m->hbuf, st));
       HIP_TRY(launch_gemm_f32(m->hbuf, d, (const float*)m->lm_head, V, d, rows, m->logits, V, 0, st));
     } else {
       GemmCall g = gemm_call(m, m->lm_head, V, d, rows, ar.xa(c.n_layers), ar.sa(c.n_layers), norm_parts, EPI_STORE);
+      ProfGemm pg(m, PIPESD_PROF_GEMM_LMHEAD, g);
       g.out = m->logits;
       g.ldo = V;
       HIP_TRY(launch_gemm_bf16(g, st));

@@ -123,6 +123,8 @@ struct GemmCall {
   KvView kv;
   int layer, start_pos, n_q_heads;
   const float* rope_cs;
+  // optional: events that take the kernel's own start and end (no marker packets around it)
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st);
 

@@ -1,6 +1,8 @@
 // Per-GEMM kernel of the NAV pass: one launch per projection (used for the LM head, for passes with
 // more than 16 rows, and for shapes the fused layer kernel does not take).  The device code lives in
 // device_gemm.h.
+#include <hip/hip_ext.h>
+
 #include "device_gemm.h"
 
 namespace pipesd {
@@ -93,10 +95,18 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.eps = c.eps;
   const int mt = c.m <= 16 ? 1 : 2;
   const size_t lds = gemm_lds_floats(p.tg, p.W, mt, 1) * sizeof(float);
-  if (mt == 1)
+  if (c.ev_start != nullptr && c.ev_stop != nullptr) {
+    if (mt == 1)
+      hipExtLaunchKernelGGL((gemm_bf16_kernel<1, 16>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
+                            c.ev_stop, 0, a);
+    else
+      hipExtLaunchKernelGGL((gemm_bf16_kernel<2, 8>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
+                            c.ev_stop, 0, a);
+  } else if (mt == 1) {
     gemm_bf16_kernel<1, 16><<<p.grid, p.W * 64, lds, st>>>(a);
-  else
+  } else {
     gemm_bf16_kernel<2, 8><<<p.grid, p.W * 64, lds, st>>>(a);
+  }
   return hipGetLastError();
 }
 
