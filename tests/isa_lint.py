@@ -5,7 +5,8 @@ completion the compiler does not track.  Between such a load and the s_waitcnt t
 compiler-generated instruction may touch the destination registers: a copy or a spill there moves
 data that has not arrived yet.  Forward dataflow over basic blocks; the state is the ordered tuple
 of in-flight hand-issued load destinations (oldest first); at joins the longest state wins (states
-from different paths are almost always equal, or one is empty).
+from different paths are almost always equal, or one is empty).  A wave can have at most 64
+loads outstanding, which also bounds the state around loops that issue loads.
 """
 import re, sys
 def regs(tok):
@@ -58,7 +59,9 @@ def transfer(state, blk, report):
                 if n < len(st): st = st[len(st) - n:] if n > 0 else []
             continue
         if in_asm and re.match(r'global_load_dword', op):
-            st.append((regs(rest.split(',')[0]), no)); continue
+            st.append((regs(rest.split(',')[0]), no))
+            st = st[-64:]  # the 6-bit counter: a wave cannot have more loads on their way
+            continue
         if in_asm: continue
         touched = frozenset()
         for o in rest.split(','): touched |= regs(o)
