@@ -182,17 +182,93 @@ def test_llama_1b_workload(nav):
         print(f"llama-1b round {r}: err {err:.2e} accepted {a}/{wl['k']}", flush=True)
 
 
-@pytest.mark.parametrize("k", [8, 16])
-def test_llama_8b_width_truncated_to_two_layers(nav, k):
+def test_llama_8b_width_truncated_to_two_layers(nav):
     """The 8B shape at full width, vocabulary and context (every per-layer launch has the shape the
-    benchmark times) with 2 of its 32 layers, so that the checker can prefill 2048 tokens."""
+    benchmark times) with 2 of its 32 layers, so that the checker can prefill 2048 tokens; k swept
+    over the configured values, the sequence cut back to the prefix between the passes."""
     wl = I.WORKLOADS["llama-8b"]
     shape, seed = wl["shape"].truncated(2), wl["seed"]
     oseq, model, kv = _both(nav, shape, seed, wl["prefix"], n_blocks=136, max_len=wl["prefix"] + 64)
-    d, q = drafts_from_oracle(oseq, k, wl["sigma"], seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U)
-    u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U)
-    err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
-    print(f"llama-8b-L2 k={k}: err {err:.2e} accepted {a}/{k}", flush=True)
+    for k in (8, 16, 1, 4):
+        d, q = drafts_from_oracle(oseq, k, wl["sigma"], seed + I.SEED_NOISE + k, seed + I.SEED_DRAFT_U + k)
+        u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U + k)
+        err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
+        print(f"llama-8b-L2 k={k}: err {err:.2e} accepted {a}/{k}", flush=True)
+        oseq.rollback(wl["prefix"])
+        kv.rollback(0, wl["prefix"])
+
+
+def test_llama_13b_width_batch_of_four(nav):
+    """The long-context 13B shape (d 5120, 40 heads MHA, FFN 13824: K slices that do not divide by 8
+    waves, 320 sums of squares per row) with 2 of its 40 layers: four clients verified by one batched
+    call, k = 16, drafts with sigma 1.0 (frequent early rejections, deep rollback), against the
+    checker.  The checker's prefixes are ~600-1000 tokens here; the 8192-token context is covered
+    on the GPU side by test_llama_13b_width_long_context_consistency."""
+    wl = I.WORKLOADS["llama-13b"]
+    shape, seed = wl["shape"].truncated(2), wl["seed"]
+    w = I.make_weights(shape, seed + I.SEED_WEIGHTS)
+    model = nav.Model(shape, w)
+    lens = [1000, 777, 612, 901]
+    kv = nav.KVCache(model, max_seqs=4, n_blocks=4 * 66)
+    oseqs = []
+    for s, n in enumerate(lens):
+        toks = I.make_tokens(n, shape.vocab, seed + I.SEED_PREFIX + 100 * s)
+        kv.prefill(s, toks)
+        oseqs.append(oracle_side(shape, w, toks, n + 40))
+    k = wl["k"]
+    for rnd in range(2):
+        drafts, probs, us, refs, prows = [], [], [], [], []
+        for s in range(4):
+            d, q = drafts_from_oracle(oseqs[s], k, wl["sigma"], seed + I.SEED_NOISE + 10 * rnd + s,
+                                      seed + I.SEED_DRAFT_U + 10 * rnd + s)
+            u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U + 10 * rnd + s)
+            z_ref = oseqs[s].forward_logits(d)
+            z = kv.forward_logits(s, d)
+            err = float(np.abs(z - z_ref).max())
+            assert err <= TOL_BF16, f"client {s}: logits max-abs {err}"
+            drafts.append([int(t) for t in d]); probs.append(q); us.append(u)
+            prows.append(softmax_rows(z_ref))
+            refs.append(oseqs[s].nav_verify(d, q, u))
+        a_b, n_b = kv.nav_verify_batch([0, 1, 2, 3], drafts, probs, us)
+        for s in range(4):
+            a_ref, n_ref = refs[s]
+            if (a_b[s], n_b[s]) != (a_ref, n_ref):
+                assert a_b[s] != a_ref and decision_excused(prows[s], probs[s], drafts[s], us[s], a_b[s], a_ref), \
+                    f"round {rnd} client {s}: {(a_b[s], n_b[s])} vs checker {(a_ref, n_ref)}"
+                o = oseqs[s]
+                o.rollback(lens[s])
+                o.committed += drafts[s][:a_b[s]] + [n_b[s]]
+                o.cached = lens[s] + a_b[s]
+            lens[s] += a_b[s] + 1
+            assert kv.length(s) == lens[s]
+        print(f"llama-13b-L2 round {rnd}: accepted {a_b}", flush=True)
+
+
+def test_llama_13b_width_long_context_consistency(nav):
+    """Prefix 8192, k = 16 on the 13B width (2 layers): the pass reproduces bit for bit after a
+    rollback, its rows equal those of shorter passes, and the token-matching decision is the argmax
+    prefix of its own logits."""
+    wl = I.WORKLOADS["llama-13b"]
+    shape, seed = wl["shape"].truncated(2), wl["seed"]
+    model = nav.Model(shape, I.make_weights(shape, seed + I.SEED_WEIGHTS))
+    prefix, k = wl["prefix"], wl["k"]
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=(prefix + 48) // 16 + 1)
+    kv.prefill(0, I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX))
+    d = I.make_tokens(k, shape.vocab, seed + 77)
+    z1 = kv.forward_logits(0, d)
+    z2 = kv.forward_logits(0, d)
+    np.testing.assert_array_equal(z1, z2)
+    for n in (0, 5, 15):
+        zn = kv.forward_logits(0, d[:n])
+        assert float(np.abs(zn - z1[:n + 1]).max()) < 2e-3, n
+    # token matching: two drafts that are the pass's own argmax continuation, then a miss
+    d0 = int(kv.forward_logits(0, [])[0].argmax())
+    d1 = int(kv.forward_logits(0, [d0])[1].argmax())
+    best2 = int(kv.forward_logits(0, [d0, d1])[2].argmax())
+    dg = [d0, d1, (best2 + 1) % shape.vocab] + [int(t) for t in d[3:]]
+    a, nxt = kv.nav_verify(0, dg)
+    assert (a, nxt) == (2, best2)
+    assert kv.length(0) == prefix + 3
 
 
 @pytest.mark.parametrize("shape,prefix,k", [(SMALL_BF16, 70, 8), (SMALL_MHA, 300, 15),
