@@ -12,6 +12,9 @@
 //    in common.h): the producing epilogue splits each value once, every consuming wave just loads
 //    registers.  Two MFMAs per weight fragment keep 16 significand bits of the activations; the
 //    matrix cores idle otherwise.
+//  * A pass of 17..32 rows is spread over PAIRS of workgroups that walk the same tiles, one per 16
+//    rows, placed on the same chiplet: the weights cross the memory interface once and the second
+//    reader is served by the chiplet's L2.
 //  * K is cut into W * P slices of KSTEPS*32 columns; a team of W waves takes slices p*W + w,
 //    p = 0..P-1, one phase after the other, for a group of tg n-tiles, each wave keeping its running
 //    16x16 sums in its own LDS slots; after the last phase the team adds them in a fixed order.
@@ -53,6 +56,7 @@ struct GemmArgs {
   const float* rope_cs;
   KvView kv;
   int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
+  int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1 or 2)
   float eps;
 };
 
@@ -65,9 +69,16 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // compiler would otherwise join the with-next and without-next paths into vmcnt(0) and drain the
 // pipeline at every chunk.  Stores are never issued by hand without trailing wait states: the
 // hardware reads store data for a few cycles after issue and only the compiler tracks that.
+// NT: non-temporal hint for weights that are read exactly once (a pass of up to 16 rows).  When two
+// workgroups on the same chiplet read the same tiles (a pass of 17..32 rows) the loads are ordinary
+// ones instead, so that the second reader finds the line in the L2.
+template <bool NT>
 __device__ __forceinline__ u32x4 stream_load(const u32x4* p) {
   u32x4 v;
-  asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
+  if constexpr (NT)
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(v) : "v"(p));
+  else
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p));
   return v;
 }
 __device__ __forceinline__ u32x4 act_load(const u32x4* p) {
@@ -137,7 +148,7 @@ __device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const f
 
 // one chunk = KSTEPS weight fragments of one n-tile against this wave's activation fragments; while
 // fragment ks is multiplied, fragment ks of the next chunk is requested into the same registers
-template <int MT, int KSTEPS, bool HAS_NEXT, int KS = 0>
+template <int MT, int KSTEPS, bool NT, bool HAS_NEXT, int KS = 0>
 __device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bhi)[MT][KSTEPS],
                                            const u32x4 (&blo)[MT][KSTEPS], f32x4 (&acc)[MT], const u32x4* nxt) {
   if constexpr (KS < KSTEPS) {
@@ -148,8 +159,8 @@ __device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bh
       acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(bhi[mt][KS]), acc[mt], 0, 0, 0);
       acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, as_bf16x8(blo[mt][KS]), acc[mt], 0, 0, 0);
     }
-    if constexpr (HAS_NEXT) af[KS] = stream_load(nxt + KS * 64);
-    chunk_mfma<MT, KSTEPS, HAS_NEXT, KS + 1>(af, bhi, blo, acc, nxt);
+    if constexpr (HAS_NEXT) af[KS] = stream_load<NT>(nxt + KS * 64);
+    chunk_mfma<MT, KSTEPS, NT, HAS_NEXT, KS + 1>(af, bhi, blo, acc, nxt);
   }
 }
 
@@ -270,9 +281,12 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
 // grid, `wt` is the wave's index in its team (waves with active == false belong to no team but must
 // still take part in the workgroup barriers), `tl` the team's index inside the workgroup (selects
 // its LDS area), `nwaves_wg` the workgroup's wave count.
+// `row_base` (0 or 16) selects which 16 rows of the pass this team multiplies when the rows of a
+// pass are spread over several workgroups (MT = 1 only).
 struct TeamPos {
   int team, nteams, wt, tl;
   bool active;
+  int row_base = 0;
 };
 
 template <int KSTEPS>
@@ -282,13 +296,13 @@ __device__ __forceinline__ const u32x4* gemm_chunk_ptr(const GemmArgs& a, int la
 
 // request the first weight chunk of this wave (it does not depend on the activations, so it can be
 // issued before whatever still separates the wave from the GEMM: a prologue, or a device-wide barrier)
-template <int KSTEPS>
+template <int KSTEPS, bool NT = true>
 __device__ __forceinline__ void gemm_prefetch(const GemmArgs& a, const TeamPos& tp, int lane, u32x4 (&af)[KSTEPS]) {
   const int ngroups = (a.ntiles + a.tg - 1) / a.tg;
   if (!tp.active || tp.team >= ngroups) return;
   const u32x4* first = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, tp.team * a.tg, 0);
 #pragma unroll
-  for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load(first + ks * 64);
+  for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load<NT>(first + ks * 64);
 }
 
 // floats of LDS one workgroup needs: reduce slots of all its teams + rstd per row
@@ -298,7 +312,7 @@ __host__ __device__ inline size_t gemm_lds_floats(int tg, int W, int MT, int tea
 
 // The GEMM proper.  `af` must hold the in-flight first chunk (gemm_prefetch).  All waves of the
 // workgroup must call this together (it contains workgroup barriers).
-template <int MT, int KSTEPS, bool CO>
+template <int MT, int KSTEPS, bool CO, bool NT = true>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, int teams_per_wg, int nwaves_wg,
                                           float* lds, u32x4 (&af)[KSTEPS]) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -317,7 +331,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
     for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        if (mt * 16 + bc < a.m) b[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt, hl, bc, bg));
+        if (tp.row_base + mt * 16 + bc < a.m)
+          b[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt + (tp.row_base >> 4), hl, bc, bg));
   };
   auto await_act = [&]() {
 #pragma unroll
@@ -346,9 +361,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         const int row = row0 + r2 * nwaves_wg, j = lane + 64 * j4;
         part[r2][j4] = 0.f;
         // ("+v": the load lands in the very register that holds the zero of the lanes that skip it)
-        if (norm && row < MT * 16 && row < a.m && j < a.ssq_parts)
+        if (norm && row < MT * 16 && tp.row_base + row < a.m && j < a.ssq_parts)
           asm volatile("global_load_dword %0, %1, off" : "+v"(part[r2][j4])
-                       : "v"(a.ssq_in + (size_t)row * a.ssq_stride + j));
+                       : "v"(a.ssq_in + (size_t)(tp.row_base + row) * a.ssq_stride + j));
       }
   };
   auto ssq_finish = [&](int row0) {
@@ -375,7 +390,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
     const int t0 = tp.team * a.tg, e_first = tp.wt * 64 + lane;
     if (e_first < min(a.tg, a.ntiles - t0) * MT * 64) {
       const int tt = e_first / (MT * 64), rem = e_first % (MT * 64), l = rem & 63;
-      const int row = (rem >> 6) * 16 + (l & 15), col = (t0 + tt) * 16 + (l >> 4) * 4;
+      const int row = tp.row_base + (rem >> 6) * 16 + (l & 15), col = (t0 + tt) * 16 + (l >> 4) * 4;
       if (row < a.m) pre_res = *(const f32x4*)(a.res_in + (size_t)row * a.ldo + col);
       pre_gain = *(const f32x4*)(a.gain_next + col);
       have_pre = true;
@@ -416,9 +431,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
           if (nxt != nullptr)
-            chunk_mfma<MT, KSTEPS, true>(af, bhi, blo, acc, nxt);
+            chunk_mfma<MT, KSTEPS, NT, true>(af, bhi, blo, acc, nxt);
           else
-            chunk_mfma<MT, KSTEPS, false>(af, bhi, blo, acc, nxt);
+            chunk_mfma<MT, KSTEPS, NT, false>(af, bhi, blo, acc, nxt);
           // this wave's running sum over its phases lives in its own LDS slot
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
@@ -436,8 +451,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         const int tt = e / (MT * 64), rem = e % (MT * 64), mt = rem >> 6, l = rem & 63;
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int ww = 0; ww < a.W; ++ww) v += red[((size_t)(tt * a.W + ww) * MT + mt) * 64 + l];
-        const int row = mt * 16 + (l & 15);
-        const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[row] : 1.0f;
+        const int lrow = mt * 16 + (l & 15), row = tp.row_base + lrow;
+        const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[lrow] : 1.0f;
         epilogue_quad<CO>(a, t0 + tt, row, l, v, rstd, pre && e == e_first, pre_res, pre_gain);
       }
     }

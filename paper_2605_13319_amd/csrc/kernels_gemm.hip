@@ -7,21 +7,26 @@
 
 namespace pipesd {
 
-template <int MT, int KSTEPS>
+template <int KSTEPS, bool NT>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  // one team per workgroup: all W waves of the workgroup
-  const TeamPos tp{(int)blockIdx.x, (int)gridDim.x, w, 0, true};
+  // One team per workgroup: all W waves of the workgroup.  With two row tiles the workgroups b and
+  // b + 8 form a pair on the same tiles (one takes rows 0..15, the other rows 16..31): workgroups
+  // are dealt to the 8 chiplets round robin, so a pair shares an L2 and the weights cross the
+  // memory interface once.
+  const int b = (int)blockIdx.x, rt = a.row_tiles;
+  TeamPos tp{(b / (8 * rt)) * 8 + (b & 7), (int)gridDim.x / rt, w, 0, true};
+  tp.row_base = ((b >> 3) % rt) * 16;
   u32x4 af[KSTEPS];
-  gemm_prefetch<KSTEPS>(a, tp, lane, af);
-  gemm_body<MT, KSTEPS, false>(a, tp, 1, a.W, lds, af);
+  gemm_prefetch<KSTEPS, NT>(a, tp, lane, af);
+  gemm_body<1, KSTEPS, false, NT>(a, tp, 1, a.W, lds, af);
 }
 
 // ------------------------------------------------------------------------------------------------
 // launch shape
 // ------------------------------------------------------------------------------------------------
-constexpr int kTmax16 = 7, kTmax32 = 3;  // n-tiles per group at W = 8 (the LDS reduce area stays under 64 KB)
+constexpr int kTmax16 = 7;  // n-tiles per group at W = 8 (the LDS reduce area stays under 64 KB)
 
 int device_cu_count() {
   static int n_cu = 0;
@@ -34,18 +39,20 @@ int device_cu_count() {
   return n_cu;
 }
 
-static void shape_for(int N, int K, int m, int n_cu, GemmPlan& p) {
+// launch shape for `slots_cu` compute units' worth of teams (a pass of more than 16 rows puts two
+// workgroups on every team's tiles, so it plans for half the device)
+static void shape_for(int N, int K, int slots_cu, GemmPlan& p) {
   p.K = K;
   p.N = N;
   p.ntiles = (N + 15) / 16;
-  const int slices = K / (m <= 16 ? 512 : 256);
+  const int slices = K / 512;
   int W = 1;
   for (int cand = 8; cand >= 1; --cand)
     if (slices % cand == 0) { W = cand; break; }
   p.W = W;
   p.P = slices / W;
-  const int slots = n_cu * (8 / W > 0 ? 8 / W : 1);
-  const int tmax = (m <= 16 ? kTmax16 : kTmax32) * 8 / W;
+  const int slots = slots_cu * (8 / W > 0 ? 8 / W : 1);
+  const int tmax = kTmax16 * 8 / W;
   int best_tg = 1;
   long best_cost = -1;
   for (int tg = 1; tg <= tmax; ++tg) {
@@ -62,10 +69,11 @@ static void shape_for(int N, int K, int m, int n_cu, GemmPlan& p) {
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   const int n_cu = device_cu_count();
   if (n_cu <= 0) return hipErrorUnknown;
-  const int slice = c.m <= 16 ? 512 : 256;
-  if (c.m < 1 || c.m > kMaxRows || c.K % slice != 0) return hipErrorInvalidValue;
+  if (c.m < 1 || c.m > kMaxRows || c.K % 512 != 0) return hipErrorInvalidValue;
+  const int row_tiles = c.m <= 16 ? 1 : 2;
   GemmPlan p;
-  shape_for(c.N, c.K, c.m, n_cu, p);
+  shape_for(c.N, c.K, n_cu / row_tiles, p);
+  if (row_tiles > 1) p.grid = (p.grid + 7) / 8 * 8 * row_tiles;  // pairs are b and b + 8: whole rounds of the 8 chiplets
   GemmArgs a{};
   a.wp = (const u32x4*)c.wp;
   a.actp = (const u32x4*)c.actp;
@@ -93,19 +101,21 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.start_pos = c.start_pos;
   a.n_q_heads = c.n_q_heads;
   a.eps = c.eps;
-  const int mt = c.m <= 16 ? 1 : 2;
-  const size_t lds = gemm_lds_floats(p.tg, p.W, mt, 1) * sizeof(float);
-  if (c.ev_start != nullptr && c.ev_stop != nullptr) {
-    if (mt == 1)
-      hipExtLaunchKernelGGL((gemm_bf16_kernel<1, 16>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
+  a.row_tiles = row_tiles;
+  const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);
+  const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;
+  if (row_tiles == 1) {
+    if (timed)
+      hipExtLaunchKernelGGL((gemm_bf16_kernel<16, true>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
                             c.ev_stop, 0, a);
     else
-      hipExtLaunchKernelGGL((gemm_bf16_kernel<2, 8>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
-                            c.ev_stop, 0, a);
-  } else if (mt == 1) {
-    gemm_bf16_kernel<1, 16><<<p.grid, p.W * 64, lds, st>>>(a);
+      gemm_bf16_kernel<16, true><<<p.grid, p.W * 64, lds, st>>>(a);
   } else {
-    gemm_bf16_kernel<2, 8><<<p.grid, p.W * 64, lds, st>>>(a);
+    if (timed)
+      hipExtLaunchKernelGGL((gemm_bf16_kernel<16, false>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
+                            c.ev_stop, 0, a);
+    else
+      gemm_bf16_kernel<16, false><<<p.grid, p.W * 64, lds, st>>>(a);
   }
   return hipGetLastError();
 }

@@ -254,6 +254,7 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   a.err = (int*)(c.bar + (1 + kBarGroups) * 32);
   const int nqkv = c.q_dim + 2 * c.kv.n_kv_heads * c.head_dim;
   GemmArgs base{};
+  base.row_tiles = 1;
   base.m = c.m;
   base.eps = c.eps;
   base.ssq_stride = c.arena.ssq_stride;
