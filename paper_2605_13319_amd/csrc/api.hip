@@ -63,7 +63,7 @@ struct pipesd_model {
   unsigned long long* step_clock = nullptr;  // [4 * n_layers + 1] clocks of the last fused launch
   bool steps_recorded = false;
   bool fused_enabled = false;  // opt-in until it beats the per-projection launches
-  int64_t fused_launches = 0;
+  int64_t fused_launches = 0, fused_checked = 0;
   // kernel timing
   int prof_class = PIPESD_PROF_OFF;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
@@ -708,7 +708,8 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
 // The fused layer kernel raises a sticky flag if one of its device-wide barriers timed out.
 static hipError_t read_layers_flag(pipesd_model* m, hipStream_t st) {
   m->result_host[2] = 0;
-  if (!m->bar) return hipSuccess;
+  if (!m->bar || m->fused_launches == m->fused_checked) return hipSuccess;
+  m->fused_checked = m->fused_launches;
   return hipMemcpyAsync(m->result_host + 2, m->bar + kLayersErrWord, 4, hipMemcpyDeviceToHost, st);
 }
 static bool layers_flag_raised(pipesd_model* m) {
@@ -789,7 +790,8 @@ static int check_verify_args(const pipesd_model* model, const pipesd_kv* kv, int
 // forward + decision + cache trim of one sequence, enqueued on `st`; the decision lands in
 // result[0..1] on the device.  On failure the sequence's block list is back to what it was.
 static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* draft_tokens, int32_t k,
-                          const float* draft_probs, const float* uniforms, int32_t* result, hipStream_t st) {
+                          const float* draft_probs, const float* uniforms, int32_t* result, int32_t* result_copy,
+                          hipStream_t st) {
   SeqState& s = kv->seqs[seq];
   const int32_t lp = (int32_t)s.text.size();
   int32_t start = 0;
@@ -807,6 +809,7 @@ static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const
   vc.scan_partial = model->scan_partial;
   vc.counter = model->counters + (kCounterSlots - 1);
   vc.result = result;
+  vc.result_copy = result_copy;
   hipError_t e = hipSuccess;
   {
     ProfScope ps(model, PIPESD_PROF_VERIFY, st);
@@ -850,10 +853,10 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
   SeqState& s = kv->seqs[seq];
   const int32_t lp = (int32_t)s.text.size();
   hipStream_t st = (hipStream_t)stream;
-  rc = enqueue_verify(model, kv, seq, draft_tokens, k, draft_probs, uniforms, model->result_dev, st);
+  model->result_host[0] = model->result_host[1] = -1;
+  rc = enqueue_verify(model, kv, seq, draft_tokens, k, draft_probs, uniforms, model->result_dev, model->result_host, st);
   if (rc) return rc;
-  hipError_t e = hipMemcpyAsync(model->result_host, model->result_dev, 8, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = read_layers_flag(model, st);
+  hipError_t e = read_layers_flag(model, st);  // the decision itself lands in pinned host memory, written by the kernel
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
     release_beyond(kv, s, lp - 1);
@@ -911,18 +914,19 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
       release_beyond(kv, s, (int32_t)s.text.size() - 1);
     }
   };
+  for (int32_t i = 0; i < 2 * n_seqs; ++i) model->result_host[4 + i] = -1;
   for (int32_t i = 0; i < n_seqs; ++i) {
     const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
     int rc = enqueue_verify(model, kv, seq_ids[i], draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
-                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr, model->result_dev + 2 * i, st);
+                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr, model->result_dev + 2 * i,
+                            model->result_host + 4 + 2 * i, st);
     if (rc) {
       (void)hipStreamSynchronize(st);
       undo(i);
       return rc;
     }
   }
-  hipError_t e = hipMemcpyAsync(model->result_host + 4, model->result_dev, (size_t)n_seqs * 8, hipMemcpyDeviceToHost, st);
-  if (e == hipSuccess) e = read_layers_flag(model, st);
+  hipError_t e = read_layers_flag(model, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
     undo(n_seqs);

@@ -212,6 +212,7 @@ struct VerifyCall {
   unsigned long long* scan_partial;  // scratch [nblocks]
   unsigned* counter;    // one zeroed counter
   int32_t* result;      // device [2]: accepted_len, next_token
+  int32_t* result_copy; // optional second place for the two values (pinned host memory the device can write), or nullptr
 };
 hipError_t launch_softmax_rows(const VerifyCall& c, hipStream_t st);  // logits -> probabilities in place
 hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st);   // decision on probabilities

@@ -121,7 +121,8 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
                                                                 int k, int V, RowTokens drafts, Uniforms un,
                                                                 unsigned long long* partial,
                                                                 unsigned* counter,
-                                                                int32_t* __restrict__ result) {
+                                                                int32_t* __restrict__ result,
+                                                                int32_t* __restrict__ result_copy) {
   __shared__ unsigned long long red[kVThreads / 64];
   __shared__ int s_a, s_last;
   const int tid = threadIdx.x;
@@ -210,6 +211,10 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
   if (tid == 0) {
     result[0] = a;
     result[1] = next;
+    if (result_copy != nullptr) {
+      result_copy[0] = a;
+      result_copy[1] = next;
+    }
     *counter = 0u;
   }
 }
@@ -218,7 +223,7 @@ hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st) {
   Uniforms un;
   for (int i = 0; i < kMaxRows; ++i) un.u[i] = c.u[i];
   spec_accept_kernel<<<kScanBlocks, kVThreads, 0, st>>>(c.logits_or_p, c.q, c.k, c.V, c.drafts, un, c.scan_partial,
-                                                        c.counter, c.result);
+                                                        c.counter, c.result, c.result_copy);
   return hipGetLastError();
 }
 
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(kVThreads) void argmax_partial_kernel(const float* 
 }
 
 __global__ void greedy_decide_kernel(const float* __restrict__ stats, int k, int V, RowTokens drafts,
-                                     int32_t* __restrict__ result) {
+                                     int32_t* __restrict__ result, int32_t* __restrict__ result_copy) {
   __shared__ int am[kMaxRows];
   const int per = (V + kStatChunks - 1) / kStatChunks;
   if ((int)threadIdx.x <= k) {
@@ -276,6 +281,10 @@ __global__ void greedy_decide_kernel(const float* __restrict__ stats, int k, int
     while (a < k && am[a] == drafts.tok[a]) ++a;
     result[0] = a;
     result[1] = am[a];
+    if (result_copy != nullptr) {
+      result_copy[0] = a;
+      result_copy[1] = am[a];
+    }
   }
 }
 
@@ -284,7 +293,7 @@ hipError_t launch_greedy_accept(const VerifyCall& c, hipStream_t st) {
   argmax_partial_kernel<<<grid, kVThreads, 0, st>>>(c.logits_or_p, c.V, c.row_stats);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  greedy_decide_kernel<<<1, 64, 0, st>>>(c.row_stats, c.k, c.V, c.drafts, c.result);
+  greedy_decide_kernel<<<1, 64, 0, st>>>(c.row_stats, c.k, c.V, c.drafts, c.result, c.result_copy);
   return hipGetLastError();
 }
 
