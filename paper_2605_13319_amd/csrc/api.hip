@@ -814,7 +814,8 @@ static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const
   {
     ProfScope ps(model, PIPESD_PROF_VERIFY, st);
     if (draft_probs) {
-      e = launch_softmax_rows(vc, st);
+      vc.from_logits = true;  // probabilities are formed inside the decision kernel, never written out
+      e = launch_softmax_stats(vc, st);
       if (e == hipSuccess) e = launch_spec_accept(vc, st);
     } else {
       e = launch_greedy_accept(vc, st);

@@ -204,6 +204,7 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st);
 // ---- vocabulary-wide decision ----
 struct VerifyCall {
   float* logits_or_p;   // [k+1][V]
+  bool from_logits;     // launch_spec_accept: logits_or_p holds logits and row_stats their softmax partials
   const float* q;       // [k][V] or nullptr (token matching)
   int k, V;
   RowTokens drafts;     // tok[0..k-1]
@@ -214,8 +215,9 @@ struct VerifyCall {
   int32_t* result;      // device [2]: accepted_len, next_token
   int32_t* result_copy; // optional second place for the two values (pinned host memory the device can write), or nullptr
 };
-hipError_t launch_softmax_rows(const VerifyCall& c, hipStream_t st);  // logits -> probabilities in place
-hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st);   // decision on probabilities
+hipError_t launch_softmax_stats(const VerifyCall& c, hipStream_t st);  // per-row (max, sum of exp) partials of the logits
+hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st);    // decision on probabilities, or (from_logits) on
+                                                                        // logits + the partials of launch_softmax_stats
 hipError_t launch_greedy_accept(const VerifyCall& c, hipStream_t st); // decision on logits
 
 // zero the cached rows of positions [first_pos + result[0] + 1, first_pos + k] in every layer

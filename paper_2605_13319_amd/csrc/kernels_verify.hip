@@ -41,8 +41,8 @@ __device__ __forceinline__ unsigned long long shfl_up_u64(unsigned long long v, 
 }
 
 // ------------------------------------------------------------------------------------------
-// softmax: per (row, chunk) max and sum of exp; then p = exp(z - M) / S with M, S merged from the
-// chunk partials in index order by every workgroup alike
+// softmax: per (row, chunk) max and sum of exp; p = exp(z - M) / S with M, S merged from the chunk
+// partials in index order is formed where it is used (spec_accept_kernel), never written out
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kVThreads) void softmax_stats_kernel(const float* __restrict__ z, int V,
                                                                   float* __restrict__ stats) {
@@ -69,28 +69,9 @@ __global__ __launch_bounds__(kVThreads) void softmax_stats_kernel(const float* _
   }
 }
 
-__global__ __launch_bounds__(kVThreads) void softmax_write_kernel(float* __restrict__ z, int V,
-                                                                  const float* __restrict__ stats) {
-  const int row = blockIdx.y, c = blockIdx.x;
-  const int per = (V + kStatChunks - 1) / kStatChunks;
-  const int lo = c * per, hi = min(V, lo + per);
-  const float* st = stats + (size_t)row * kStatChunks * 2;
-  float M = -INFINITY;
-  for (int j = 0; j < kStatChunks; ++j)
-    if (j * per < V) M = fmaxf(M, st[j * 2]);
-  float S = 0.f;
-  for (int j = 0; j < kStatChunks; ++j)
-    if (j * per < V) S += st[j * 2 + 1] * expf(st[j * 2] - M);
-  float* zr = z + (size_t)row * V;
-  for (int i = lo + threadIdx.x; i < hi; i += kVThreads) zr[i] = expf(zr[i] - M) / S;
-}
-
-hipError_t launch_softmax_rows(const VerifyCall& c, hipStream_t st) {
+hipError_t launch_softmax_stats(const VerifyCall& c, hipStream_t st) {
   dim3 grid(kStatChunks, c.k + 1);
   softmax_stats_kernel<<<grid, kVThreads, 0, st>>>(c.logits_or_p, c.V, c.row_stats);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  softmax_write_kernel<<<grid, kVThreads, 0, st>>>(c.logits_or_p, c.V, c.row_stats);
   return hipGetLastError();
 }
 
@@ -117,7 +98,11 @@ __device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v
   return red[0] + red[1] + red[2] + red[3];
 }
 
+// `stats` == nullptr: `p` holds probabilities.  Otherwise `p` holds logits and `stats` the (max,
+// sum of exp) chunk partials of softmax_stats_kernel: the probabilities are formed on the fly by the
+// very expressions softmax_write_kernel uses, so the decision is the one the two-step path takes.
 __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __restrict__ p, const float* __restrict__ q,
+                                                                const float* __restrict__ stats,
                                                                 int k, int V, RowTokens drafts, Uniforms un,
                                                                 unsigned long long* partial,
                                                                 unsigned* counter,
@@ -125,27 +110,57 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
                                                                 int32_t* __restrict__ result_copy) {
   __shared__ unsigned long long red[kVThreads / 64];
   __shared__ int s_a, s_last;
+  __shared__ float s_M[kMaxRows], s_S[kMaxRows];
   const int tid = threadIdx.x;
-  // every workgroup walks the k tests itself (2k scalar loads)
-  if (tid == 0) {
-    int a = 0;
-    while (a < k) {
-      const int d = drafts.tok[a];
-      if (!accept_test(p[(size_t)a * V + d], q[(size_t)a * V + d], un.u[a])) break;
-      ++a;
+  const bool from_logits = stats != nullptr;
+  __shared__ int s_ok[kMaxRows];
+  // Row statistics: one wave per row, lane j holding chunk j's (max, sum of exp); the row's max and
+  // the rescaled sum are folded across the wave in a fixed butterfly order.  Every workgroup does
+  // this for all k + 1 rows itself (one 512-byte load per row).
+  static_assert(kStatChunks == 64, "one chunk partial per lane");
+  if (from_logits) {
+    const int sper = (V + kStatChunks - 1) / kStatChunks;
+    const int lane = tid & 63;
+    for (int row = tid >> 6; row <= k; row += kVThreads / 64) {
+      const bool have = lane * sper < V;
+      const float2 ms = have ? *(const float2*)(stats + ((size_t)row * kStatChunks + lane) * 2) : make_float2(-INFINITY, 0.f);
+      float M = ms.x;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+      float S = have ? ms.y * expf(ms.x - M) : 0.f;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) S += __shfl_xor(S, o, 64);
+      if (lane == 0) {
+        s_M[row] = M;
+        s_S[row] = S;
+      }
     }
+  }
+  __syncthreads();
+  if (tid < k) {  // the k tests side by side
+    const int d = drafts.tok[tid];
+    const float v = p[(size_t)tid * V + d];
+    s_ok[tid] = accept_test(from_logits ? expf(v - s_M[tid]) / s_S[tid] : v, q[(size_t)tid * V + d], un.u[tid]) ? 1 : 0;
+  }
+  __syncthreads();
+  auto prob = [&](int row, int i) -> float {
+    const float v = p[(size_t)row * V + i];
+    return from_logits ? expf(v - s_M[row]) / s_S[row] : v;
+  };
+  if (tid == 0) {  // the tests count in order, up to the first failure
+    int a = 0;
+    while (a < k && s_ok[a]) ++a;
     s_a = a;
   }
   __syncthreads();
   const int a = s_a;
   const bool residual = a < k;
-  const float* pr = p + (size_t)a * V;
   const float* qr = q + (size_t)(residual ? a : 0) * V;
 
   const int per = (V + kScanBlocks - 1) / kScanBlocks;
   const int lo = blockIdx.x * per, hi = min(V, lo + per);
   unsigned long long s = 0;
-  for (int i = lo + tid; i < hi; i += kVThreads) s += fixed_weight(pr[i], residual ? qr[i] : 0.f, residual);
+  for (int i = lo + tid; i < hi; i += kVThreads) s += fixed_weight(prob(a, i), residual ? qr[i] : 0.f, residual);
   s = block_sum_u64(s, red);
   if (tid == 0) {
     partial[blockIdx.x] = s;
@@ -166,7 +181,7 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
     float best = -INFINITY;
     int bi = 0x7fffffff;
     for (int i = tid; i < V; i += 64) {
-      const float v = pr[i];
+      const float v = prob(a, i);
       if (v > best) { best = v; bi = i; }
     }
     for (int o = 32; o > 0; o >>= 1) {
@@ -191,7 +206,7 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
     bool found = false;
     for (int base = clo; base < chi && !found; base += 64) {
       const int i = base + tid;
-      unsigned long long w = (i < chi) ? fixed_weight(pr[i], residual ? qr[i] : 0.f, residual) : 0ull;
+      unsigned long long w = (i < chi) ? fixed_weight(prob(a, i), residual ? qr[i] : 0.f, residual) : 0ull;
       unsigned long long inc = w;  // inclusive scan across the wave
 #pragma unroll
       for (int d = 1; d < 64; d <<= 1) {
@@ -222,7 +237,8 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
 hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st) {
   Uniforms un;
   for (int i = 0; i < kMaxRows; ++i) un.u[i] = c.u[i];
-  spec_accept_kernel<<<kScanBlocks, kVThreads, 0, st>>>(c.logits_or_p, c.q, c.k, c.V, c.drafts, un, c.scan_partial,
+  spec_accept_kernel<<<kScanBlocks, kVThreads, 0, st>>>(c.logits_or_p, c.q, c.from_logits ? c.row_stats : nullptr, c.k,
+                                                        c.V, c.drafts, un, c.scan_partial,
                                                         c.counter, c.result, c.result_copy);
   return hipGetLastError();
 }
