@@ -50,6 +50,7 @@ struct pipesd_model {
         *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
   unsigned* counters = nullptr;
   ActArena arena{};  // bf16 path: per-layer activation buffers
+  RowMap* rowmap_dev = nullptr;  // bf16 path: per-row placement of a pass that holds several clients
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
   float* row_stats = nullptr;
@@ -240,6 +241,7 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     if ((rc = dev_alloc(m, (void**)&m->arena.base, arena_bytes))) return rc;
     HIP_TRY(hipMemset(m->arena.base, 0, arena_bytes));
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
+    if ((rc = dev_alloc(m, (void**)&m->rowmap_dev, sizeof(RowMap)))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
     HIP_TRY(hipMemset(m->bar, 0, 4096));
   }
@@ -555,29 +557,66 @@ static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int row
   return c;
 }
 
-static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* row_tokens, int rows, int start_pos,
-                    bool want_logits, hipStream_t st) {
+// The rows of one pass: one client's k + 1 rows, or (bf16) the rows of up to 16 clients one after
+// the other, at most 32 in all.
+struct PassClient {
+  int32_t seq, rows, start_pos;
+};
+struct PassLayout {
+  int n_clients = 0, rows = 0;
+  PassClient client[kMaxPassClients];
+  RowTokens tok{};
+};
+
+static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool want_logits, hipStream_t st) {
   const pipesd_config& c = m->cfg;
   const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, F = c.d_ffn, V = c.vocab;
   const int nqkv = qd + 2 * kvd;
-  const KvView view = view_of(kv, seq);
-  RowTokens rt{};
-  for (int r = 0; r < rows; ++r) rt.tok[r] = row_tokens[r];
-  const int chunk = attn_chunk_tokens(c.dtype);
-  const int nsplit = attn_nsplit(start_pos + rows, chunk);
+  const int rows = pl.rows;
   const bool bf = c.dtype == PIPESD_BF16;
-  const size_t part_floats = (size_t)c.n_q_heads * rows * nsplit * (c.head_dim + 4);
+  const bool single = pl.n_clients == 1;
+  if (pl.n_clients < 1 || pl.n_clients > kMaxPassClients || rows < 1 || rows > kMaxRows || (!bf && !single))
+    return PIPESD_EINVAL;
+  const int32_t seq = pl.client[0].seq;
+  const int start_pos = pl.client[0].start_pos;
+  // one client: the block table pointer is the client's own; several: the tables' common base + an offset per row
+  KvView view = view_of(kv, single ? seq : 0);
+  const int chunk = attn_chunk_tokens(c.dtype);
+  const int nsplit = attn_nsplit(start_pos + rows, chunk);  // (one client)
+  RowMap map{};
+  AttnBatch ab{};
+  ab.n = pl.n_clients;
+  size_t part_floats = 0;
+  for (int i = 0, r0 = 0; i < pl.n_clients; ++i) {
+    const PassClient& pc = pl.client[i];
+    const int32_t toff = single ? 0 : pc.seq * kv->n_blocks;
+    for (int r = 0; r < pc.rows; ++r) {
+      map.pos[r0 + r] = pc.start_pos + r;
+      map.table_off[r0 + r] = toff;
+    }
+    AttnClient& ac = ab.c[i];
+    ac.row_off = r0;
+    ac.m = pc.rows;
+    ac.start_pos = pc.start_pos;
+    ac.table_off = toff;
+    ac.nsplit = attn_nsplit(pc.start_pos + pc.rows, chunk);
+    if (part_floats > (size_t)INT32_MAX) return PIPESD_ENOMEM;
+    ac.part_off = (int32_t)part_floats;
+    part_floats += (size_t)c.n_q_heads * pc.rows * ac.nsplit * (c.head_dim + 4);
+    r0 += pc.rows;
+  }
   int rc = ensure_attn_scratch(m, part_floats * (bf ? c.n_layers : 1));
   if (rc) return rc;
   ActArena& ar = m->arena;
   ar.part = m->attn_part;
   ar.part_stride = bf ? part_floats : 0;
-  HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, rt, rows, start_pos, d, c.head_dim, m->theta, bf ? ar.ra(0) : m->xres,
+  const RowMap* rows_dev = single ? nullptr : m->rowmap_dev;
+  HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, pl.tok, map, rows, d, c.head_dim, m->theta, bf ? ar.ra(0) : m->xres,
                             m->rope_cs, bf ? m->attn_norm[0] : nullptr, bf ? ar.xa(0) : nullptr, bf ? ar.sa(0) : nullptr,
-                            ar.ssq_stride, st));
+                            ar.ssq_stride, single ? nullptr : m->rowmap_dev, st));
   int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
   bool fused = false;
-  if (c.dtype == PIPESD_BF16 && m->fused_enabled) {
+  if (bf && single && m->fused_enabled) {
     LayersCall lc{};
     lc.slabs = m->slabs;
     lc.final_norm = m->final_norm;
@@ -617,6 +656,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     at.part = ar.partials(l);
     at.out = m->attn_out;
     at.outp = bf ? ar.ap(l) : nullptr;
+    at.batch = ab;
     if (c.dtype == PIPESD_F32) {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
@@ -648,6 +688,7 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
         ProfGemm pg(m, PIPESD_PROF_GEMM_QKV, g);
         g.out = ar.q(l);
         g.ldo = qd;
+        g.rows = rows_dev;
         g.kv = view;
         g.layer = l;
         g.start_pos = start_pos;
@@ -703,6 +744,16 @@ static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* 
     }
   }
   return PIPESD_OK;
+}
+
+static int run_rows(pipesd_model* m, pipesd_kv* kv, int32_t seq, const int32_t* row_tokens, int rows, int start_pos,
+                    bool want_logits, hipStream_t st) {
+  PassLayout pl;
+  pl.n_clients = 1;
+  pl.rows = rows;
+  pl.client[0] = PassClient{seq, rows, start_pos};
+  for (int r = 0; r < rows; ++r) pl.tok.tok[r] = row_tokens[r];
+  return run_pass(m, kv, pl, want_logits, st);
 }
 
 // The fused layer kernel raises a sticky flag if one of its device-wide barriers timed out.
@@ -787,18 +838,13 @@ static int check_verify_args(const pipesd_model* model, const pipesd_kv* kv, int
   return PIPESD_OK;
 }
 
-// forward + decision + cache trim of one sequence, enqueued on `st`; the decision lands in
-// result[0..1] on the device.  On failure the sequence's block list is back to what it was.
-static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* draft_tokens, int32_t k,
-                          const float* draft_probs, const float* uniforms, int32_t* result, int32_t* result_copy,
-                          hipStream_t st) {
-  SeqState& s = kv->seqs[seq];
-  const int32_t lp = (int32_t)s.text.size();
-  int32_t start = 0;
-  int rc = verify_common(model, kv, seq, draft_tokens, k, &start, st);
-  if (rc) return rc;
+// decision + cache trim of one sequence on logits rows [row_off, row_off + k] of the model's logits
+// buffer, enqueued on `st`; the decision lands in result[0..1] on the device (and in result_copy)
+static hipError_t enqueue_decision(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t row_off, int32_t start,
+                                   const int32_t* draft_tokens, int32_t k, const float* draft_probs,
+                                   const float* uniforms, int32_t* result, int32_t* result_copy, hipStream_t st) {
   VerifyCall vc{};
-  vc.logits_or_p = model->logits;
+  vc.logits_or_p = model->logits + (size_t)row_off * model->cfg.vocab;
   vc.q = draft_probs;
   vc.k = k;
   vc.V = model->cfg.vocab;
@@ -811,18 +857,30 @@ static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const
   vc.result = result;
   vc.result_copy = result_copy;
   hipError_t e = hipSuccess;
-  {
-    ProfScope ps(model, PIPESD_PROF_VERIFY, st);
-    if (draft_probs) {
-      vc.from_logits = true;  // probabilities are formed inside the decision kernel, never written out
-      e = launch_softmax_stats(vc, st);
-      if (e == hipSuccess) e = launch_spec_accept(vc, st);
-    } else {
-      e = launch_greedy_accept(vc, st);
-    }
-    if (e == hipSuccess)
-      e = launch_kv_trim(model->cfg.dtype, view_of(kv, seq), model->cfg.n_layers, start, k, result, st);
+  ProfScope ps(model, PIPESD_PROF_VERIFY, st);
+  if (draft_probs) {
+    vc.from_logits = true;  // probabilities are formed inside the decision kernel, never written out
+    e = launch_softmax_stats(vc, st);
+    if (e == hipSuccess) e = launch_spec_accept(vc, st);
+  } else {
+    e = launch_greedy_accept(vc, st);
   }
+  if (e == hipSuccess)
+    e = launch_kv_trim(model->cfg.dtype, view_of(kv, seq), model->cfg.n_layers, start, k, result, st);
+  return e;
+}
+
+// forward + decision + cache trim of one sequence, enqueued on `st`.  On failure the sequence's
+// block list is back to what it was.
+static int enqueue_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* draft_tokens, int32_t k,
+                          const float* draft_probs, const float* uniforms, int32_t* result, int32_t* result_copy,
+                          hipStream_t st) {
+  SeqState& s = kv->seqs[seq];
+  const int32_t lp = (int32_t)s.text.size();
+  int32_t start = 0;
+  int rc = verify_common(model, kv, seq, draft_tokens, k, &start, st);
+  if (rc) return rc;
+  hipError_t e = enqueue_decision(model, kv, seq, 0, start, draft_tokens, k, draft_probs, uniforms, result, result_copy, st);
   if (e != hipSuccess) {
     release_beyond(kv, s, lp - 1);
     return hip_fail(e, "verify step");
@@ -916,16 +974,41 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
     }
   };
   for (int32_t i = 0; i < 2 * n_seqs; ++i) model->result_host[4 + i] = -1;
-  for (int32_t i = 0; i < n_seqs; ++i) {
-    const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
-    int rc = enqueue_verify(model, kv, seq_ids[i], draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
-                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr, model->result_dev + 2 * i,
-                            model->result_host + 4 + 2 * i, st);
+  // bf16: clients are packed, in the order given, into passes of up to 32 rows and 16 clients, so
+  // that the weights are streamed once per pass instead of once per client (a row's results do not
+  // depend on which other rows share its pass); fp32: one pass per client
+  const bool pack = model->cfg.dtype == PIPESD_BF16;
+  for (int32_t first = 0; first < n_seqs;) {
+    PassLayout pl;
+    int32_t last = first;
+    while (last < n_seqs && pl.n_clients < (pack ? kMaxPassClients : 1) && pl.rows + k_per_seq[last] + 1 <= kMaxRows) {
+      const int32_t sq = seq_ids[last], k = k_per_seq[last];
+      const SeqState& s = kv->seqs[sq];
+      pl.client[pl.n_clients++] = PassClient{sq, k + 1, (int32_t)s.text.size() - 1};
+      pl.tok.tok[pl.rows] = s.text.back();
+      for (int32_t j = 0; j < k; ++j) pl.tok.tok[pl.rows + 1 + j] = draft_tokens_concat[tok_off[last] + j];
+      pl.rows += k + 1;
+      ++last;
+    }
+    int rc = PIPESD_OK;
+    for (int32_t i = first; i < last && rc == PIPESD_OK; ++i)
+      rc = ensure_blocks(kv, seq_ids[i], (int32_t)kv->seqs[seq_ids[i]].text.size() + k_per_seq[i], st);
+    if (rc == PIPESD_OK) rc = run_pass(model, kv, pl, true, st);
+    for (int32_t i = first, row_off = 0; i < last && rc == PIPESD_OK; ++i) {
+      const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
+      const hipError_t e = enqueue_decision(model, kv, seq_ids[i], row_off, pl.client[i - first].start_pos,
+                                            draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
+                                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr,
+                                            model->result_dev + 2 * i, model->result_host + 4 + 2 * i, st);
+      if (e != hipSuccess) rc = hip_fail(e, "batched verify");
+      row_off += k_per_seq[i] + 1;
+    }
     if (rc) {
       (void)hipStreamSynchronize(st);
-      undo(i);
+      undo(last);
       return rc;
     }
+    first = last;
   }
   hipError_t e = read_layers_flag(model, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);

@@ -37,6 +37,22 @@ struct KvView {
   int32_t n_kv_heads, head_dim;
 };
 
+// Rows of several clients in one pass (bf16 path): where each row sits in its own client's sequence.
+struct RowMap {
+  int32_t pos[kMaxRows];        // position of the row in its client's sequence
+  int32_t table_off[kMaxRows];  // entries from KvView::table to the client's block table
+};
+constexpr int kMaxPassClients = 16;  // clients whose rows share one pass (each has at least 2 rows)
+struct AttnClient {
+  int32_t row_off, m, start_pos;  // the client's rows in the pass; position of its first row
+  int32_t table_off;              // entries from KvView::table to the client's block table
+  int32_t nsplit, part_off;       // 256-token splits; floats from the partial buffer's start to the client's partials
+};
+struct AttnBatch {
+  int32_t n;
+  AttnClient c[kMaxPassClients];
+};
+
 __device__ __forceinline__ int64_t k_index(const KvView& kv, int layer, int pos, int kvh, int e) {
   const int blk = kv.table[pos / kBlockTokens];
   return (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems +
@@ -84,9 +100,12 @@ struct RowTokens {
 
 // embedding gather into the fp32 residual stream + rotary cos/sin of the m positions; for bf16
 // models also the packed, gained copy and the per-row sum of squares for the first fused norm
-hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, int m, int start_pos, int d_model,
-                             int head_dim, const double* theta, float* xres, float* rope_cs, const float* gain,
-                             void* xpk, float* ssq_out, int ssq_stride, hipStream_t st);
+// `map` gives every row's position; it is also copied to `map_dev` (if not null) for the kernels
+// that need it per row
+hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, const RowMap& map, int m,
+                             int d_model, int head_dim, const double* theta, float* xres, float* rope_cs,
+                             const float* gain, void* xpk, float* ssq_out, int ssq_stride, RowMap* map_dev,
+                             hipStream_t st);
 
 // ---- fp32 path (plain ALU kernels) ----
 hipError_t launch_rmsnorm_rows(const float* x, const float* gain, float eps, int m, int d, float* out, hipStream_t st);
@@ -123,6 +142,7 @@ struct GemmCall {
   KvView kv;
   int layer, start_pos, n_q_heads;
   const float* rope_cs;
+  const RowMap* rows;  // device; nullptr: one client, row r at position start_pos + r, table kv.table
   // optional: events that take the kernel's own start and end (no marker packets around it)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
@@ -189,13 +209,14 @@ constexpr int kLayersErrWord = 32 * 9;
 // ---- attention over the paged cache (both dtypes) ----
 struct AttnCall {
   int dtype;
-  const float* q;  // [m][n_q_heads*head_dim]
+  const float* q;  // [rows][n_q_heads*head_dim]
   KvView kv;
-  int layer, m, start_pos, n_q_heads;
-  int chunk;       // tokens per workgroup
-  float* part;     // [(head*m + r)*nsplit + split][head_dim + 2]
+  int layer, m, start_pos, n_q_heads;  // fp32 cache: the one client's rows and first position
+  int chunk;       // fp32 cache: tokens per workgroup
+  float* part;     // per client [(head*m + r)*nsplit + split][head_dim + 4]
   float* out;      // fp32 cache: [m][n_q_heads*head_dim]
   void* outp;      // bf16 cache: packed output (ActPack with n_q_heads*head_dim columns)
+  AttnBatch batch; // bf16 cache: the clients of the pass
 };
 int attn_nsplit(int total_tokens, int chunk);
 int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type

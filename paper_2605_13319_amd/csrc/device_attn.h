@@ -198,9 +198,10 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
 // Merge the splits of one (row, head): one thread per 8 consecutive elements, all of a batch's loads
 // issued before any is used; the result is written packed for the O projection.  `gt` numbers the
 // threads over all (pair, segment) tasks.
+// `row_off`: the client's first row in the pass (rows of the packed output).
 template <bool CO>
 __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int n_q_heads, int h, int nsplit,
-                                                  u32x4* outp, int gt) {
+                                                  u32x4* outp, int gt, int row_off = 0) {
   constexpr int BATCH = 9;
   const int segs = h / 8;
   const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
@@ -249,7 +250,7 @@ __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int 
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] /= L;
-  store_act8x<CO>(outp, r, head * h + e0, acc);
+  store_act8x<CO>(outp, row_off + r, head * h + e0, acc);
 }
 
 }  // namespace pipesd

@@ -54,6 +54,7 @@ struct GemmArgs {
   const float* gain_next; // RESID: gain applied to the packed copy
   float* ssq_out;         // RESID: [row][ssq_stride] per-tile sums of x_new^2
   const float* rope_cs;
+  const RowMap* rows;     // QKV: per-row position and block table (several clients in the pass), or nullptr
   KvView kv;
   int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
   int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1 or 2)
@@ -250,7 +251,12 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
         Xwg<CO>::st4f(o + half, r1);
       } else {
         uint16_t* pool = (uint16_t*)a.kv.pool;
-        const int pos = a.start_pos + row;
+        KvView kvr = a.kv;  // the row's own client
+        int pos = a.start_pos + row;
+        if (a.rows != nullptr) {
+          pos = a.rows->pos[row];
+          kvr.table += a.rows->table_off[row];
+        }
         uint16_t b0[4], b1[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -259,16 +265,16 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
         }
         if (hd < a.n_q_heads + a.kv.n_kv_heads) {
           const int kvh = hd - a.n_q_heads;
-          Xwg<CO>::st2(pool + k_index(a.kv, a.layer, pos, kvh, i0),
+          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0),
                        u32x2{(unsigned)b0[0] | ((unsigned)b0[1] << 16), (unsigned)b0[2] | ((unsigned)b0[3] << 16)});
-          Xwg<CO>::st2(pool + k_index(a.kv, a.layer, pos, kvh, i0 + half),
+          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0 + half),
                        u32x2{(unsigned)b1[0] | ((unsigned)b1[1] << 16), (unsigned)b1[2] | ((unsigned)b1[3] << 16)});
         } else {
           const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            Xwg<CO>::st_u16(pool + v_index(a.kv, a.layer, pos, kvh, i0 + i), b0[i]);
-            Xwg<CO>::st_u16(pool + v_index(a.kv, a.layer, pos, kvh, i0 + half + i), b1[i]);
+            Xwg<CO>::st_u16(pool + v_index(kvr, a.layer, pos, kvh, i0 + i), b0[i]);
+            Xwg<CO>::st_u16(pool + v_index(kvr, a.layer, pos, kvh, i0 + half + i), b1[i]);
           }
         }
       }

@@ -91,16 +91,24 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
 // bf16 cache: the same computation on the matrix cores (device code in device_attn.h)
 // ------------------------------------------------------------------------------------------------
 template <int HD>
-__global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float* q, KvView kv, int layer, int m,
-                                                                    int start_pos, int n_q_heads, int nsplit,
-                                                                    float* part) {
+// grid = (kv heads x clients of the pass, splits of the longest client, query tiles of the largest client)
+__global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float* q, KvView kv, int layer, int n_q_heads,
+                                                                    AttnBatch batch, float* part) {
   extern __shared__ float lds[];
-  attn_task<HD, false>(q, kv, layer, m, start_pos, n_q_heads, nsplit, part, blockIdx.x, blockIdx.y, blockIdx.z, lds);
+  const int ci = blockIdx.x / kv.n_kv_heads, kvh = blockIdx.x % kv.n_kv_heads;
+  const AttnClient c = batch.c[ci];
+  if ((int)blockIdx.y >= c.nsplit || (int)blockIdx.z * 16 >= n_q_heads / kv.n_kv_heads * c.m) return;  // whole workgroup
+  kv.table += c.table_off;
+  attn_task<HD, false>(q + (size_t)c.row_off * n_q_heads * HD, kv, layer, c.m, c.start_pos, n_q_heads, c.nsplit,
+                       part + c.part_off, kvh, blockIdx.y, blockIdx.z, lds);
 }
 
-__global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* part, int m, int n_q_heads, int h,
-                                                              int nsplit, uint4* outp) {
-  attn_merge_thread<false>(part, m, n_q_heads, h, nsplit, (u32x4*)outp, blockIdx.x * blockDim.x + threadIdx.x);
+// grid = (threads of the largest client / 64, clients)
+__global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* part, int n_q_heads, int h, AttnBatch batch,
+                                                              uint4* outp) {
+  const AttnClient c = batch.c[blockIdx.y];
+  attn_merge_thread<false>(part + c.part_off, c.m, n_q_heads, h, c.nsplit, (u32x4*)outp,
+                           blockIdx.x * blockDim.x + threadIdx.x, c.row_off);
 }
 
 // merge the splits of one (row, head): o = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s, splits taken
@@ -146,9 +154,15 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     attn_partial_kernel<float><<<grid, kAttnThreads, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads,
                                                                 c.chunk, nsplit, c.part);
   } else {
-    const int nsp = attn_nsplit(total, kAttnWgTokens);
+    const AttnBatch& b = c.batch;
+    if (b.n < 1 || b.n > kMaxPassClients) return hipErrorInvalidValue;
     const int group = c.n_q_heads / c.kv.n_kv_heads;
-    dim3 grid(c.kv.n_kv_heads, nsp, (group * c.m + 15) / 16);
+    int max_split = 1, max_m = 1;
+    for (int i = 0; i < b.n; ++i) {
+      max_split = b.c[i].nsplit > max_split ? b.c[i].nsplit : max_split;
+      max_m = b.c[i].m > max_m ? b.c[i].m : max_m;
+    }
+    dim3 grid(c.kv.n_kv_heads * b.n, max_split, (group * max_m + 15) / 16);
     if (h != 128 && h != 64) return hipErrorInvalidValue;
     const size_t lds = attn_lds_floats(h) * sizeof(float);
     static bool lds_allowed = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
@@ -162,20 +176,22 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
       lds_allowed = true;
     }
     if (h == 128)
-      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
-                                                                c.part);
+      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part);
     else
-      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.m, c.start_pos, c.n_q_heads, nsp,
-                                                               c.part);
+      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int threads = c.m * c.n_q_heads * (h / 8);
-  if (c.dtype == PIPESD_F32)
+  if (c.dtype == PIPESD_F32) {
+    const int threads = c.m * c.n_q_heads * (h / 8);
     attn_combine_kernel<<<(threads + 255) / 256, 256, 0, st>>>(c.part, c.m, c.n_q_heads, h, nsplit, c.out);
-  else
-    attn_merge_packed_kernel<<<(threads + 63) / 64, 64, 0, st>>>(c.part, c.m, c.n_q_heads, h,
-                                                                 attn_nsplit(total, kAttnWgTokens), (uint4*)c.outp);
+  } else {
+    int max_m = 1;
+    for (int i = 0; i < c.batch.n; ++i) max_m = c.batch.c[i].m > max_m ? c.batch.c[i].m : max_m;
+    const int threads = max_m * c.n_q_heads * (h / 8);
+    attn_merge_packed_kernel<<<dim3((threads + 63) / 64, c.batch.n), 64, 0, st>>>(c.part, c.n_q_heads, h, c.batch,
+                                                                                   (uint4*)c.outp);
+  }
   return hipGetLastError();
 }
 

@@ -86,6 +86,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.gain_next = c.gain_next;
   a.ssq_out = c.ssq_out;
   a.rope_cs = c.rope_cs;
+  a.rows = c.rows;
   a.kv = c.kv;
   a.m = c.m;
   a.K = p.K;

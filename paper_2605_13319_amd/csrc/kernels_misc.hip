@@ -8,13 +8,17 @@ namespace pipesd {
 // evaluated in fp64 and rounded once (rotary positions; the target forward of Sec. 2.2).
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, int m, int start_pos, int d, int half,
+__global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, RowMap map, int m, int d, int half,
                                   const double* __restrict__ theta, float* __restrict__ xres,
                                   float* __restrict__ rope_cs, const float* __restrict__ gain, uint4* xpk,
-                                  float* __restrict__ ssq_out, int ssq_stride) {
+                                  float* __restrict__ ssq_out, int ssq_stride, RowMap* __restrict__ map_dev) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   if (r >= m) return;
+  if (map_dev != nullptr && r == 0 && threadIdx.x < kMaxRows) {
+    map_dev->pos[threadIdx.x] = map.pos[threadIdx.x];
+    map_dev->table_off[threadIdx.x] = map.table_off[threadIdx.x];
+  }
   const size_t base = (size_t)toks.tok[r] * d;
   float sq = 0.f;
   for (int j = threadIdx.x; j < d / 8; j += blockDim.x) {
@@ -40,22 +44,22 @@ __global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, int
     if (threadIdx.x == 0) ssq_out[(size_t)r * ssq_stride] = (red[0] + red[1]) + (red[2] + red[3]);
   }
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
-    const double ang = (double)(start_pos + r) * theta[i];
+    const double ang = (double)map.pos[r] * theta[i];
     rope_cs[((size_t)r * half + i) * 2 + 0] = (float)cos(ang);
     rope_cs[((size_t)r * half + i) * 2 + 1] = (float)sin(ang);
   }
 }
 
-hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, int m, int start_pos, int d_model,
-                             int head_dim, const double* theta, float* xres, float* rope_cs, const float* gain,
-                             void* xpk, float* ssq_out, int ssq_stride, hipStream_t st) {
+hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, const RowMap& map, int m,
+                             int d_model, int head_dim, const double* theta, float* xres, float* rope_cs,
+                             const float* gain, void* xpk, float* ssq_out, int ssq_stride, RowMap* map_dev,
+                             hipStream_t st) {
   if (dtype == PIPESD_F32)
-    setup_rows_kernel<float><<<m, 256, 0, st>>>((const float*)tok_emb, toks, m, start_pos, d_model, head_dim / 2,
-                                                theta, xres, rope_cs, nullptr, nullptr, nullptr, 0);
+    setup_rows_kernel<float><<<m, 256, 0, st>>>((const float*)tok_emb, toks, map, m, d_model, head_dim / 2, theta, xres,
+                                                rope_cs, nullptr, nullptr, nullptr, 0, map_dev);
   else
-    setup_rows_kernel<uint16_t><<<m, 256, 0, st>>>((const uint16_t*)tok_emb, toks, m, start_pos, d_model,
-                                                   head_dim / 2, theta, xres, rope_cs, gain, (uint4*)xpk, ssq_out,
-                                                   ssq_stride);
+    setup_rows_kernel<uint16_t><<<m, 256, 0, st>>>((const uint16_t*)tok_emb, toks, map, m, d_model, head_dim / 2, theta,
+                                                   xres, rope_cs, gain, (uint4*)xpk, ssq_out, ssq_stride, map_dev);
   return hipGetLastError();
 }
 
