@@ -49,7 +49,9 @@ struct pipesd_model {
   float *xres = nullptr, *hbuf = nullptr, *qkv = nullptr, *qbuf = nullptr, *attn_out = nullptr, *gu = nullptr,
         *act2 = nullptr, *logits = nullptr, *rope_cs = nullptr;
   unsigned* counters = nullptr;
-  ActArena arena{};  // bf16 path: per-layer activation buffers
+  ActArena arena{};  // bf16 path: per-layer activation buffers (passes of up to 32 rows)
+  int pass_act_tiles = 2;  // row tiles of the buffers of the pass being enqueued
+  ActArena arena_big{};  // bf16 path: one buffer of each kind, 8 row tiles (passes of several clients, up to 128 rows)
   RowMap* rowmap_dev = nullptr;  // bf16 path: per-row placement of a pass that holds several clients
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
@@ -228,8 +230,9 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   if ((rc = dev_alloc(m, (void**)&m->attn_out, R * qd * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->gu, R * 2 * (size_t)F * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->act2, R * (size_t)F * 4))) return rc;
-  if ((rc = dev_alloc(m, (void**)&m->logits, R * (size_t)V * 4))) return rc;
-  if ((rc = dev_alloc(m, (void**)&m->rope_cs, R * c.head_dim * 4))) return rc;
+  const size_t RP = c.dtype == PIPESD_BF16 ? kMaxPassRows : kMaxRows;  // rows of the largest pass
+  if ((rc = dev_alloc(m, (void**)&m->logits, RP * (size_t)V * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->rope_cs, RP * c.head_dim * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->row_stats, (R * 64 * 2 + 64) * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->scan_partial, 64 * 8))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->result_dev, (size_t)2 * kMaxBatchResults * 4))) return rc;
@@ -237,9 +240,12 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
   if (c.dtype == PIPESD_BF16) {
     if (device_cu_count() <= 0) return PIPESD_EHIP;
-    const size_t arena_bytes = act_arena_layout(m->arena, L, d, qd, F);
+    const size_t arena_bytes = act_arena_layout(m->arena, L, d, qd, F, true, 2);
     if ((rc = dev_alloc(m, (void**)&m->arena.base, arena_bytes))) return rc;
     HIP_TRY(hipMemset(m->arena.base, 0, arena_bytes));
+    const size_t big_bytes = act_arena_layout(m->arena_big, L, d, qd, F, false, kMaxPassRows / 16);
+    if ((rc = dev_alloc(m, (void**)&m->arena_big.base, big_bytes))) return rc;
+    HIP_TRY(hipMemset(m->arena_big.base, 0, big_bytes));
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->rowmap_dev, sizeof(RowMap)))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
@@ -548,6 +554,7 @@ static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int row
   c.K = K;
   c.m = rows;
   c.actp = actp;
+  c.act_tiles = m->pass_act_tiles;
   c.ssq_in = ssq_in;
   c.ssq_parts = norm_parts;
   c.ssq_stride = m->arena.ssq_stride;
@@ -565,8 +572,9 @@ struct PassClient {
 struct PassLayout {
   int n_clients = 0, rows = 0;
   PassClient client[kMaxPassClients];
-  RowTokens tok{};
+  PassTokens tok{};
 };
+constexpr int kPassRowsCap = 128;  // rows the batched call puts into one pass (<= kMaxPassRows)
 
 static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool want_logits, hipStream_t st) {
   const pipesd_config& c = m->cfg;
@@ -575,7 +583,8 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
   const int rows = pl.rows;
   const bool bf = c.dtype == PIPESD_BF16;
   const bool single = pl.n_clients == 1;
-  if (pl.n_clients < 1 || pl.n_clients > kMaxPassClients || rows < 1 || rows > kMaxRows || (!bf && !single))
+  if (pl.n_clients < 1 || pl.n_clients > kMaxPassClients || rows < 1 || rows > (bf ? kMaxPassRows : kMaxRows) ||
+      (!bf && !single))
     return PIPESD_EINVAL;
   const int32_t seq = pl.client[0].seq;
   const int start_pos = pl.client[0].start_pos;
@@ -605,15 +614,19 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
     part_floats += (size_t)c.n_q_heads * pc.rows * ac.nsplit * (c.head_dim + 4);
     r0 += pc.rows;
   }
-  int rc = ensure_attn_scratch(m, part_floats * (bf ? c.n_layers : 1));
+  // per-layer partial buffers only where the all-layers kernel may run (one client); otherwise one, reused
+  const bool part_per_layer = bf && single;
+  int rc = ensure_attn_scratch(m, part_floats * (part_per_layer ? c.n_layers : 1));
   if (rc) return rc;
-  ActArena& ar = m->arena;
+  ActArena& ar = rows <= 2 * 16 ? m->arena : m->arena_big;
+  const int act_tiles = rows <= 2 * 16 ? 2 : kMaxPassRows / 16;
+  m->pass_act_tiles = act_tiles;
   ar.part = m->attn_part;
-  ar.part_stride = bf ? part_floats : 0;
+  ar.part_stride = part_per_layer ? part_floats : 0;
   const RowMap* rows_dev = single ? nullptr : m->rowmap_dev;
   HIP_TRY(launch_setup_rows(c.dtype, m->tok_emb, pl.tok, map, rows, d, c.head_dim, m->theta, bf ? ar.ra(0) : m->xres,
-                            m->rope_cs, bf ? m->attn_norm[0] : nullptr, bf ? ar.xa(0) : nullptr, bf ? ar.sa(0) : nullptr,
-                            ar.ssq_stride, single ? nullptr : m->rowmap_dev, st));
+                            m->rope_cs, bf ? m->attn_norm[0] : nullptr, bf ? ar.xa(0) : nullptr, act_tiles,
+                            bf ? ar.sa(0) : nullptr, ar.ssq_stride, single ? nullptr : m->rowmap_dev, st));
   int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
   bool fused = false;
   if (bf && single && m->fused_enabled) {
@@ -656,6 +669,7 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
     at.part = ar.partials(l);
     at.out = m->attn_out;
     at.outp = bf ? ar.ap(l) : nullptr;
+    at.act_tiles = act_tiles;
     at.batch = ab;
     if (c.dtype == PIPESD_F32) {
       {
@@ -981,7 +995,8 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
   for (int32_t first = 0; first < n_seqs;) {
     PassLayout pl;
     int32_t last = first;
-    while (last < n_seqs && pl.n_clients < (pack ? kMaxPassClients : 1) && pl.rows + k_per_seq[last] + 1 <= kMaxRows) {
+    while (last < n_seqs && pl.n_clients < (pack ? kMaxPassClients : 1) &&
+           pl.rows + k_per_seq[last] + 1 <= (pack ? kPassRowsCap : kMaxRows)) {
       const int32_t sq = seq_ids[last], k = k_per_seq[last];
       const SeqState& s = kv->seqs[sq];
       pl.client[pl.n_clients++] = PassClient{sq, k + 1, (int32_t)s.text.size() - 1};

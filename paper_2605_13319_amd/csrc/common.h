@@ -8,7 +8,8 @@
 
 namespace pipesd {
 
-constexpr int kMaxRows = PIPESD_MAX_ROWS;  // rows per pass
+constexpr int kMaxRows = PIPESD_MAX_ROWS;  // rows of one client per pass (k + 1)
+constexpr int kMaxPassRows = 128;          // rows of all clients that share a pass (bf16)
 constexpr int kBlockTokens = 16;           // tokens per KV block
 constexpr int kWave = 64;
 
@@ -39,8 +40,8 @@ struct KvView {
 
 // Rows of several clients in one pass (bf16 path): where each row sits in its own client's sequence.
 struct RowMap {
-  int32_t pos[kMaxRows];        // position of the row in its client's sequence
-  int32_t table_off[kMaxRows];  // entries from KvView::table to the client's block table
+  int32_t pos[kMaxPassRows];        // position of the row in its client's sequence
+  int32_t table_off[kMaxPassRows];  // entries from KvView::table to the client's block table
 };
 constexpr int kMaxPassClients = 16;  // clients whose rows share one pass (each has at least 2 rows)
 struct AttnClient {
@@ -66,17 +67,18 @@ __device__ __forceinline__ int64_t v_index(const KvView& kv, int layer, int pos,
 
 // ActPack: activations handed from one kernel to the next GEMM, already in the B-operand layout of
 // the 16x16x32 bf16 MFMA and split into a bf16 hi + lo pair.  For a consumer with K columns the
-// buffer is uint4[K/32][2 row tiles][hi, lo][16 rows][4 column groups]: entry (c, g) of k-step ks
+// buffer is uint4[K/32][nt row tiles][hi, lo][16 rows][4 column groups] (nt = 2 for passes of up to
+// 32 rows, 8 for the largest passes of several clients): entry (c, g) of k-step ks
 // holds columns ks*32 + g*8 .. +7 of row (row tile)*16 + c and is what MFMA lane g*16 + c consumes.
 // A row's 64 bytes are contiguous, so a pass with m < 16 rows touches only the first m*64 bytes of
 // each 1 KB fragment.
-__device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int c, int g) {
-  return (((size_t)kstep * 2 + mt) * 2 + hl) * 64 + c * 4 + g;
+__device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int c, int g, int nt) {
+  return (((size_t)kstep * nt + mt) * 2 + hl) * 64 + c * 4 + g;
 }
-inline size_t act_pack_bytes(int K) { return (size_t)(K / 32) * 2 * 2 * 64 * 16; }
+inline size_t act_pack_bytes(int K, int nt) { return (size_t)(K / 32) * nt * 2 * 64 * 16; }
 
 // split 8 consecutive columns k0..k0+7 (k0 % 8 == 0) of `row` into hi + lo and store them
-__device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const float (&v)[8]) {
+__device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const float (&v)[8], int nt) {
   uint32_t h[4], l[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -87,8 +89,8 @@ __device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const fl
     l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
   }
   const int g = (k0 & 31) >> 3, c = row & 15;
-  buf[act_index(k0 >> 5, row >> 4, 0, c, g)] = make_uint4(h[0], h[1], h[2], h[3]);
-  buf[act_index(k0 >> 5, row >> 4, 1, c, g)] = make_uint4(l[0], l[1], l[2], l[3]);
+  buf[act_index(k0 >> 5, row >> 4, 0, c, g, nt)] = make_uint4(h[0], h[1], h[2], h[3]);
+  buf[act_index(k0 >> 5, row >> 4, 1, c, g, nt)] = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -97,15 +99,18 @@ __device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const fl
 struct RowTokens {
   int32_t tok[kMaxRows];
 };
+struct PassTokens {
+  int32_t tok[kMaxPassRows];
+};
 
 // embedding gather into the fp32 residual stream + rotary cos/sin of the m positions; for bf16
 // models also the packed, gained copy and the per-row sum of squares for the first fused norm
 // `map` gives every row's position; it is also copied to `map_dev` (if not null) for the kernels
 // that need it per row
-hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, const RowMap& map, int m,
+hipError_t launch_setup_rows(int dtype, const void* tok_emb, const PassTokens& toks, const RowMap& map, int m,
                              int d_model, int head_dim, const double* theta, float* xres, float* rope_cs,
-                             const float* gain, void* xpk, float* ssq_out, int ssq_stride, RowMap* map_dev,
-                             hipStream_t st);
+                             const float* gain, void* xpk, int act_tiles, float* ssq_out, int ssq_stride,
+                             RowMap* map_dev, hipStream_t st);
 
 // ---- fp32 path (plain ALU kernels) ----
 hipError_t launch_rmsnorm_rows(const float* x, const float* gain, float eps, int m, int d, float* out, hipStream_t st);
@@ -128,6 +133,7 @@ struct GemmCall {
   const void* wp;     // re-tiled weights [N][K]
   int N, K, m;
   const void* actp;   // packed activations (ActPack with K columns)
+  int act_tiles;      // row tiles of this pass's ActPack buffers (input and output)
   const float* ssq_in;  // fused RMSNorm: [row][ssq_stride] partial sums of x^2 (ssq_parts used), or nullptr
   int ssq_parts, ssq_stride;
   float eps;
@@ -183,7 +189,9 @@ struct ActArena {
   __host__ __device__ float* sb(int l) const { return (float*)(base + off_sb + (size_t)l * s_bytes); }  // sums of squares of rb(l)
   __host__ __device__ float* partials(int l) const { return part + (size_t)l * part_stride; }
 };
-size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn);  // fills offsets; returns bytes
+// fills offsets; returns bytes.  per_layer = false: all layers share one buffer of each kind (enough
+// for the per-projection launches), with `act_tiles` row tiles of 16 rows.
+size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn, bool per_layer, int act_tiles);
 
 // ---- all decoder layers of a pass in one cooperative kernel (bf16, up to 16 rows) ----
 struct LayerSlabs {  // bf16 models: layer l of each tensor kind sits at base + l * bytes
@@ -216,6 +224,7 @@ struct AttnCall {
   float* part;     // per client [(head*m + r)*nsplit + split][head_dim + 4]
   float* out;      // fp32 cache: [m][n_q_heads*head_dim]
   void* outp;      // bf16 cache: packed output (ActPack with n_q_heads*head_dim columns)
+  int act_tiles;   // bf16 cache: row tiles of outp
   AttnBatch batch; // bf16 cache: the clients of the pass
 };
 int attn_nsplit(int total_tokens, int chunk);

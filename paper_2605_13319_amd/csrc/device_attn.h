@@ -201,7 +201,7 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
 // `row_off`: the client's first row in the pass (rows of the packed output).
 template <bool CO>
 __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int n_q_heads, int h, int nsplit,
-                                                  u32x4* outp, int gt, int row_off = 0) {
+                                                  u32x4* outp, int gt, int row_off = 0, int act_tiles = 2) {
   constexpr int BATCH = 9;
   const int segs = h / 8;
   const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
@@ -250,7 +250,7 @@ __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int 
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] /= L;
-  store_act8x<CO>(outp, row_off + r, head * h + e0, acc);
+  store_act8x<CO>(outp, row_off + r, head * h + e0, acc, act_tiles);
 }
 
 }  // namespace pipesd

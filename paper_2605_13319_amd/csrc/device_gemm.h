@@ -12,9 +12,9 @@
 //    in common.h): the producing epilogue splits each value once, every consuming wave just loads
 //    registers.  Two MFMAs per weight fragment keep 16 significand bits of the activations; the
 //    matrix cores idle otherwise.
-//  * A pass of 17..32 rows is spread over PAIRS of workgroups that walk the same tiles, one per 16
-//    rows, placed on the same chiplet: the weights cross the memory interface once and the second
-//    reader is served by the chiplet's L2.
+//  * A pass of more than 16 rows is spread over GROUPS of workgroups that walk the same tiles, one
+//    per 16 rows, placed on the same chiplet: the weights cross the memory interface once and the
+//    other readers are served by the chiplet's L2.
 //  * K is cut into W * P slices of KSTEPS*32 columns; a team of W waves takes slices p*W + w,
 //    p = 0..P-1, one phase after the other, for a group of tg n-tiles, each wave keeping its running
 //    16x16 sums in its own LDS slots; after the last phase the team adds them in a fixed order.
@@ -57,7 +57,8 @@ struct GemmArgs {
   const RowMap* rows;     // QKV: per-row position and block table (several clients in the pass), or nullptr
   KvView kv;
   int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
-  int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1 or 2)
+  int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1..8)
+  int act_tiles;          // row tiles of the pass's ActPack buffers
   float eps;
 };
 
@@ -132,7 +133,7 @@ struct Xwg {
 
 // split 8 consecutive columns k0..k0+7 (k0 % 8 == 0) of `row` into hi + lo and store them (ActPack)
 template <bool CO>
-__device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const float (&v)[8]) {
+__device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const float (&v)[8], int nt) {
   uint32_t h[4], l[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -143,8 +144,8 @@ __device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const f
     l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
   }
   const int g = (k0 & 31) >> 3, c = row & 15;
-  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 0, c, g), u32x4{h[0], h[1], h[2], h[3]});
-  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 1, c, g), u32x4{l[0], l[1], l[2], l[3]});
+  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 0, c, g, nt), u32x4{h[0], h[1], h[2], h[3]});
+  Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 1, c, g, nt), u32x4{l[0], l[1], l[2], l[3]});
 }
 
 // one chunk = KSTEPS weight fragments of one n-tile against this wave's activation fragments; while
@@ -207,7 +208,7 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
       const f32x4 hi4 = shfl4(y, lane + 16);  // columns +4..+7 of the 8-column group
       if (live && (gg & 1) == 0) {
         const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-        store_act8x<CO>(a.outp, row, t * 16 + gg * 4, y8);
+        store_act8x<CO>(a.outp, row, t * 16 + gg * 4, y8, a.act_tiles);
         if (gg == 0) Xwg<CO>::st1(a.ssq_out + (size_t)row * a.ssq_stride + t, sq);
       }
       break;
@@ -223,7 +224,7 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
       const f32x4 hi4 = shfl4(y, lane + 16);
       if (live && gg == 0) {
         const float y8[8] = {y[0], y[1], y[2], y[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-        store_act8x<CO>(a.outp, row, t * 8, y8);
+        store_act8x<CO>(a.outp, row, t * 8, y8, a.act_tiles);
       }
       break;
     }
@@ -287,8 +288,8 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
 // grid, `wt` is the wave's index in its team (waves with active == false belong to no team but must
 // still take part in the workgroup barriers), `tl` the team's index inside the workgroup (selects
 // its LDS area), `nwaves_wg` the workgroup's wave count.
-// `row_base` (0 or 16) selects which 16 rows of the pass this team multiplies when the rows of a
-// pass are spread over several workgroups (MT = 1 only).
+// `row_base` (a multiple of 16) selects which 16 rows of the pass this team multiplies when the rows
+// of a pass are spread over several workgroups (MT = 1 only).
 struct TeamPos {
   int team, nteams, wt, tl;
   bool active;
@@ -338,7 +339,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
         if (tp.row_base + mt * 16 + bc < a.m)
-          b[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt + (tp.row_base >> 4), hl, bc, bg));
+          b[mt][ks] = act_load(a.actp + act_index(slice * KSTEPS + ks, mt + (tp.row_base >> 4), hl, bc, bg, a.act_tiles));
   };
   auto await_act = [&]() {
 #pragma unroll

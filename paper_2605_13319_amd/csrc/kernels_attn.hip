@@ -105,10 +105,10 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 
 // grid = (threads of the largest client / 64, clients)
 __global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* part, int n_q_heads, int h, AttnBatch batch,
-                                                              uint4* outp) {
+                                                              uint4* outp, int act_tiles) {
   const AttnClient c = batch.c[blockIdx.y];
   attn_merge_thread<false>(part + c.part_off, c.m, n_q_heads, h, c.nsplit, (u32x4*)outp,
-                           blockIdx.x * blockDim.x + threadIdx.x, c.row_off);
+                           blockIdx.x * blockDim.x + threadIdx.x, c.row_off, act_tiles);
 }
 
 // merge the splits of one (row, head): o = sum_s e^{m_s - M} o_s / sum_s e^{m_s - M} l_s, splits taken
@@ -190,7 +190,7 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     for (int i = 0; i < c.batch.n; ++i) max_m = c.batch.c[i].m > max_m ? c.batch.c[i].m : max_m;
     const int threads = max_m * c.n_q_heads * (h / 8);
     attn_merge_packed_kernel<<<dim3((threads + 63) / 64, c.batch.n), 64, 0, st>>>(c.part, c.n_q_heads, h, c.batch,
-                                                                                   (uint4*)c.outp);
+                                                                                   (uint4*)c.outp, c.act_tiles);
   }
   return hipGetLastError();
 }

@@ -11,9 +11,9 @@ template <int KSTEPS, bool NT>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  // One team per workgroup: all W waves of the workgroup.  With two row tiles the workgroups b and
-  // b + 8 form a pair on the same tiles (one takes rows 0..15, the other rows 16..31): workgroups
-  // are dealt to the 8 chiplets round robin, so a pair shares an L2 and the weights cross the
+  // One team per workgroup: all W waves of the workgroup.  With rt row tiles the workgroups b,
+  // b + 8, .. b + 8 (rt - 1) form a group on the same tiles (16 rows of the pass each): workgroups
+  // are dealt to the 8 chiplets round robin, so a group shares an L2 and the weights cross the
   // memory interface once.
   const int b = (int)blockIdx.x, rt = a.row_tiles;
   TeamPos tp{(b / (8 * rt)) * 8 + (b & 7), (int)gridDim.x / rt, w, 0, true};
@@ -69,11 +69,11 @@ static void shape_for(int N, int K, int slots_cu, GemmPlan& p) {
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   const int n_cu = device_cu_count();
   if (n_cu <= 0) return hipErrorUnknown;
-  if (c.m < 1 || c.m > kMaxRows || c.K % 512 != 0) return hipErrorInvalidValue;
-  const int row_tiles = c.m <= 16 ? 1 : 2;
+  if (c.m < 1 || c.m > kMaxPassRows || c.K % 512 != 0 || c.act_tiles * 16 < c.m) return hipErrorInvalidValue;
+  const int row_tiles = (c.m + 15) / 16;
   GemmPlan p;
   shape_for(c.N, c.K, n_cu / row_tiles, p);
-  if (row_tiles > 1) p.grid = (p.grid + 7) / 8 * 8 * row_tiles;  // pairs are b and b + 8: whole rounds of the 8 chiplets
+  if (row_tiles > 1) p.grid = (p.grid + 7) / 8 * 8 * row_tiles;  // groups are b, b + 8, ..: whole rounds of the 8 chiplets
   GemmArgs a{};
   a.wp = (const u32x4*)c.wp;
   a.actp = (const u32x4*)c.actp;
@@ -103,6 +103,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.n_q_heads = c.n_q_heads;
   a.eps = c.eps;
   a.row_tiles = row_tiles;
+  a.act_tiles = c.act_tiles;
   const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);
   const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;
   if (row_tiles == 1) {

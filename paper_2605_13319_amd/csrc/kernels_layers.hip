@@ -181,11 +181,11 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
 // ------------------------------------------------------------------------------------------------
 int device_cu_count();
 
-size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn) {
-  const size_t L = (size_t)n_layers, R = kMaxRows;
-  a.x_bytes = act_pack_bytes(d_model);
-  a.ap_bytes = act_pack_bytes(q_dim);
-  a.gp_bytes = act_pack_bytes(d_ffn);
+size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d_ffn, bool per_layer, int act_tiles) {
+  const size_t L = per_layer ? (size_t)n_layers : 0, R = (size_t)act_tiles * 16;
+  a.x_bytes = act_pack_bytes(d_model, act_tiles);
+  a.ap_bytes = act_pack_bytes(q_dim, act_tiles);
+  a.gp_bytes = act_pack_bytes(d_ffn, act_tiles);
   a.r_bytes = R * d_model * sizeof(float);
   a.q_bytes = R * q_dim * sizeof(float);
   a.ssq_stride = d_model / 16;
@@ -200,6 +200,19 @@ size_t act_arena_layout(ActArena& a, int n_layers, int d_model, int q_dim, int d
   a.off_q = off; off += L * a.q_bytes;
   a.off_sa = off; off += (L + 1) * a.s_bytes;
   a.off_sb = off; off += L * a.s_bytes;
+  if (!per_layer) {  // one buffer of each kind: every layer's accessor lands on it
+    off = 0;
+    a.off_xa = off; off += a.x_bytes;
+    a.off_xb = off; off += a.x_bytes;
+    a.off_ap = off; off += a.ap_bytes;
+    a.off_gp = off; off += a.gp_bytes;
+    a.off_ra = off; off += a.r_bytes;
+    a.off_rb = off; off += a.r_bytes;
+    a.off_q = off; off += a.q_bytes;
+    a.off_sa = off; off += a.s_bytes;
+    a.off_sb = off; off += a.s_bytes;
+    a.x_bytes = a.ap_bytes = a.gp_bytes = a.r_bytes = a.q_bytes = a.s_bytes = 0;
+  }
   return off;
 }
 
@@ -255,6 +268,7 @@ hipError_t launch_layers(const LayersCall& c, hipStream_t st) {
   const int nqkv = c.q_dim + 2 * c.kv.n_kv_heads * c.head_dim;
   GemmArgs base{};
   base.row_tiles = 1;
+  base.act_tiles = 2;
   base.m = c.m;
   base.eps = c.eps;
   base.ssq_stride = c.arena.ssq_stride;

@@ -8,14 +8,15 @@ namespace pipesd {
 // evaluated in fp64 and rounded once (rotary positions; the target forward of Sec. 2.2).
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, RowMap map, int m, int d, int half,
+__global__ void setup_rows_kernel(const T* __restrict__ emb, PassTokens toks, RowMap map, int m, int d, int half,
                                   const double* __restrict__ theta, float* __restrict__ xres,
                                   float* __restrict__ rope_cs, const float* __restrict__ gain, uint4* xpk,
-                                  float* __restrict__ ssq_out, int ssq_stride, RowMap* __restrict__ map_dev) {
+                                  int act_tiles, float* __restrict__ ssq_out, int ssq_stride,
+                                  RowMap* __restrict__ map_dev) {
   __shared__ float red[4];
   const int r = blockIdx.x;
   if (r >= m) return;
-  if (map_dev != nullptr && r == 0 && threadIdx.x < kMaxRows) {
+  if (map_dev != nullptr && r == 0 && threadIdx.x < kMaxPassRows) {
     map_dev->pos[threadIdx.x] = map.pos[threadIdx.x];
     map_dev->table_off[threadIdx.x] = map.table_off[threadIdx.x];
   }
@@ -32,7 +33,7 @@ __global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, Row
     if (xpk != nullptr) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) y[i] = v[i] * gain[j * 8 + i];
-      store_act8(xpk, r, j * 8, y);
+      store_act8(xpk, r, j * 8, y, act_tiles);
     }
   }
   for (int i = (d / 8) * 8 + threadIdx.x; i < d; i += blockDim.x) xres[(size_t)r * d + i] = load_elem(emb, base + i);
@@ -50,16 +51,17 @@ __global__ void setup_rows_kernel(const T* __restrict__ emb, RowTokens toks, Row
   }
 }
 
-hipError_t launch_setup_rows(int dtype, const void* tok_emb, const RowTokens& toks, const RowMap& map, int m,
+hipError_t launch_setup_rows(int dtype, const void* tok_emb, const PassTokens& toks, const RowMap& map, int m,
                              int d_model, int head_dim, const double* theta, float* xres, float* rope_cs,
-                             const float* gain, void* xpk, float* ssq_out, int ssq_stride, RowMap* map_dev,
-                             hipStream_t st) {
+                             const float* gain, void* xpk, int act_tiles, float* ssq_out, int ssq_stride,
+                             RowMap* map_dev, hipStream_t st) {
   if (dtype == PIPESD_F32)
     setup_rows_kernel<float><<<m, 256, 0, st>>>((const float*)tok_emb, toks, map, m, d_model, head_dim / 2, theta, xres,
-                                                rope_cs, nullptr, nullptr, nullptr, 0, map_dev);
+                                                rope_cs, nullptr, nullptr, 0, nullptr, 0, map_dev);
   else
     setup_rows_kernel<uint16_t><<<m, 256, 0, st>>>((const uint16_t*)tok_emb, toks, map, m, d_model, head_dim / 2, theta,
-                                                   xres, rope_cs, gain, (uint4*)xpk, ssq_out, ssq_stride, map_dev);
+                                                   xres, rope_cs, gain, (uint4*)xpk, act_tiles, ssq_out, ssq_stride,
+                                                   map_dev);
   return hipGetLastError();
 }
 

@@ -21,29 +21,30 @@ def nav():
     return n
 
 
-@pytest.mark.parametrize("shape_name", ["tiny", "small-bf16"])
-def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name):
+@pytest.mark.parametrize("shape_name,n_seq,rounds", [("tiny", 5, 4), ("small-bf16", 5, 4), ("small-bf16", 16, 12)])
+def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds):
+    """bf16: the clients' rows share passes of up to 128 rows (16 clients with k ~ U[1,16] need two);
+    a row's results must not depend on what else is in its pass."""
     shape = I.WORKLOADS["tiny"]["shape"] if shape_name == "tiny" else SMALL_BF16
     w = I.make_weights(shape, 9001)
     model = nav.Model(shape, w)
-    n_seq = 5
     rng = np.random.default_rng(9002)
     lens = [int(x) for x in rng.integers(17, 150, n_seq)]
-    kv_b = nav.KVCache(model, max_seqs=n_seq, n_blocks=80)
-    kv_s = nav.KVCache(model, max_seqs=n_seq, n_blocks=80)
+    kv_b = nav.KVCache(model, max_seqs=n_seq, n_blocks=30 * n_seq)
+    kv_s = nav.KVCache(model, max_seqs=n_seq, n_blocks=30 * n_seq)
     for s, n in enumerate(lens):
         toks = I.make_tokens(n, shape.vocab, 9100 + s)
         kv_b.prefill(s, toks)
         kv_s.prefill(s, toks)
-    for rnd in range(4):
+    for rnd in range(rounds):
         ks = [int(x) for x in rng.integers(1, 17, n_seq)]
         drafts, probs, us = [], [], []
         for s in range(n_seq):
-            d, q = I.make_independent_drafts(ks[s], shape.vocab, 9200 + 10 * rnd + s, 9300 + 10 * rnd + s, scale=1.0)
+            d, q = I.make_independent_drafts(ks[s], shape.vocab, 9200 + 100 * rnd + s, 9300 + 100 * rnd + s, scale=1.0)
             drafts.append([int(t) for t in d])
             greedy = (s == 2)  # one client uses token matching
             probs.append(None if greedy else q)
-            us.append(None if greedy else I.make_uniforms(ks[s] + 1, 9400 + 10 * rnd + s))
+            us.append(None if greedy else I.make_uniforms(ks[s] + 1, 9400 + 100 * rnd + s))
         order = [int(x) for x in rng.permutation(n_seq)]  # clients in any order
         a_b, n_b = kv_b.nav_verify_batch(order, [drafts[s] for s in order], [probs[s] for s in order],
                                          [us[s] for s in order])
