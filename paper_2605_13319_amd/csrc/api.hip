@@ -615,7 +615,7 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
     r0 += pc.rows;
   }
   // per-layer partial buffers only where the all-layers kernel may run (one client); otherwise one, reused
-  const bool part_per_layer = bf && single;
+  const bool part_per_layer = bf && single && rows <= 16;
   int rc = ensure_attn_scratch(m, part_floats * (part_per_layer ? c.n_layers : 1));
   if (rc) return rc;
   ActArena& ar = rows <= 2 * 16 ? m->arena : m->arena_big;
@@ -803,8 +803,9 @@ extern "C" int pipesd_prefill(pipesd_model* model, pipesd_kv* kv, int32_t seq, c
   const int32_t cached_before = start;
   int rc = ensure_blocks(kv, seq, start + (int32_t)rows.size(), st);
   if (rc) return rc;
-  for (size_t i = 0; i < rows.size(); i += kMaxRows) {
-    const int nr = (int)((rows.size() - i < (size_t)kMaxRows) ? rows.size() - i : kMaxRows);
+  const size_t block = model->cfg.dtype == PIPESD_BF16 ? kMaxPassRows : kMaxRows;  // rows per pass
+  for (size_t i = 0; i < rows.size(); i += block) {
+    const int nr = (int)((rows.size() - i < block) ? rows.size() - i : block);
     rc = run_rows(model, kv, seq, rows.data() + i, nr, start + (int)i, false, st);
     if (rc) {
       release_beyond(kv, s, cached_before);
