@@ -190,6 +190,14 @@ int pipesd_kv_read(const pipesd_model *model, const pipesd_kv *kv, int32_t seq, 
 int pipesd_model_set_fused(pipesd_model *model, int32_t on);
 int pipesd_model_fused_launches(const pipesd_model *model, int64_t *n);
 
+/* GEMM kernel of bf16 passes of more than 64 rows (batched verification, prompt ingestion).  Two
+ * kernels compute them: the narrow one of the single-client pass, run by groups of workgroups that
+ * share the weights through a chiplet's L2, and a wide one that stages the activations of all rows
+ * in LDS.  mode 0 (default): per product, whichever was measured faster for its shape; 1: always the
+ * narrow kernel; 2: always the wide one.  Both accumulate every output in the same order and give
+ * bit-identical results, so the mode changes speed only.  PIPESD_EINVAL for another mode. */
+int pipesd_model_set_wide_gemm(pipesd_model *model, int32_t mode);
+
 /* Per-kernel timing for roofline accounting: when enabled, every launch of the selected kernel
  * class is timed with HIP events on its stream (the bf16 GEMM launches carry their own start and
  * stop events, the other classes are bracketed by recorded events).  pipesd_profile_read waits for them and returns

@@ -10,10 +10,6 @@
 
 using namespace pipesd;
 
-namespace pipesd {
-int device_cu_count();
-}
-
 // text of the most recent failing HIP call of this thread, for pipesd_last_hip_error()
 static thread_local char g_hip_msg[256] = "";
 static int hip_fail(hipError_t e, const char* what) {
@@ -52,6 +48,9 @@ struct pipesd_model {
   ActArena arena{};  // bf16 path: per-layer activation buffers (passes of up to 32 rows)
   int pass_act_tiles = 2;  // row tiles of the buffers of the pass being enqueued
   ActArena arena_big{};  // bf16 path: one buffer of each kind, 8 row tiles (passes of several clients, up to 128 rows)
+  int wide_mode = 0;        // GEMM kernel of passes of more than 64 rows: 0 by shape, 1 narrow, 2 wide
+  void* wide_ws = nullptr;  // bf16 path: running sums of the K-split workgroups of passes of more than 64 rows
+  size_t wide_ws_bytes = 0;
   RowMap* rowmap_dev = nullptr;  // bf16 path: per-row placement of a pass that holds several clients
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
@@ -246,6 +245,9 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     const size_t big_bytes = act_arena_layout(m->arena_big, L, d, qd, F, false, kMaxPassRows / 16);
     if ((rc = dev_alloc(m, (void**)&m->arena_big.base, big_bytes))) return rc;
     HIP_TRY(hipMemset(m->arena_big.base, 0, big_bytes));
+    const int gemm_nk[5][2] = {{(int)nqkv, (int)d}, {(int)d, (int)qd}, {2 * (int)F, (int)d}, {(int)d, (int)F}, {(int)V, (int)d}};
+    for (const auto& nk : gemm_nk) m->wide_ws_bytes = std::max(m->wide_ws_bytes, gemm_wide_workspace_bytes(nk[0], nk[1]));  // (sized as if every product ran wide)
+    if (m->wide_ws_bytes && (rc = dev_alloc(m, &m->wide_ws, m->wide_ws_bytes))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->rowmap_dev, sizeof(RowMap)))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
@@ -398,6 +400,12 @@ extern "C" const char* pipesd_strerror(int status) {
 // ---------------------------------------------------------------------------------------------
 // kernel timing
 // ---------------------------------------------------------------------------------------------
+extern "C" int pipesd_model_set_wide_gemm(pipesd_model* model, int32_t mode) {
+  if (!model || mode < 0 || mode > 2) return PIPESD_EINVAL;
+  model->wide_mode = mode;
+  return PIPESD_OK;
+}
+
 extern "C" int pipesd_model_set_fused(pipesd_model* model, int32_t on) {
   if (!model) return PIPESD_EINVAL;
   model->fused_enabled = on != 0;
@@ -561,11 +569,14 @@ static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int row
   c.eps = m->cfg.rms_eps;
   c.epi = epi;
   c.rope_cs = m->rope_cs;
+  c.wide_ws = m->wide_ws;
+  c.wide_ws_bytes = m->wide_ws_bytes;
+  c.wide_mode = m->wide_mode;
   return c;
 }
 
 // The rows of one pass: one client's k + 1 rows, or (bf16) the rows of up to 16 clients one after
-// the other, at most 32 in all.
+// the other, at most 128 in all.
 struct PassClient {
   int32_t seq, rows, start_pos;
 };

@@ -17,10 +17,18 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest even (finite inputs)
-  return (uint16_t)(u >> 16);
+// float -> bf16, round to nearest even: the hardware conversion (checked on MI355X against
+// add-0x7FFF-plus-lsb-and-shift on every finite float: identical)
+typedef __attribute__((ext_vector_type(2))) float cvt_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 cvt_bf16x2;
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {  // a in the low half
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((cvt_f32x2){a, b}, cvt_bf16x2));
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) { return (uint16_t)pack2_bf16(f, 0.f); }
+// (a, b) = hi + lo with hi = bf16(x), lo = bf16(x - hi): 16 significand bits of x
+__device__ __forceinline__ void split2_bf16(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = pack2_bf16(a, b);
+  lo = pack2_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
 }
 __device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_bits_to_f32(p[i]); }
@@ -67,13 +75,16 @@ __device__ __forceinline__ int64_t v_index(const KvView& kv, int layer, int pos,
 
 // ActPack: activations handed from one kernel to the next GEMM, already in the B-operand layout of
 // the 16x16x32 bf16 MFMA and split into a bf16 hi + lo pair.  For a consumer with K columns the
-// buffer is uint4[K/32][nt row tiles][hi, lo][16 rows][4 column groups] (nt = 2 for passes of up to
-// 32 rows, 8 for the largest passes of several clients): entry (c, g) of k-step ks
-// holds columns ks*32 + g*8 .. +7 of row (row tile)*16 + c and is what MFMA lane g*16 + c consumes.
-// A row's 64 bytes are contiguous, so a pass with m < 16 rows touches only the first m*64 bytes of
-// each 1 KB fragment.
+// buffer is uint4[K/32][nt row tiles][hi, lo][64 entries] (nt = 2 for passes of up to 32 rows, 8 for
+// the largest passes of several clients): entry (c, g) of k-step ks holds columns ks*32 + g*8 .. +7
+// of row (row tile)*16 + c and is what MFMA lane g*16 + c consumes.  Within a 1 KB fragment:
+//  * nt = 2: entry c*4 + g.  A row's 64 bytes are contiguous, so a pass with m < 16 rows (the usual
+//    single-client pass) touches only the first m*64 bytes of each fragment;
+//  * nt = 8: entry g*16 + c, the consumer's lane order: full tiles are read with lane l taking
+//    entry l (fully coalesced, and a straight copy into LDS for the wide GEMM), and the 16 lanes of
+//    an epilogue that hold the same columns of 16 rows store 256 contiguous bytes.
 __device__ __forceinline__ size_t act_index(int kstep, int mt, int hl, int c, int g, int nt) {
-  return (((size_t)kstep * nt + mt) * 2 + hl) * 64 + c * 4 + g;
+  return (((size_t)kstep * nt + mt) * 2 + hl) * 64 + (nt == 2 ? c * 4 + g : g * 16 + c);
 }
 inline size_t act_pack_bytes(int K, int nt) { return (size_t)(K / 32) * nt * 2 * 64 * 16; }
 
@@ -81,13 +92,7 @@ inline size_t act_pack_bytes(int K, int nt) { return (size_t)(K / 32) * nt * 2 *
 __device__ __forceinline__ void store_act8(uint4* buf, int row, int k0, const float (&v)[8], int nt) {
   uint32_t h[4], l[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
-    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
-    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
-    h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-    l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-  }
+  for (int i = 0; i < 4; ++i) split2_bf16(v[2 * i], v[2 * i + 1], h[i], l[i]);
   const int g = (k0 & 31) >> 3, c = row & 15;
   buf[act_index(k0 >> 5, row >> 4, 0, c, g, nt)] = make_uint4(h[0], h[1], h[2], h[3]);
   buf[act_index(k0 >> 5, row >> 4, 1, c, g, nt)] = make_uint4(l[0], l[1], l[2], l[3]);
@@ -149,10 +154,19 @@ struct GemmCall {
   int layer, start_pos, n_q_heads;
   const float* rope_cs;
   const RowMap* rows;  // device; nullptr: one client, row r at position start_pos + r, table kv.table
+  // passes of more than 64 rows: workspace for the running sums of K-split workgroups
+  // (gemm_wide_workspace_bytes; may be null when that is 0)
+  void* wide_ws = nullptr;
+  size_t wide_ws_bytes = 0;
+  int wide_mode = 0;  // 0: kernel chosen by shape, 1: narrow kernel, 2: wide kernel
   // optional: events that take the kernel's own start and end (no marker packets around it)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st);
+int device_cu_count();
+// bytes of GemmCall::wide_ws a product with N weight rows and K columns needs on this device when
+// it runs on the wide kernel (0 when that needs no workspace)
+size_t gemm_wide_workspace_bytes(int N, int K);
 
 // re-tile [rows][K] bf16 row-major (up to 3 stacked sources) into 16-row x 32-column matrix-core
 // fragments; PACK_HALVES makes tile rows 8..15 the partners (second source half / second half of
@@ -184,7 +198,7 @@ struct ActArena {
   __host__ __device__ void* gp(int l) const { return base + off_gp + (size_t)l * gp_bytes; }  // packed silu(gate)*up
   __host__ __device__ float* ra(int l) const { return (float*)(base + off_ra + (size_t)l * r_bytes); }  // residual entering layer l
   __host__ __device__ float* rb(int l) const { return (float*)(base + off_rb + (size_t)l * r_bytes); }  // residual after attention
-  __host__ __device__ float* q(int l) const { return (float*)(base + off_q + (size_t)l * q_bytes); }    // rotated queries
+  __host__ __device__ float* q(int l) const { return (float*)(base + off_q + (size_t)l * q_bytes); }    // rotated queries, bf16 hi | lo halves per row
   __host__ __device__ float* sa(int l) const { return (float*)(base + off_sa + (size_t)l * s_bytes); }  // sums of squares of ra(l)
   __host__ __device__ float* sb(int l) const { return (float*)(base + off_sb + (size_t)l * s_bytes); }  // sums of squares of rb(l)
   __host__ __device__ float* partials(int l) const { return part + (size_t)l * part_stride; }
@@ -217,7 +231,7 @@ constexpr int kLayersErrWord = 32 * 9;
 // ---- attention over the paged cache (both dtypes) ----
 struct AttnCall {
   int dtype;
-  const float* q;  // [rows][n_q_heads*head_dim]
+  const float* q;  // fp32 cache: [rows][n_q_heads*head_dim]; bf16 cache: the same bytes per row holding bf16 hi halves, then lo halves
   KvView kv;
   int layer, m, start_pos, n_q_heads;  // fp32 cache: the one client's rows and first position
   int chunk;       // fp32 cache: tokens per workgroup

@@ -26,29 +26,28 @@ typedef __attribute__((ext_vector_type(2))) unsigned au32x2;
 __device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf16x8& lo) {
   unsigned h[4], l[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
-    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
-    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
-    h[i] = (unsigned)h0 | ((unsigned)h1 << 16);
-    l[i] = (unsigned)l0 | ((unsigned)l1 << 16);
-  }
+  for (int i = 0; i < 4; ++i) split2_bf16(v[2 * i], v[2 * i + 1], h[i], l[i]);
   hi = __builtin_bit_cast(bf16x8, au32x4{h[0], h[1], h[2], h[3]});
   lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
 }
 
 constexpr size_t attn_lds_floats(int hd) { return (size_t)kAttnWaves * 16 * (hd + 4) + 2 * kAttnWaves * 16; }
 
-// Task (kv_head, split, query tile) = 8 waves x 32 tokens against 16 of the query rows that share
-// the KV head (row rr of the head group is head kvh*group + rr/m, pass row rr%m).  Everything the
-// task needs is requested up front (its keys, values and queries), each wave computes its 32
-// tokens' (max, sum, O), and after ONE workgroup barrier the eight results are merged by all 512
-// threads, waves in index order, and written as the split's partial.  All 8 waves of the workgroup
-// must call this together; the caller separates two calls on the same LDS by a barrier.
-template <int HD, bool CO>
+// Task (kv_head, split, query tiles qt0..qt1-1) = 8 waves x 32 tokens against the query rows that
+// share the KV head, 16 at a time (row rr of the head group is head kvh*group + rr/m, pass row
+// rr%m).  Everything the task needs is requested up front (its keys, values and the first tile's
+// queries; the next tile's queries while the current one is worked on); per tile each wave computes
+// its 32 tokens' (max, sum, O), and after ONE workgroup barrier the eight results are merged by all
+// 512 threads, waves in index order, and written as the split's partial.  A launch with few tasks
+// gives every tile its own workgroup (shortest path); one with many lets a workgroup keep its keys
+// and values in registers for all tiles.  The partials do not depend on that choice.  All 8 waves of
+// the workgroup must call this together; the caller separates two calls on the same LDS by a barrier.
+// MULTI = false: exactly one tile (qt1 is taken as qt0 + 1; fewer registers).
+template <int HD, bool CO, bool MULTI = false>
 __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int layer, int m, int start_pos,
-                                          int n_q_heads, int nsplit, float* part, int kvh, int split, int qt,
+                                          int n_q_heads, int nsplit, float* part, int kvh, int split, int qt0, int qt1,
                                           float* lds) {
+  if constexpr (!MULTI) qt1 = qt0 + 1;
   constexpr int KSQ = HD / 32, HT = HD / 16, ROW = HD + 4;
   float(*o_lds)[16][ROW] = (float(*)[16][ROW])lds;
   float(*m_lds)[16] = (float(*)[16])(lds + (size_t)kAttnWaves * 16 * ROW);
@@ -79,17 +78,21 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
       if (tt == 0) vlo[j] = v; else vhi[j] = v;
     }
   }
-  const int rr = qt * 16 + c;
-  const bool row_ok = rr < R;
-  const int gq = row_ok ? rr / m : 0, r = row_ok ? rr % m : 0;
-  const int head = kvh * group + gq;
-  au32x4 qa[KSQ], qb[KSQ];
+  // queries arrive as bf16 hi + lo halves (written by the QKV epilogue): row = [n_q_heads*HD hi][.. lo]
+  au32x4 qa[KSQ], qb[KSQ];  // hi, lo
+  const uint16_t* q16 = (const uint16_t*)q;
+  const int qd = n_q_heads * HD;
+  auto q_request = [&](int qt) {  // rows beyond the head group read row 0 of the group (and are masked)
+    const int rr = qt * 16 + c;
+    const int gq = rr < R ? rr / m : 0, r = rr < R ? rr % m : 0;
 #pragma unroll
-  for (int s = 0; s < KSQ; ++s) {
-    const float* qp = q + ((size_t)r * n_q_heads + head) * HD + s * 32 + g * 8;
-    qa[s] = *(const au32x4*)qp;
-    qb[s] = *(const au32x4*)(qp + 4);
-  }
+    for (int s = 0; s < KSQ; ++s) {
+      const uint16_t* qp = q16 + (size_t)r * 2 * qd + (kvh * group + gq) * HD + s * 32 + g * 8;
+      qa[s] = *(const au32x4*)qp;
+      qb[s] = *(const au32x4*)(qp + qd);
+    }
+  };
+  q_request(qt0);
 
   // ---- operands: tokens at or beyond `total` read as zero ----
   bf16x8 kf[2][KSQ], vf[HT];
@@ -110,18 +113,15 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
       vf[j] = __builtin_bit_cast(bf16x8, au32x4{vlo[j].x & (unsigned)keep[0], vlo[j].y & (unsigned)(keep[0] >> 32),
                                                 vhi[j].x & (unsigned)keep[1], vhi[j].y & (unsigned)(keep[1] >> 32)});
   }
+  for (int qt = qt0; qt < qt1; ++qt) {
+  const int rr = qt * 16 + c;
+  const bool row_ok = rr < R;
+  const int r = row_ok ? rr % m : 0;
   bf16x8 qhi[KSQ], qlo[KSQ];
 #pragma unroll
   for (int s = 0; s < KSQ; ++s) {
-    // (whole-vector casts: a bit cast of one vector element reads element 0 with this compiler)
-    const f32x4 fa = __builtin_bit_cast(f32x4, qa[s]), fb = __builtin_bit_cast(f32x4, qb[s]);
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[i] = row_ok ? fa[i] : 0.f;
-      v[i + 4] = row_ok ? fb[i] : 0.f;
-    }
-    split_hi_lo8(v, qhi[s], qlo[s]);
+    qhi[s] = __builtin_bit_cast(bf16x8, row_ok ? qa[s] : au32x4{0u, 0u, 0u, 0u});
+    qlo[s] = __builtin_bit_cast(bf16x8, row_ok ? qb[s] : au32x4{0u, 0u, 0u, 0u});
   }
 
   // ---- scores of query row c against tokens tok0 + tt*16 + g*4 + i ----
@@ -168,6 +168,7 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
     l_lds[w][c] = l_run;
   }
   __syncthreads();
+  if (qt + 1 < qt1) q_request(qt + 1);  // travels during the merge
 
   // ---- merge of the eight waves: thread -> (query row, 4 consecutive elements), waves in index order ----
   constexpr int TPR = HD / 4;  // threads per row: all 512 threads for h = 128, the first 256 for h = 64
@@ -192,6 +193,8 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
       Xwg<CO>::st4f(dst + e0, o);
       if (e0 == 0) Xwg<CO>::st4f(dst + HD, f32x4{M, L, 0.f, 0.f});
     }
+  }
+  if (qt + 1 < qt1) __syncthreads();  // the merge has read the LDS the next tile writes
   }
 }
 

@@ -48,7 +48,7 @@ struct GemmArgs {
   const u32x4* actp;      // packed activations (ActPack, K columns)
   const float* ssq_in;    // fused norm: [row][ssq_stride] partial sums of x^2, or nullptr
   int ssq_parts, ssq_stride;
-  float* out;             // STORE: logits; RESID: new residual stream; QKV: query buffer
+  float* out;             // STORE: logits; RESID: new residual stream; QKV: query buffer (bf16 hi | lo halves per row)
   const float* res_in;    // RESID: residual stream the product is added to (may be `out`)
   u32x4* outp;            // RESID / SWIGLU: packed output for the next GEMM
   const float* gain_next; // RESID: gain applied to the packed copy
@@ -61,6 +61,12 @@ struct GemmArgs {
   int act_tiles;          // row tiles of the pass's ActPack buffers
   float eps;
 };
+
+// passes of at least this many row tiles take the wide kernel (kernels_gemm_wide.hip); `a` comes
+// filled in by launch_gemm_bf16
+constexpr int kWideMinRowTiles = 5;
+hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st);
+bool gemm_wide_preferred(int N, int K);
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -136,13 +142,7 @@ template <bool CO>
 __device__ __forceinline__ void store_act8x(u32x4* buf, int row, int k0, const float (&v)[8], int nt) {
   uint32_t h[4], l[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint16_t h0 = f32_to_bf16_bits(v[2 * i]), h1 = f32_to_bf16_bits(v[2 * i + 1]);
-    const uint16_t l0 = f32_to_bf16_bits(v[2 * i] - bf16_bits_to_f32(h0));
-    const uint16_t l1 = f32_to_bf16_bits(v[2 * i + 1] - bf16_bits_to_f32(h1));
-    h[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-    l[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-  }
+  for (int i = 0; i < 4; ++i) split2_bf16(v[2 * i], v[2 * i + 1], h[i], l[i]);
   const int g = (k0 & 31) >> 3, c = row & 15;
   Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 0, c, g, nt), u32x4{h[0], h[1], h[2], h[3]});
   Xwg<CO>::st4(buf + act_index(k0 >> 5, row >> 4, 1, c, g, nt), u32x4{l[0], l[1], l[2], l[3]});
@@ -247,9 +247,20 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
         r1 = x1 * rstd;
       }
       if (hd < a.n_q_heads) {
-        float* o = a.out + (size_t)row * a.ldo + hd * h + i0;
-        Xwg<CO>::st4f(o, r0);
-        Xwg<CO>::st4f(o + half, r1);
+        // queries go to attention as the bf16 hi + lo pair its matrix-core operands are made of:
+        // row = [ldo hi halves][ldo lo halves] (the bytes of ldo floats)
+        uint16_t* o = (uint16_t*)(a.out + (size_t)row * a.ldo) + hd * h + i0;
+        unsigned hh[2][2], ll[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const f32x4& rv = i == 0 ? r0 : r1;
+          split2_bf16(rv[0], rv[1], hh[i][0], ll[i][0]);
+          split2_bf16(rv[2], rv[3], hh[i][1], ll[i][1]);
+        }
+        Xwg<CO>::st2(o, u32x2{hh[0][0], hh[0][1]});
+        Xwg<CO>::st2(o + half, u32x2{hh[1][0], hh[1][1]});
+        Xwg<CO>::st2(o + a.ldo, u32x2{ll[0][0], ll[0][1]});
+        Xwg<CO>::st2(o + a.ldo + half, u32x2{ll[1][0], ll[1][1]});
       } else {
         uint16_t* pool = (uint16_t*)a.kv.pool;
         KvView kvr = a.kv;  // the row's own client
@@ -258,19 +269,15 @@ __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row,
           pos = a.rows->pos[row];
           kvr.table += a.rows->table_off[row];
         }
-        uint16_t b0[4], b1[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          b0[i] = f32_to_bf16_bits(r0[i]);
-          b1[i] = f32_to_bf16_bits(r1[i]);
-        }
+        const unsigned p0[2] = {pack2_bf16(r0[0], r0[1]), pack2_bf16(r0[2], r0[3])};
+        const unsigned p1[2] = {pack2_bf16(r1[0], r1[1]), pack2_bf16(r1[2], r1[3])};
         if (hd < a.n_q_heads + a.kv.n_kv_heads) {
           const int kvh = hd - a.n_q_heads;
-          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0),
-                       u32x2{(unsigned)b0[0] | ((unsigned)b0[1] << 16), (unsigned)b0[2] | ((unsigned)b0[3] << 16)});
-          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0 + half),
-                       u32x2{(unsigned)b1[0] | ((unsigned)b1[1] << 16), (unsigned)b1[2] | ((unsigned)b1[3] << 16)});
+          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0), u32x2{p0[0], p0[1]});
+          Xwg<CO>::st2(pool + k_index(kvr, a.layer, pos, kvh, i0 + half), u32x2{p1[0], p1[1]});
         } else {
+          const uint16_t b0[4] = {(uint16_t)p0[0], (uint16_t)(p0[0] >> 16), (uint16_t)p0[1], (uint16_t)(p0[1] >> 16)};
+          const uint16_t b1[4] = {(uint16_t)p1[0], (uint16_t)(p1[0] >> 16), (uint16_t)p1[1], (uint16_t)(p1[1] >> 16)};
           const int kvh = hd - a.n_q_heads - a.kv.n_kv_heads;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {

@@ -90,17 +90,21 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
 // ------------------------------------------------------------------------------------------------
 // bf16 cache: the same computation on the matrix cores (device code in device_attn.h)
 // ------------------------------------------------------------------------------------------------
-template <int HD>
-// grid = (kv heads x clients of the pass, splits of the longest client, query tiles of the largest client)
+// grid = (kv heads, splits of all clients of the pass one client after the other, query tiles of the
+// largest client / qpw); a workgroup takes qpw query tiles (MULTI) or one
+template <int HD, bool MULTI>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float* q, KvView kv, int layer, int n_q_heads,
-                                                                    AttnBatch batch, float* part) {
+                                                                    AttnBatch batch, float* part, int qpw) {
   extern __shared__ float lds[];
-  const int ci = blockIdx.x / kv.n_kv_heads, kvh = blockIdx.x % kv.n_kv_heads;
+  const int kvh = blockIdx.x;
+  int ci = 0, split = blockIdx.y;
+  while (ci + 1 < batch.n && split >= batch.c[ci].nsplit) split -= batch.c[ci++].nsplit;
   const AttnClient c = batch.c[ci];
-  if ((int)blockIdx.y >= c.nsplit || (int)blockIdx.z * 16 >= n_q_heads / kv.n_kv_heads * c.m) return;  // whole workgroup
+  const int nqt = (n_q_heads / kv.n_kv_heads * c.m + 15) / 16, qt0 = (int)blockIdx.z * qpw;
+  if (split >= c.nsplit || qt0 >= nqt) return;  // whole workgroup
   kv.table += c.table_off;
-  attn_task<HD, false>(q + (size_t)c.row_off * n_q_heads * HD, kv, layer, c.m, c.start_pos, n_q_heads, c.nsplit,
-                       part + c.part_off, kvh, blockIdx.y, blockIdx.z, lds);
+  attn_task<HD, false, MULTI>(q + (size_t)c.row_off * n_q_heads * HD, kv, layer, c.m, c.start_pos, n_q_heads,
+                              c.nsplit, part + c.part_off, kvh, split, qt0, min(nqt, qt0 + qpw), lds);
 }
 
 // grid = (threads of the largest client / 64, clients)
@@ -157,28 +161,40 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     const AttnBatch& b = c.batch;
     if (b.n < 1 || b.n > kMaxPassClients) return hipErrorInvalidValue;
     const int group = c.n_q_heads / c.kv.n_kv_heads;
-    int max_split = 1, max_m = 1;
+    int splits = 0, max_m = 1;
+    long tasks = 0;  // (kv head, split, query tile) over all clients
     for (int i = 0; i < b.n; ++i) {
-      max_split = b.c[i].nsplit > max_split ? b.c[i].nsplit : max_split;
+      splits += b.c[i].nsplit;
       max_m = b.c[i].m > max_m ? b.c[i].m : max_m;
+      tasks += (long)c.kv.n_kv_heads * b.c[i].nsplit * ((group * b.c[i].m + 15) / 16);
     }
-    dim3 grid(c.kv.n_kv_heads * b.n, max_split, (group * max_m + 15) / 16);
+    // more tasks than the device holds at once (two workgroups per compute unit): one workgroup per
+    // (kv head, split) walks all query tiles with its keys and values in registers
+    const int max_qt = (group * max_m + 15) / 16;
+    const int qpw = tasks > 4L * device_cu_count() ? max_qt : 1;
+    dim3 grid(c.kv.n_kv_heads, splits, (max_qt + qpw - 1) / qpw);
     if (h != 128 && h != 64) return hipErrorInvalidValue;
     const size_t lds = attn_lds_floats(h) * sizeof(float);
     static bool lds_allowed = false;  // more than 64 KB of dynamic LDS has to be asked for once per kernel
     if (!lds_allowed) {
-      hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)(attn_lds_floats(128) * sizeof(float)));
-      if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void*)attn_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(attn_lds_floats(64) * sizeof(float)));
+      const int b128 = (int)(attn_lds_floats(128) * sizeof(float)), b64 = (int)(attn_lds_floats(64) * sizeof(float));
+      const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+      hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<128, false>, attr, b128);
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_mfma_kernel<128, true>, attr, b128);
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_mfma_kernel<64, false>, attr, b64);
+      if (e == hipSuccess) e = hipFuncSetAttribute((const void*)attn_mfma_kernel<64, true>, attr, b64);
       if (e != hipSuccess) return e;
       lds_allowed = true;
     }
-    if (h == 128)
-      attn_mfma_kernel<128><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part);
+    const dim3 block(kAttnWaves * 64);
+    if (h == 128 && qpw > 1)
+      attn_mfma_kernel<128, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+    else if (h == 128)
+      attn_mfma_kernel<128, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+    else if (qpw > 1)
+      attn_mfma_kernel<64, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
     else
-      attn_mfma_kernel<64><<<grid, kAttnWaves * 64, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part);
+      attn_mfma_kernel<64, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

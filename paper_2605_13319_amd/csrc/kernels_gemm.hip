@@ -104,6 +104,9 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.eps = c.eps;
   a.row_tiles = row_tiles;
   a.act_tiles = c.act_tiles;
+  if (row_tiles >= kWideMinRowTiles && c.act_tiles == 8 &&
+      (c.wide_mode == 2 || (c.wide_mode == 0 && gemm_wide_preferred(c.N, c.K))))
+    return launch_gemm_wide(c, a, st);
   const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);
   const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;
   if (row_tiles == 1) {

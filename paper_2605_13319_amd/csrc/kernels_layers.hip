@@ -154,7 +154,8 @@ __global__ __launch_bounds__(512) void layers_kernel(LayersArgs a) {
       const int ntasks = nkv * a.nsplit * nqt;
       for (int task = blockIdx.x; task < ntasks; task += gridDim.x) {
         attn_task<HD, true>(a.arena.q(l), gq.kv, l, gq.m, gq.start_pos, gq.n_q_heads, a.nsplit, a.arena.partials(l),
-                            task % nkv, (task / nkv) % a.nsplit, task / (nkv * a.nsplit), lds);
+                            task % nkv, (task / nkv) % a.nsplit, task / (nkv * a.nsplit), task / (nkv * a.nsplit) + 1,
+                            lds);
         __syncthreads();  // the task's LDS is free again
       }
       Xwg<true>::drain();

@@ -60,6 +60,7 @@ _SIGS = {
                                      C.c_void_p]),
     "pipesd_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p]),
     "pipesd_model_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
+    "pipesd_model_set_wide_gemm": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_model_fused_launches": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "pipesd_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_profile_read": (C.c_int, [C.c_void_p, _i32p, C.POINTER(C.c_double)]),
@@ -146,6 +147,10 @@ class Model:
             self.close()
         except Exception:
             pass
+
+    def set_wide_gemm(self, mode: int) -> None:
+        """GEMM kernel of passes of more than 64 rows: 0 by shape, 1 narrow, 2 wide (same results)."""
+        _check(_lib.pipesd_model_set_wide_gemm(self.handle, int(mode)), "pipesd_model_set_wide_gemm")
 
     def set_fused(self, on: bool) -> None:
         _check(_lib.pipesd_model_set_fused(self.handle, 1 if on else 0), "pipesd_model_set_fused")

@@ -367,3 +367,32 @@ def test_bf16_row_block_equals_shorter_row_blocks(nav, fused):
     for n in (0, 1, 3, 8, 12):
         zn = kv.forward_logits(0, d[:n])
         assert float(np.abs(zn - z16[:n + 1]).max()) < 2e-3, n
+
+
+WIDE_CHECK = I.ModelShape("wide-check", 2, 2048, 16, 4, 128, 7168, 4096)
+
+
+@pytest.mark.parametrize("shape,prefix", [(SMALL_BF16, 150), (WIDE_CHECK, 200)])
+def test_wide_gemm_kernel_is_bit_identical_to_the_narrow_one(nav, shape, prefix):
+    """Passes of more than 64 rows (here: prompt ingestion in 128-row passes) give the same cache
+    and the same logits, bit for bit, whether their products run on the wide GEMM kernel (LDS-staged
+    activations, whole-K or K-split workgroups) or on the narrow one: W = 1, W = 4 and W = 7 / P = 2
+    slice layouts are among the shapes."""
+    w = I.make_weights(shape, 41)
+    model = nav.Model(shape, w)
+    toks = I.make_tokens(prefix, shape.vocab, 42)
+    d = I.make_tokens(9, shape.vocab, 43)
+    caches, logits = [], []
+    for mode in (1, 2, 0):
+        model.set_wide_gemm(mode)
+        kv = nav.KVCache(model, max_seqs=1, n_blocks=prefix // 16 + 4)
+        kv.prefill(0, toks)
+        rows = [kv.read_kv(0, layer, pos) for layer in (0, shape.n_layers - 1) for pos in (0, 63, 64, 127, 128, prefix - 2)]
+        caches.append(np.concatenate([np.concatenate(r) for r in rows]))
+        model.set_wide_gemm(0)
+        logits.append(kv.forward_logits(0, d))
+    for i in (1, 2):
+        assert np.array_equal(caches[0], caches[i]), f"cache rows differ (mode index {i})"
+        assert np.array_equal(logits[0], logits[i]), f"logits differ (mode index {i})"
+    with pytest.raises(Exception):
+        model.set_wide_gemm(3)
