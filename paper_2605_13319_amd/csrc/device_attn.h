@@ -31,6 +31,12 @@ __device__ __forceinline__ void split_hi_lo8(const float (&v)[8], bf16x8& hi, bf
   lo = __builtin_bit_cast(bf16x8, au32x4{l[0], l[1], l[2], l[3]});
 }
 
+// e^x through the hardware base-2 exponential (x <= 0 here; e^-inf = 0)
+__device__ __forceinline__ float attn_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+// n / m for 0 <= n < 4096, 1 <= m <= 128 with rinv = 1/m to within an ulp: (n + 0.5) / m is at least
+// 0.5/m away from an integer, far more than the rounding error
+__device__ __forceinline__ int div_small(int n, float rinv) { return (int)(((float)n + 0.5f) * rinv); }
+
 constexpr size_t attn_lds_floats(int hd) { return (size_t)kAttnWaves * 16 * (hd + 4) + 2 * kAttnWaves * 16; }
 
 // Task (kv_head, split, query tiles qt0..qt1-1) = 8 waves x 32 tokens against the query rows that
@@ -60,6 +66,9 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
   const int tok0 = split * kAttnWgTokens + w * 32;
   const uint16_t* pool = (const uint16_t*)kv.pool;
   const float scale = 1.0f / sqrtf((float)HD);
+  const float m_rinv = __builtin_amdgcn_rcpf((float)m);
+  // all 32 tokens of this wave are cached tokens that every row of the pass sees: no masks needed
+  const bool full = tok0 + 31 <= start_pos;
 
   // ---- requests: keys and values of this wave's 32 tokens, queries of row tile qt ----
   au32x4 kraw[2][KSQ];
@@ -82,9 +91,9 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
   au32x4 qa[KSQ], qb[KSQ];  // hi, lo
   const uint16_t* q16 = (const uint16_t*)q;
   const int qd = n_q_heads * HD;
-  auto q_request = [&](int qt) {  // rows beyond the head group read row 0 of the group (and are masked)
+  auto q_request = [&](int qt) {  // rows beyond the head group read row 0 of the group (their results are dropped)
     const int rr = qt * 16 + c;
-    const int gq = rr < R ? rr / m : 0, r = rr < R ? rr % m : 0;
+    const int gq = rr < R ? div_small(rr, m_rinv) : 0, r = rr < R ? rr - gq * m : 0;
 #pragma unroll
     for (int s = 0; s < KSQ; ++s) {
       const uint16_t* qp = q16 + (size_t)r * 2 * qd + (kvh * group + gq) * HD + s * 32 + g * 8;
@@ -96,7 +105,13 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
 
   // ---- operands: tokens at or beyond `total` read as zero ----
   bf16x8 kf[2][KSQ], vf[HT];
-  {
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+    for (int s = 0; s < KSQ; ++s) kf[tt][s] = __builtin_bit_cast(bf16x8, kraw[tt][s]);
+#pragma unroll
+  for (int j = 0; j < HT; ++j) vf[j] = __builtin_bit_cast(bf16x8, au32x4{vlo[j].x, vlo[j].y, vhi[j].x, vhi[j].y});
+  if (!full) {
     unsigned long long keep[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -115,13 +130,12 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
   }
   for (int qt = qt0; qt < qt1; ++qt) {
   const int rr = qt * 16 + c;
-  const bool row_ok = rr < R;
-  const int r = row_ok ? rr % m : 0;
+  const int r = rr < R ? rr - div_small(rr, m_rinv) * m : 0;
   bf16x8 qhi[KSQ], qlo[KSQ];
 #pragma unroll
   for (int s = 0; s < KSQ; ++s) {
-    qhi[s] = __builtin_bit_cast(bf16x8, row_ok ? qa[s] : au32x4{0u, 0u, 0u, 0u});
-    qlo[s] = __builtin_bit_cast(bf16x8, row_ok ? qb[s] : au32x4{0u, 0u, 0u, 0u});
+    qhi[s] = __builtin_bit_cast(bf16x8, qa[s]);
+    qlo[s] = __builtin_bit_cast(bf16x8, qb[s]);
   }
 
   // ---- scores of query row c against tokens tok0 + tt*16 + g*4 + i ----
@@ -136,20 +150,23 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][s], qlo[s], acc, 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int t = tok0 + tt * 16 + g * 4 + i;
-      sc[tt * 4 + i] = (row_ok && t <= pos_q) ? acc[i] * scale : -INFINITY;
-    }
+    for (int i = 0; i < 4; ++i) sc[tt * 4 + i] = acc[i] * scale;
+  }
+  if (!full) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (tok0 + (i >> 2) * 16 + g * 4 + (i & 3) > pos_q) sc[i] = -INFINITY;
   }
   float m_run = sc[0];
 #pragma unroll
   for (int i = 1; i < 8; ++i) m_run = fmaxf(m_run, sc[i]);
   m_run = fmaxf(m_run, __shfl_xor(m_run, 16, 64));
   m_run = fmaxf(m_run, __shfl_xor(m_run, 32, 64));
+  const float m_ref = (m_run == -INFINITY) ? 0.f : m_run;  // a row that sees none of the tokens: all weights 0
   float pv[8], l_run = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    pv[i] = (sc[i] == -INFINITY) ? 0.f : expf(sc[i] - m_run);
+    pv[i] = attn_exp(sc[i] - m_ref);
     l_run += pv[i];
   }
   l_run += __shfl_xor(l_run, 16, 64);
@@ -177,18 +194,19 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
     float M = m_lds[0][mr];
 #pragma unroll
     for (int ww = 1; ww < kAttnWaves; ++ww) M = fmaxf(M, m_lds[ww][mr]);
+    const float M_ref = (M == -INFINITY) ? 0.f : M;
     float L = 0.f;
     f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ww = 0; ww < kAttnWaves; ++ww) {
-      const float mw = m_lds[ww][mr];
-      const float sw = (mw == -INFINITY) ? 0.f : expf(mw - M);
+      const float sw = attn_exp(m_lds[ww][mr] - M_ref);
       L += l_lds[ww][mr] * sw;
       o += *(const f32x4*)&o_lds[ww][mr][e0] * sw;
     }
     const int rr2 = qt * 16 + mr;
     if (rr2 < R) {
-      const int head2 = kvh * group + rr2 / m, r2 = rr2 % m;
+      const int g2 = div_small(rr2, m_rinv);
+      const int head2 = kvh * group + g2, r2 = rr2 - g2 * m;
       float* dst = part + (((size_t)head2 * m + r2) * nsplit + split) * (HD + kPartPad);
       Xwg<CO>::st4f(dst + e0, o);
       if (e0 == 0) Xwg<CO>::st4f(dst + HD, f32x4{M, L, 0.f, 0.f});
@@ -235,13 +253,13 @@ __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int 
     for (int j = 0; j < BATCH; ++j)
       if (s0 + j < nsplit) bm = fmaxf(bm, ml[j][0]);
     if (bm == -INFINITY) continue;
-    const float so = (M == -INFINITY) ? 0.f : expf(M - bm);
+    const float so = (M == -INFINITY) ? 0.f : attn_exp(M - bm);
     L *= so;
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] *= so;
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const float wgt = (s0 + j < nsplit && ml[j][0] != -INFINITY) ? expf(ml[j][0] - bm) : 0.f;
+      const float wgt = (s0 + j < nsplit && ml[j][0] != -INFINITY) ? attn_exp(ml[j][0] - bm) : 0.f;
       L += ml[j][1] * wgt;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
