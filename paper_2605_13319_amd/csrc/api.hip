@@ -232,8 +232,9 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
   const size_t RP = c.dtype == PIPESD_BF16 ? kMaxPassRows : kMaxRows;  // rows of the largest pass
   if ((rc = dev_alloc(m, (void**)&m->logits, RP * (size_t)V * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->rope_cs, RP * c.head_dim * 4))) return rc;
-  if ((rc = dev_alloc(m, (void**)&m->row_stats, (R * 64 * 2 + 64) * 4))) return rc;
-  if ((rc = dev_alloc(m, (void**)&m->scan_partial, 64 * 8))) return rc;
+  // decision scratch: softmax partials of every row of the largest pass, scan sums per client
+  if ((rc = dev_alloc(m, (void**)&m->row_stats, ((size_t)kMaxPassRows * 64 * 2 + 64) * 4))) return rc;
+  if ((rc = dev_alloc(m, (void**)&m->scan_partial, (size_t)kMaxPassClients * 64 * 8))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->result_dev, (size_t)2 * kMaxBatchResults * 4))) return rc;
   if ((rc = dev_alloc(m, (void**)&m->counters, (size_t)kCounterSlots * 4))) return rc;
   HIP_TRY(hipMemset(m->counters, 0, (size_t)kCounterSlots * 4));
@@ -1021,13 +1022,51 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
     for (int32_t i = first; i < last && rc == PIPESD_OK; ++i)
       rc = ensure_blocks(kv, seq_ids[i], (int32_t)kv->seqs[seq_ids[i]].text.size() + k_per_seq[i], st);
     if (rc == PIPESD_OK) rc = run_pass(model, kv, pl, true, st);
+    // The clients that use the sampling rule are decided, and their caches trimmed, by one launch
+    // each for the whole pass (bf16, two or more such clients); token-matching clients, and passes
+    // with a single sampling client, take the single-client kernels.
+    int n_sampling = 0;
+    for (int32_t i = first; i < last; ++i) n_sampling += (draft_probs_per_seq && draft_probs_per_seq[i]) ? 1 : 0;
+    const bool batched = pack && n_sampling > 1;
+    if (rc == PIPESD_OK && batched) {
+      DecisionCall dc{};
+      TrimBatch tb{};
+      dc.logits = model->logits;
+      dc.rows = pl.rows;
+      dc.V = model->cfg.vocab;
+      for (int32_t i = first, row_off = 0; i < last; ++i) {
+        const int32_t k = k_per_seq[i];
+        if (draft_probs_per_seq[i]) {
+          dc.batch.c[dc.batch.n++] = DecisionClient{draft_probs_per_seq[i], row_off, k, i - first};
+          for (int32_t j = 0; j < k; ++j) dc.batch.drafts.tok[row_off + j] = draft_tokens_concat[tok_off[i] + j];
+          for (int32_t j = 0; j <= k; ++j) dc.batch.u[row_off + j] = uniforms_concat[u_off[i] + j];
+          tb.c[tb.n++] = TrimClient{seq_ids[i] * kv->n_blocks, pl.client[i - first].start_pos, k, i - first};
+        }
+        row_off += k + 1;
+      }
+      dc.row_stats = model->row_stats;
+      dc.scan_partial = model->scan_partial;
+      dc.counter = model->counters + (kCounterSlots - 1 - kMaxPassClients);
+      dc.result = model->result_dev + 2 * first;
+      dc.result_copy = model->result_host + 4 + 2 * first;
+      hipError_t e;
+      {
+        ProfScope ps(model, PIPESD_PROF_VERIFY, st);
+        e = launch_spec_accept_batch(dc, st);
+        if (e == hipSuccess)
+          e = launch_kv_trim_batch(model->cfg.dtype, view_of(kv, 0), model->cfg.n_layers, tb, dc.result, st);
+      }
+      if (e != hipSuccess) rc = hip_fail(e, "batched verify");
+    }
     for (int32_t i = first, row_off = 0; i < last && rc == PIPESD_OK; ++i) {
       const float* qi = draft_probs_per_seq ? draft_probs_per_seq[i] : nullptr;
-      const hipError_t e = enqueue_decision(model, kv, seq_ids[i], row_off, pl.client[i - first].start_pos,
-                                            draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
-                                            uniforms_concat ? uniforms_concat + u_off[i] : nullptr,
-                                            model->result_dev + 2 * i, model->result_host + 4 + 2 * i, st);
-      if (e != hipSuccess) rc = hip_fail(e, "batched verify");
+      if (!(batched && qi)) {
+        const hipError_t e = enqueue_decision(model, kv, seq_ids[i], row_off, pl.client[i - first].start_pos,
+                                              draft_tokens_concat + tok_off[i], k_per_seq[i], qi,
+                                              uniforms_concat ? uniforms_concat + u_off[i] : nullptr,
+                                              model->result_dev + 2 * i, model->result_host + 4 + 2 * i, st);
+        if (e != hipSuccess) rc = hip_fail(e, "batched verify");
+      }
       row_off += k_per_seq[i] + 1;
     }
     if (rc) {

@@ -259,6 +259,39 @@ struct VerifyCall {
   int32_t* result;      // device [2]: accepted_len, next_token
   int32_t* result_copy; // optional second place for the two values (pinned host memory the device can write), or nullptr
 };
+// all clients of a pass at once (sampling rule)
+struct DecisionClient {
+  const float* q;       // draft distributions [k][V] (never null: token-matching clients are not part of the batch)
+  int32_t row_off, k;   // the client's logits rows are row_off .. row_off + k of the pass
+  int32_t slot;         // its decision goes to result[2 slot], result[2 slot + 1]
+};
+struct DecisionBatch {
+  int32_t n;
+  DecisionClient c[kMaxPassClients];
+  PassTokens drafts;        // tok[row_off + j] = draft j of the client, j < k
+  float u[kMaxPassRows];    // u[row_off + j] = uniform j of the client, j <= k
+};
+struct DecisionCall {
+  const float* logits;  // [rows][V]
+  int rows, V;
+  DecisionBatch batch;
+  float* row_stats;                  // scratch [rows][64][2]
+  unsigned long long* scan_partial;  // scratch [clients][64]
+  unsigned* counter;                 // [clients] zeroed counters
+  int32_t* result;                   // device [slots][2]
+  int32_t* result_copy;              // pinned host [slots][2], or nullptr
+};
+hipError_t launch_spec_accept_batch(const DecisionCall& c, hipStream_t st);
+// cache trim of several clients of a pass (result[2 slot] = accepted length of the client)
+struct TrimClient {
+  int32_t table_off, first_pos, k, slot;
+};
+struct TrimBatch {
+  int32_t n;
+  TrimClient c[kMaxPassClients];
+};
+hipError_t launch_kv_trim_batch(int dtype, const KvView& kv, int n_layers, const TrimBatch& b, const int32_t* result,
+                                hipStream_t st);
 hipError_t launch_softmax_stats(const VerifyCall& c, hipStream_t st);  // per-row (max, sum of exp) partials of the logits
 hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st);    // decision on probabilities, or (from_logits) on
                                                                         // logits + the partials of launch_softmax_stats

@@ -210,6 +210,39 @@ hipError_t launch_kv_trim(int dtype, const KvView& kv, int n_layers, int first_p
   return hipGetLastError();
 }
 
+// grid (draft rows of the longest client, layers, clients)
+template <typename T>
+__global__ void kv_trim_batch_kernel(KvView kv, TrimBatch b, const int32_t* __restrict__ result) {
+  const TrimClient c = b.c[blockIdx.z];
+  const int a = result[2 * c.slot];
+  const int j = blockIdx.x;
+  const int layer = blockIdx.y;
+  if (j >= c.k || j + 1 <= a) return;
+  kv.table += c.table_off;
+  const int pos = c.first_pos + j + 1;
+  T* p = (T*)kv.pool;
+  const int kvd = kv.n_kv_heads * kv.head_dim;
+  for (int i = threadIdx.x; i < kvd; i += blockDim.x) {
+    const int kvh = i / kv.head_dim, e = i % kv.head_dim;
+    p[k_index(kv, layer, pos, kvh, e)] = (T)0;
+    p[v_index(kv, layer, pos, kvh, e)] = (T)0;
+  }
+}
+
+hipError_t launch_kv_trim_batch(int dtype, const KvView& kv, int n_layers, const TrimBatch& b, const int32_t* result,
+                                hipStream_t st) {
+  if (b.n < 1 || b.n > kMaxPassClients) return hipErrorInvalidValue;
+  int max_k = 0;
+  for (int i = 0; i < b.n; ++i) max_k = b.c[i].k > max_k ? b.c[i].k : max_k;
+  if (max_k <= 0) return hipSuccess;
+  dim3 grid(max_k, n_layers, b.n);
+  if (dtype == PIPESD_F32)
+    kv_trim_batch_kernel<float><<<grid, 256, 0, st>>>(kv, b, result);
+  else
+    kv_trim_batch_kernel<uint16_t><<<grid, 256, 0, st>>>(kv, b, result);
+  return hipGetLastError();
+}
+
 struct TableEntries {
   int32_t v[16];
 };

@@ -101,13 +101,11 @@ __device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long v
 // `stats` == nullptr: `p` holds probabilities.  Otherwise `p` holds logits and `stats` the (max,
 // sum of exp) chunk partials of softmax_stats_kernel: the probabilities are formed on the fly by the
 // very expressions softmax_write_kernel uses, so the decision is the one the two-step path takes.
-__global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __restrict__ p, const float* __restrict__ q,
-                                                                const float* __restrict__ stats,
-                                                                int k, int V, RowTokens drafts, Uniforms un,
-                                                                unsigned long long* partial,
-                                                                unsigned* counter,
-                                                                int32_t* __restrict__ result,
-                                                                int32_t* __restrict__ result_copy) {
+// (drafts[0..k-1] and un[0..k] may point into kernel arguments)
+__device__ __forceinline__ void spec_accept_body(const float* __restrict__ p, const float* __restrict__ q,
+                                                 const float* __restrict__ stats, int k, int V, const int32_t* drafts,
+                                                 const float* un, unsigned long long* partial, unsigned* counter,
+                                                 int32_t* __restrict__ result, int32_t* __restrict__ result_copy) {
   __shared__ unsigned long long red[kVThreads / 64];
   __shared__ int s_a, s_last;
   __shared__ float s_M[kMaxRows], s_S[kMaxRows];
@@ -138,9 +136,9 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
   }
   __syncthreads();
   if (tid < k) {  // the k tests side by side
-    const int d = drafts.tok[tid];
+    const int d = drafts[tid];
     const float v = p[(size_t)tid * V + d];
-    s_ok[tid] = accept_test(from_logits ? expf(v - s_M[tid]) / s_S[tid] : v, q[(size_t)tid * V + d], un.u[tid]) ? 1 : 0;
+    s_ok[tid] = accept_test(from_logits ? expf(v - s_M[tid]) / s_S[tid] : v, q[(size_t)tid * V + d], un[tid]) ? 1 : 0;
   }
   __syncthreads();
   auto prob = [&](int row, int i) -> float {
@@ -191,7 +189,7 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
     }
     next = bi;
   } else {
-    const unsigned long long ui = (unsigned long long)(un.u[k] * 16777216.0f);  // floor(u * 2^24)
+    const unsigned long long ui = (unsigned long long)(un[k] * 16777216.0f);  // floor(u * 2^24)
     const unsigned long long T = (__umul64hi(W, ui) << 40) | ((W * ui) >> 24);
     // chunk whose running total first exceeds T
     unsigned long long run = 0;
@@ -234,12 +232,51 @@ __global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __r
   }
 }
 
+__global__ __launch_bounds__(kVThreads) void spec_accept_kernel(const float* __restrict__ p, const float* __restrict__ q,
+                                                                const float* __restrict__ stats, int k, int V,
+                                                                RowTokens drafts, Uniforms un, unsigned long long* partial,
+                                                                unsigned* counter, int32_t* __restrict__ result,
+                                                                int32_t* __restrict__ result_copy) {
+  spec_accept_body(p, q, stats, k, V, drafts.tok, un.u, partial, counter, result, result_copy);
+}
+
 hipError_t launch_spec_accept(const VerifyCall& c, hipStream_t st) {
   Uniforms un;
   for (int i = 0; i < kMaxRows; ++i) un.u[i] = c.u[i];
   spec_accept_kernel<<<kScanBlocks, kVThreads, 0, st>>>(c.logits_or_p, c.q, c.from_logits ? c.row_stats : nullptr, c.k,
                                                         c.V, c.drafts, un, c.scan_partial,
                                                         c.counter, c.result, c.result_copy);
+  return hipGetLastError();
+}
+
+// The decisions of all clients of a pass in one launch: workgroups (scan block, client).  Client ci
+// owns logits rows row_off .. row_off + k of the pass, partial sums [ci][kScanBlocks], counter ci and
+// result slots 2 slot, 2 slot + 1; its drafts and uniforms sit at the indices of its rows.  Each client
+// is decided by the very code of the single-client kernel.
+__global__ __launch_bounds__(kVThreads) void spec_accept_batch_kernel(const float* __restrict__ logits,
+                                                                      const float* __restrict__ stats, int V,
+                                                                      DecisionBatch b, unsigned long long* partial,
+                                                                      unsigned* counter, int32_t* __restrict__ result,
+                                                                      int32_t* __restrict__ result_copy) {
+  const int ci = blockIdx.y;
+  const DecisionClient c = b.c[ci];
+  spec_accept_body(logits + (size_t)c.row_off * V, c.q, stats + (size_t)c.row_off * kStatChunks * 2, c.k, V,
+                   b.drafts.tok + c.row_off, b.u + c.row_off, partial + (size_t)ci * kScanBlocks, counter + ci,
+                   result + 2 * c.slot, result_copy ? result_copy + 2 * c.slot : nullptr);
+}
+
+hipError_t launch_spec_accept_batch(const DecisionCall& c, hipStream_t st) {
+  if (c.batch.n < 1 || c.batch.n > kMaxPassClients || c.rows < 1 || c.rows > kMaxPassRows) return hipErrorInvalidValue;
+  for (int i = 0; i < c.batch.n; ++i) {
+    const DecisionClient& d = c.batch.c[i];
+    if (d.q == nullptr || d.k < 1 || d.k > kMaxRows - 1 || d.row_off < 0 || d.row_off + d.k + 1 > c.rows || d.slot < 0)
+      return hipErrorInvalidValue;
+  }
+  softmax_stats_kernel<<<dim3(kStatChunks, c.rows), kVThreads, 0, st>>>(c.logits, c.V, c.row_stats);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  spec_accept_batch_kernel<<<dim3(kScanBlocks, c.batch.n), kVThreads, 0, st>>>(
+      c.logits, c.row_stats, c.V, c.batch, c.scan_partial, c.counter, c.result, c.result_copy);
   return hipGetLastError();
 }
 
