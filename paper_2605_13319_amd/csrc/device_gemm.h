@@ -1,7 +1,7 @@
 // Device code of the skinny bf16 GEMM, shared by the per-GEMM kernel and the fused layer kernel.
 //
-// y[m][N] = act[m][K] * W[N][K]^T with m = k + 1 <= 32 rows (the QKV / O / SwiGLU-FFN / LM-head
-// products of the target forward, Sec. 2.2).  The pass is bound by streaming W once from HBM, so
+// y[m][N] = act[m][K] * W[N][K]^T with few rows m (a client's k + 1 <= 32, or the rows of several
+// clients, up to 128; the QKV / O / SwiGLU-FFN / LM-head products of the target forward, Sec. 2.2).  The pass is bound by streaming W once from HBM, so
 // everything is arranged around that stream:
 //  * W is re-tiled once, at model creation, into the order the matrix cores consume it: tile
 //    (n-tile of 16 weight rows, k-step of 32 columns) is 1 KB, lane l holding row l%16, columns
@@ -14,7 +14,8 @@
 //    matrix cores idle otherwise.
 //  * A pass of more than 16 rows is spread over GROUPS of workgroups that walk the same tiles, one
 //    per 16 rows, placed on the same chiplet: the weights cross the memory interface once and the
-//    other readers are served by the chiplet's L2.
+//    other readers are served by the chiplet's L2.  (Beyond 64 rows the larger products go to the
+//    kernel of kernels_gemm_wide.hip, which stages all rows' activations in LDS instead.)
 //  * K is cut into W * P slices of KSTEPS*32 columns; a team of W waves takes slices p*W + w,
 //    p = 0..P-1, one phase after the other, for a group of tg n-tiles, each wave keeping its running
 //    16x16 sums in its own LDS slots; after the last phase the team adds them in a fixed order.
