@@ -54,6 +54,26 @@ class OracleSeq:
         self.committed += [int(t) for t in drafts[:a]] + [nxt]
         return a, nxt
 
+    def nav_verify_chain(self, rounds) -> list:
+        """Proactively sent drafts (Appendix B).  rounds[0] = (drafts, q, u) is an ordinary round.
+        rounds[r], r >= 1 = (buffer, q, u): `buffer` holds the tokens the edge went on drafting while
+        round r - 1 was being verified, buffer[0] being its guess of that round's extra token.  The
+        buffer stays valid iff every draft of round r - 1 was accepted and the extra token the
+        target produced equals buffer[0]; then buffer[1:] are round r's drafts (q, u belong to
+        them), otherwise this buffer and all later ones are discarded.  Returns the (accepted,
+        next token) pairs of the rounds that ran."""
+        out = []
+        for r, (toks, q, u) in enumerate(rounds):
+            toks = [int(t) for t in toks]
+            if r > 0:
+                a_prev, next_prev = out[-1]
+                k_prev = len(rounds[r - 1][0]) - (1 if r - 1 > 0 else 0)
+                if a_prev != k_prev or next_prev != toks[0]:
+                    break
+                toks = toks[1:]
+            out.append(self.nav_verify(toks, q, u))
+        return out
+
     def rollback(self, new_prefix_len: int) -> None:
         """Cut the committed text to `new_prefix_len` tokens; its last token becomes pending."""
         assert 1 <= new_prefix_len <= self.prefix_len

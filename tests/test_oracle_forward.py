@@ -253,3 +253,82 @@ def test_greedy_verify_matches_sequential_argmax_decoding():
             d[j] = (d[j] + 1) % SMALL.vocab
         s.nav_verify(d, None, None)
     assert s.committed[:len(ref)] == ref
+
+
+def _greedy_text(m, base, n):
+    """n tokens of plain one-token-at-a-time argmax decoding after `base`."""
+    ar = OracleSeq(m, 96)
+    ar.prefill(base, chunk=64)
+    for _ in range(n):
+        t = int(np.argmax(ar.forward_logits([])[0]))
+        ar.cached += 1
+        ar.committed.append(t)
+    return ar.committed
+
+
+def test_chained_rounds_on_proactive_buffers_equal_plain_greedy_decoding():
+    """Appendix B: buffers whose first token is the extra token the target produces, and whose
+    other tokens are what the target would generate, stay valid round after round; the committed
+    text is then plain argmax decoding, one round's k + 1 tokens at a time."""
+    m = _model()
+    base = I.make_tokens(9, SMALL.vocab, 21)
+    ref = _greedy_text(m, base, 14)
+    n0 = len(base)
+    # round 0: 3 drafts (+ extra token = ref[n0 + 3]); buffer 1: guess ref[n0 + 3] + 4 drafts; buffer 2: guess + 2 drafts
+    rounds = [(ref[n0:n0 + 3], None, None), (ref[n0 + 3:n0 + 8], None, None), (ref[n0 + 8:n0 + 11], None, None)]
+    s = OracleSeq(m, 96)
+    s.prefill(base, chunk=64)
+    out = s.nav_verify_chain(rounds)
+    assert [a for a, _ in out] == [3, 4, 2]
+    assert s.committed == ref[:n0 + 3 + 1 + 4 + 1 + 2 + 1]
+    assert [nx for _, nx in out] == [ref[n0 + 3], ref[n0 + 8], ref[n0 + 11]]
+
+
+def test_chain_stops_at_a_wrong_guess_or_a_rejected_draft_and_leaves_the_state_of_the_last_round():
+    m = _model()
+    base = I.make_tokens(9, SMALL.vocab, 21)
+    ref = _greedy_text(m, base, 14)
+    n0 = len(base)
+    wrong = (ref[n0 + 3] + 1) % SMALL.vocab
+    # (i) wrong guess of the extra token: only round 0 runs
+    s = OracleSeq(m, 96)
+    s.prefill(base, chunk=64)
+    out = s.nav_verify_chain([(ref[n0:n0 + 3], None, None), ([wrong] + ref[n0 + 4:n0 + 8], None, None)])
+    assert out == [(3, ref[n0 + 3])] and s.committed == ref[:n0 + 4] and s.cached == n0 + 3
+    # (ii) a rejected draft in round 0: its buffer is dropped even though the guess equals the correction
+    bad = list(ref[n0:n0 + 3])
+    bad[1] = (bad[1] + 1) % SMALL.vocab
+    s = OracleSeq(m, 96)
+    s.prefill(base, chunk=64)
+    out = s.nav_verify_chain([(bad, None, None), ([ref[n0 + 1]] + ref[n0 + 2:n0 + 5], None, None)])
+    assert out == [(1, ref[n0 + 1])] and s.committed == ref[:n0 + 2]
+    # (iii) the same rounds given one by one, with the validity rule applied by hand, end in the same state
+    t = OracleSeq(m, 96)
+    t.prefill(base, chunk=64)
+    assert t.nav_verify(bad, None, None) == (1, ref[n0 + 1]) and t.committed == s.committed and t.cached == s.cached
+
+
+def test_chain_with_the_sampling_rule_keeps_buffers_exactly_when_the_rule_says():
+    """q == p makes every draft accepted whatever the uniforms are (ratio 1), so the chain goes on
+    exactly when the buffer's first token is the extra token drawn from p_{k+1}."""
+    m = _model()
+    base = I.make_tokens(7, SMALL.vocab, 33)
+    probe = OracleSeq(m, 96)
+    probe.prefill(base, chunk=64)
+    d0 = I.make_tokens(3, SMALL.vocab, 34)
+    p0 = softmax_rows(probe.forward_logits(d0))
+    u0 = I.make_uniforms(4, 35)
+    a0, x0 = probe.nav_verify(d0, p0[:3].copy(), u0)
+    assert a0 == 3
+    d1 = I.make_tokens(2, SMALL.vocab, 36)
+    p1 = softmax_rows(probe.forward_logits(d1))
+    u1 = I.make_uniforms(3, 37)
+    a1, x1 = probe.nav_verify(d1, p1[:2].copy(), u1)
+    s = OracleSeq(m, 96)
+    s.prefill(base, chunk=64)
+    out = s.nav_verify_chain([(d0, p0[:3].copy(), u0), ([x0] + list(d1), p1[:2].copy(), u1)])
+    assert out == [(a0, x0), (a1, x1)] and s.committed == probe.committed
+    s = OracleSeq(m, 96)
+    s.prefill(base, chunk=64)
+    out = s.nav_verify_chain([(d0, p0[:3].copy(), u0), ([(x0 + 1) % SMALL.vocab] + list(d1), p1[:2].copy(), u1)])
+    assert out == [(a0, x0)] and s.prefix_len == len(base) + 4
