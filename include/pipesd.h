@@ -175,6 +175,28 @@ int pipesd_spec_accept(const float *p, const float *q, const int32_t *draft_toke
                        int32_t vocab, const float *uniforms, int32_t *accepted_len, int32_t *next_token,
                        void *stream);
 
+/* Chained rounds on proactively sent drafts (Appendix B: while a round is being verified the edge
+ * goes on drafting and sending; the cloud buffers those tokens and keeps them only if the round
+ * accepts every draft AND its extra token equals the first buffered token).
+ *   Round 0 is an ordinary round: k_per_round[0] drafts.  Round r >= 1 brings a buffer of
+ *   1 + k_per_round[r] tokens: the edge's guess of round r-1's extra token, then round r's drafts.
+ *   tokens_concat (host) holds round 0's drafts, then each buffer; draft_probs_per_round[r] (host
+ *   array of device pointers, or NULL = token matching for every round; entries may be NULL) is the
+ *   fp32 [k_r][vocab] distribution block of round r's DRAFTS (the guess has none: it is compared with
+ *   the target's own extra token); uniforms_concat (host) holds k_r + 1 values per round, one round
+ *   after the other (ignored for token-matching rounds, may then be NULL).
+ * Round r runs iff every earlier round ran, accepted all its drafts and produced the guessed extra
+ * token; each round that runs is exactly a pipesd_nav_verify call on the state the round before
+ * left.  *rounds_run (>= 1 on success) tells how many ran; accepted_len / next_token (host,
+ * [n_rounds]) are filled for those.  1 <= n_rounds <= 16.
+ * Errors: all argument checks (PIPESD_EINVAL), the state check (PIPESD_ESTATE) and the check that the
+ * pool can hold the longest possible outcome (PIPESD_ENOMEM) come before anything changes.  A HIP
+ * failure in round r > 0 leaves rounds 0..r-1 committed and *rounds_run = r.  Synchronises. */
+int pipesd_nav_verify_chain(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t prefix_len,
+                            int32_t n_rounds, const int32_t *k_per_round, const int32_t *tokens_concat,
+                            const float *const *draft_probs_per_round, const float *uniforms_concat,
+                            int32_t *accepted_len, int32_t *next_token, int32_t *rounds_run, void *stream);
+
 /* Test hook: copy the cached key and value of one (layer, position) of client `seq` to host fp32
  * arrays [n_kv_heads*head_dim] (keys as stored, i.e. rotated).  Synchronises the device. */
 int pipesd_kv_read(const pipesd_model *model, const pipesd_kv *kv, int32_t seq, int32_t layer,

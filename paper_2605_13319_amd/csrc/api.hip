@@ -957,6 +957,61 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
   return rc;
 }
 
+extern "C" int pipesd_nav_verify_chain(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t prefix_len,
+                                       int32_t n_rounds, const int32_t* k_per_round, const int32_t* tokens_concat,
+                                       const float* const* draft_probs_per_round, const float* uniforms_concat,
+                                       int32_t* accepted_len, int32_t* next_token, int32_t* rounds_run, void* stream) {
+  if (!model || !kv || kv->model != model || !k_per_round || !tokens_concat || !accepted_len || !next_token ||
+      !rounds_run)
+    return PIPESD_EINVAL;
+  if (n_rounds < 1 || n_rounds > 16 || !seq_ok(kv, seq)) return PIPESD_EINVAL;
+  // ---- every check that can fail without running a pass comes before the first change of state ----
+  std::vector<int32_t> tok_off(n_rounds), u_off(n_rounds);
+  int32_t toks = 0, us = 0, growth = 0;
+  for (int32_t r = 0; r < n_rounds; ++r) {
+    const int32_t k = k_per_round[r];
+    if (k < 1 || k > kMaxRows - 1) return PIPESD_EINVAL;
+    if (r > 0) {  // the guess of the previous round's extra token
+      if (tokens_concat[toks] < 0 || tokens_concat[toks] >= model->cfg.vocab) return PIPESD_EINVAL;
+      ++toks;
+    }
+    tok_off[r] = toks;  // the round's drafts
+    u_off[r] = us;
+    toks += k;
+    us += k + 1;
+    growth += k + 1;
+  }
+  for (int pass = 0; pass < 2; ++pass)  // argument errors of every round first, then the state
+    for (int32_t r = 0; r < (pass == 0 ? n_rounds : 1); ++r) {
+      const float* qr = draft_probs_per_round ? draft_probs_per_round[r] : nullptr;
+      const int rc = check_verify_args(model, kv, seq, prefix_len, tokens_concat + tok_off[r], k_per_round[r], qr,
+                                       uniforms_concat ? uniforms_concat + u_off[r] : nullptr, pass == 1);
+      if (rc) return rc;
+    }
+  {
+    const SeqState& s = kv->seqs[seq];
+    // the longest outcome: every round runs and accepts everything (the last round's rows included)
+    const int64_t need = blocks_for((int32_t)s.text.size() - 1 + growth);
+    if (need > (int64_t)s.blocks.size() + (int64_t)kv->free_list.size()) return PIPESD_ENOMEM;
+  }
+  *rounds_run = 0;
+  int32_t lp = prefix_len;
+  for (int32_t r = 0; r < n_rounds; ++r) {
+    const int32_t k = k_per_round[r];
+    if (r > 0) {  // Appendix B: the buffer survives iff all of round r-1 was accepted and the guess was right
+      if (accepted_len[r - 1] != k_per_round[r - 1] || next_token[r - 1] != tokens_concat[tok_off[r] - 1]) break;
+    }
+    const float* qr = draft_probs_per_round ? draft_probs_per_round[r] : nullptr;
+    const int rc = pipesd_nav_verify(model, kv, seq, lp, tokens_concat + tok_off[r], k, qr,
+                                     uniforms_concat ? uniforms_concat + u_off[r] : nullptr, accepted_len + r,
+                                     next_token + r, stream);
+    if (rc) return rc;
+    lp += accepted_len[r] + 1;
+    *rounds_run = r + 1;
+  }
+  return PIPESD_OK;
+}
+
 extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32_t n_seqs, const int32_t* seq_ids,
                                        const int32_t* prefix_lens, const int32_t* k_per_seq,
                                        const int32_t* draft_tokens_concat, const float* const* draft_probs_per_seq,

@@ -59,6 +59,8 @@ _SIGS = {
     "pipesd_spec_accept": (C.c_int, [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_int32, _f32p, _i32p, _i32p,
                                      C.c_void_p]),
     "pipesd_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p]),
+    "pipesd_nav_verify_chain": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, _i32p,
+                                          C.POINTER(C.c_void_p), _f32p, _i32p, _i32p, _i32p, C.c_void_p]),
     "pipesd_model_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_model_set_wide_gemm": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_model_fused_launches": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
@@ -277,6 +279,38 @@ class KVCache:
                                             _ptr(ks, _i32p), _ptr(cat, _i32p), qarr, _ptr(ucat, _f32p),
                                             _ptr(a, _i32p), _ptr(nx, _i32p), _stream()), "pipesd_nav_verify_batch")
         return a.tolist(), nx.tolist()
+
+    def nav_verify_chain(self, seq: int, rounds, prefix_len: Optional[int] = None):
+        """Chained rounds on proactively sent drafts.  rounds[0] = (drafts, q, u); rounds[r >= 1] =
+        (buffer, q, u) with buffer[0] the guess of the previous round's extra token and buffer[1:]
+        the round's drafts (q: [k][V] array / CUDA tensor for the drafts, or None; u: k + 1 values or
+        None).  Returns the (accepted_len, next_token) pairs of the rounds that ran."""
+        n = len(rounds)
+        ks = _i32([len(t) - (1 if r > 0 else 0) for r, (t, _, _) in enumerate(rounds)])
+        cat = _i32([int(x) for t, _, _ in rounds for x in t])
+        keep, qarr, flat, any_q = [], (C.c_void_p * n)(), [], False
+        for r, (t, q, u) in enumerate(rounds):
+            k = int(ks[r])
+            if q is None:
+                qarr[r] = None
+            else:
+                tq = torch.from_numpy(_f32(q)).cuda() if isinstance(q, np.ndarray) else q.contiguous()
+                assert tq.dtype == torch.float32 and tq.numel() == k * self.model.shape.vocab
+                keep.append(tq)
+                qarr[r] = tq.data_ptr()
+                any_q = True
+            flat.extend([0.0] * (k + 1) if u is None else list(u))
+        ucat = _f32(flat)
+        if prefix_len is None:
+            prefix_len = self.length(seq)
+        a = np.full(n, -1, dtype=np.int32)
+        nx = np.full(n, -1, dtype=np.int32)
+        ran = _i32([0])
+        _check(_lib.pipesd_nav_verify_chain(self.model.handle, self.handle, seq, prefix_len, n, _ptr(ks, _i32p),
+                                            _ptr(cat, _i32p), qarr if any_q else None, _ptr(ucat, _f32p),
+                                            _ptr(a, _i32p), _ptr(nx, _i32p), _ptr(ran, _i32p), _stream()),
+               "pipesd_nav_verify_chain")
+        return [(int(a[r]), int(nx[r])) for r in range(int(ran[0]))]
 
     def rollback(self, seq: int, new_prefix_len: int) -> None:
         _check(_lib.pipesd_kv_rollback(self.handle, seq, new_prefix_len), "pipesd_kv_rollback")

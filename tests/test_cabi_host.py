@@ -116,6 +116,25 @@ def test_shape_only_handles_do_bookkeeping_but_refuse_compute():
     assert nav._lib.pipesd_nav_verify_batch(m.handle, kv.handle, 2, None, None, None, None, None, None, None, None,
                                             None) == nav.EINVAL
     assert kv.free_blocks() == 100
+    # chained rounds: the same checks for every round and for the guessed tokens in between
+    ran = np.zeros(1, dtype=np.int32)
+
+    def chain(n, ks_, cat_, seq=0):
+        return nav._lib.pipesd_nav_verify_chain(m.handle, kv.handle, seq, 5, n, ks_.ctypes.data_as(ip),
+                                                cat_.ctypes.data_as(ip), None, None, out_a.ctypes.data_as(ip),
+                                                out_n.ctypes.data_as(ip), ran.ctypes.data_as(ip), None)
+
+    cat2 = np.array([1, 2, 9, 3, 4], dtype=np.int32)  # round 0: 1 2; buffer: guess 9, drafts 3 4
+    assert chain(2, ks, cat2) == nav.ESTATE              # shape-only handles refuse compute
+    assert chain(0, ks, cat2) == nav.EINVAL
+    assert chain(17, ks, cat2) == nav.EINVAL
+    assert chain(2, ks, cat2, seq=4) == nav.EINVAL       # no such client
+    assert chain(2, np.array([2, 32], dtype=np.int32), cat2) == nav.EINVAL
+    assert chain(2, ks, np.array([1, 2, -1, 3, 4], dtype=np.int32)) == nav.EINVAL   # a guess outside the vocabulary
+    assert chain(2, ks, np.array([1, 2, 9, 3, I.LLAMA_8B.vocab], dtype=np.int32)) == nav.EINVAL
+    assert nav._lib.pipesd_nav_verify_chain(m.handle, kv.handle, 0, 5, 2, None, None, None, None, None, None, None,
+                                            None) == nav.EINVAL
+    assert kv.free_blocks() == 100
     kv.close()
     m.close()
 

@@ -396,3 +396,72 @@ def test_wide_gemm_kernel_is_bit_identical_to_the_narrow_one(nav, shape, prefix)
         assert np.array_equal(logits[0], logits[i]), f"logits differ (mode index {i})"
     with pytest.raises(Exception):
         model.set_wide_gemm(3)
+
+
+def _chain_by_hand(kv, seq, rounds):
+    """Appendix B's rule applied outside the library: single calls, stop at the first dropped buffer."""
+    out = []
+    for r, (toks, q, u) in enumerate(rounds):
+        toks = [int(t) for t in toks]
+        if r > 0:
+            k_prev = len(rounds[r - 1][0]) - (1 if r > 1 else 0)
+            if out[-1][0] != k_prev or out[-1][1] != toks[0]:
+                break
+            toks = toks[1:]
+        out.append(kv.nav_verify(seq, toks, q, u))
+    return out
+
+
+@pytest.mark.parametrize("wl_name,tol", [("tiny", 1e-4), ("small", 2e-2)])
+def test_chained_rounds_on_proactive_buffers(nav, wl_name, tol):
+    """Appendix B, cloud side: a buffer of proactively sent drafts is kept iff the round before it
+    accepted everything and produced the guessed extra token.  The chained call equals single calls
+    with the rule applied by hand, bit for bit; and where the checker's argmax margins are clear of
+    the logit tolerance (the fp32 model) the rounds that run, their decisions and the state they
+    leave equal the checker's.  Drafts: the target's own greedy text according to the checker, a
+    wrong guess at the end; then the sampling rule."""
+    if wl_name == "tiny":
+        shape, seed, prefix = I.WORKLOADS["tiny"]["shape"], 5100, 40
+    else:
+        shape, seed, prefix = SMALL_BF16, 5200, 70
+    oseq, model, kv = _both(nav, shape, seed, prefix, n_blocks=16)
+    toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX)
+    kv.prefill(1, toks)
+    probe = oracle_side(shape, I.make_weights(shape, seed + I.SEED_WEIGHTS), toks, prefix + 64)
+    margins = []
+    for _ in range(12):
+        z = probe.forward_logits([])[0]
+        top = np.sort(z)[-2:]
+        margins.append(float(top[1] - top[0]))
+        probe.cached += 1
+        probe.committed.append(int(np.argmax(z)))
+    ref, n0 = probe.committed, prefix
+    rounds = [(ref[n0:n0 + 3], None, None), (ref[n0 + 3:n0 + 8], None, None),
+              ([(ref[n0 + 8] + 1) % shape.vocab] + ref[n0 + 9:n0 + 11], None, None)]  # third buffer: wrong guess
+    out = kv.nav_verify_chain(0, rounds)
+    assert out == _chain_by_hand(kv, 1, rounds) and kv.length(0) == kv.length(1)
+    assert 1 <= len(out) <= 2
+    if min(margins) > 2.5 * tol:
+        out_ref = oseq.nav_verify_chain(rounds)
+        assert out == out_ref and [a for a, _ in out] == [3, 4]
+        assert kv.length(0) == oseq.prefix_len == n0 + 9
+    else:
+        print(f"checker comparison skipped: smallest argmax margin {min(margins):.4f} within the tolerance", flush=True)
+    # sampling rule: a round whose drafts are all accepted (q far below p: every ratio exceeds 1),
+    # then a buffer whose guess is the extra token the GPU itself draws (kept) or another token
+    # (dropped); chain == single calls
+    d0 = I.make_tokens(3, shape.vocab, seed + 50)
+    q0 = np.full((3, shape.vocab), 1e-30, dtype=np.float32)
+    u0 = I.make_uniforms(4, seed + 51)
+    d1, q1 = I.make_independent_drafts(2, shape.vocab, seed + 52, seed + 53, scale=1.0)
+    d1 = [int(t) for t in d1]
+    u1 = I.make_uniforms(3, seed + 54)
+    lp = kv.length(1)
+    a0, x0 = kv.nav_verify(1, d0, q0, u0)
+    assert a0 == 3
+    r1 = kv.nav_verify(1, d1, q1, u1)
+    out = kv.nav_verify_chain(0, [(d0, q0, u0), ([x0] + d1, q1, u1)])
+    assert out == [(a0, x0), r1] and kv.length(0) == kv.length(1)
+    kv.rollback(0, lp)
+    out = kv.nav_verify_chain(0, [(d0, q0, u0), ([(x0 + 1) % shape.vocab] + d1, q1, u1)])
+    assert out == [(a0, x0)] and kv.length(0) == lp + 4
