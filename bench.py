@@ -132,7 +132,7 @@ def main():
     ap.add_argument("--prof", default="all_gemm", help="kernel class bracketed by HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs the NAV pass on ONE GPU; --gpus N with N > 1 is not supported")
+        sys.exit("bench.py: the NAV pass runs on ONE GPU; --gpus N with N > 1 is not supported")
 
     import numpy as np
     import torch

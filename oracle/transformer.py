@@ -3,7 +3,7 @@
 The paper only says the target is a decoder-only stack of masked self-attention and
 feed-forward layers (Sec. 2.1); the concrete layer (RMSNorm, rotary positions on pairs
 (i, i + h/2), grouped-query attention, SwiGLU, no biases, untied LM head) is the Llama-style
-reading fixed for this build.
+reading taken here (the paper evaluates Llama-family targets, Sec. 5.1).
 """
 from __future__ import annotations
 
