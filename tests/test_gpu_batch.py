@@ -21,11 +21,17 @@ def nav():
     return n
 
 
-@pytest.mark.parametrize("shape_name,n_seq,rounds", [("tiny", 5, 4), ("small-bf16", 5, 4), ("small-bf16", 16, 12)])
+# vocabulary 24581 = 1537 n-tiles: the last tile is ragged (5 of 16 rows), the last group of 8 tiles
+# holds one tile, and the LM head of a pass of more than 64 rows runs whole-K workgroups
+RAGGED_BF16 = I.ModelShape("ragged-bf16", 2, 512, 8, 2, 64, 1024, 24581)
+
+
+@pytest.mark.parametrize("shape_name,n_seq,rounds", [("tiny", 5, 4), ("small-bf16", 5, 4), ("small-bf16", 16, 12),
+                                                      ("ragged-bf16", 16, 3)])
 def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds):
     """bf16: the clients' rows share passes of up to 128 rows (16 clients with k ~ U[1,16] need two);
     a row's results must not depend on what else is in its pass."""
-    shape = I.WORKLOADS["tiny"]["shape"] if shape_name == "tiny" else SMALL_BF16
+    shape = {"tiny": I.WORKLOADS["tiny"]["shape"], "small-bf16": SMALL_BF16, "ragged-bf16": RAGGED_BF16}[shape_name]
     w = I.make_weights(shape, 9001)
     model = nav.Model(shape, w)
     rng = np.random.default_rng(9002)
