@@ -5,6 +5,8 @@
 // query row of the query heads that share the KV head, producing an un-normalised partial
 // (max, sum, o); a second kernel merges the splits in a fixed order, so results do not depend on
 // scheduling.
+#include <algorithm>
+
 #include "device_attn.h"
 
 namespace pipesd {
@@ -168,10 +170,11 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
       max_m = b.c[i].m > max_m ? b.c[i].m : max_m;
       tasks += (long)c.kv.n_kv_heads * b.c[i].nsplit * ((group * b.c[i].m + 15) / 16);
     }
-    // more tasks than the device holds at once (two workgroups per compute unit): one workgroup per
-    // (kv head, split) walks all query tiles with its keys and values in registers
-    const int max_qt = (group * max_m + 15) / 16;
-    const int qpw = tasks > 4L * device_cu_count() ? max_qt : 1;
+    // more tasks than the device holds at once (two workgroups per compute unit): a workgroup walks
+    // several query tiles with its keys and values in registers, as many as still leave about two
+    // workgroups per compute unit (a 128-row prompt block has 32 tiles per (kv head, split))
+    const int max_qt = (group * max_m + 15) / 16, n_cu = device_cu_count();
+    const int qpw = tasks > 4L * n_cu ? (int)std::max(1L, std::min((long)max_qt, tasks / (2L * n_cu))) : 1;
     dim3 grid(c.kv.n_kv_heads, splits, (max_qt + qpw - 1) / qpw);
     if (h != 128 && h != 64) return hipErrorInvalidValue;
     const size_t lds = attn_lds_floats(h) * sizeof(float);
