@@ -116,6 +116,60 @@ def cpu_baseline(shape, weights, prefix, k, layers):
                       f"per-layer time x {shape.n_layers} + head/decision time; median of 3"}
 
 
+def batched(args, np, torch, I, nav):
+    """Several clients per call (the multi-client setting of Appendix I): every round each client
+    brings k ~ U[1,16] drafts; the clients' rows share passes of up to 128 rows."""
+    wl = I.WORKLOADS[args.workload]
+    shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
+    seed = wl["seed"] + 1000
+    n_seq = args.batch
+    weights = I.make_weights(shape, wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+    model = nav.Model(shape, weights)
+    rng = np.random.default_rng(seed + I.SEED_LENGTHS)
+    lens = [int(x) for x in rng.integers(256, 4097, n_seq)]
+    kv = nav.KVCache(model, n_seq, sum((n + 64) // 16 + 2 for n in lens))
+    t0 = time.time()
+    for s, n in enumerate(lens):
+        kv.prefill(s, I.make_tokens(n, shape.vocab, seed + 100 + s))
+    torch.cuda.synchronize()
+    log(f"[bench] {n_seq} prefixes ({sum(lens)} tokens) cached in {time.time() - t0:.1f}s")
+    esz = 4 if shape.dtype == I.DTYPE_F32 else 2
+    w_bytes = shape.n_params_streamed() * esz
+    times, ks_sum, rows, alg = [], 0, [], 0.0
+    for r in range(args.warmup + args.steps):
+        ks = [int(x) for x in rng.integers(1, 17, n_seq)]
+        drafts, probs, us = [], [], []
+        for s in range(n_seq):
+            d, q = I.make_independent_drafts(ks[s], shape.vocab, seed + 1000 * r + s, seed + 1000 * r + 500 + s, scale=1.0)
+            drafts.append([int(t) for t in d])
+            probs.append(torch.from_numpy(q).cuda())
+            us.append(I.make_uniforms(ks[s] + 1, seed + 7 + 100 * r + s))
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        a, _ = kv.nav_verify_batch(list(range(n_seq)), drafts, probs, us)
+        dt = time.perf_counter() - t
+        for s in range(n_seq):
+            kv.rollback(s, lens[s])  # every round starts from the same prefixes
+        if r >= args.warmup:
+            times.append(dt)
+            ks_sum += sum(ks)
+            rows.append(sum(ks) + n_seq)
+            # weights once per call; per client the cached K/V read, the new rows written and q read
+            alg += w_bytes + sum(shape.algorithmic_bytes(lens[s], ks[s]) - w_bytes for s in range(n_seq))
+    total = sum(times)
+    out = {
+        "metric": "verified_tokens_per_sec", "value": ks_sum / total, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / len(times) * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
+        "config": {"workload": f"{shape.name}: {n_seq} clients per call, prefixes U[256,4096], k U[1,16] redrawn every "
+                               f"round, paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
+        "hbm_algorithmic_gbps": alg / total / 1e9, "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS,
+        "ms_per_step_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)],
+        "roofline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,6 +184,9 @@ def main():
                     help="also run one plain 1 GiB device copy kernel (scale for the HBM byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof", default="all_gemm", help="kernel class bracketed by HIP events")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096], k U[1,16] "
+                         "redrawn every round; --steps rounds).  An auxiliary line: no roofline / cpu_baseline objects")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the NAV pass runs on ONE GPU; --gpus N with N > 1 is not supported")
@@ -139,6 +196,8 @@ def main():
     from paper_2605_13319_amd import inputs as I
     from paper_2605_13319_amd import nav
 
+    if args.batch > 0:
+        return batched(args, np, torch, I, nav)
     wl = I.WORKLOADS[args.workload]
     shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
     k = args.k or wl["k"]
