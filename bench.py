@@ -126,7 +126,7 @@ def batched(args, np, torch, I, nav):
     weights = I.make_weights(shape, wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
     model = nav.Model(shape, weights)
     rng = np.random.default_rng(seed + I.SEED_LENGTHS)
-    lens = [int(x) for x in rng.integers(256, 4097, n_seq)]
+    lens = [args.prefix] * n_seq if args.prefix else [int(x) for x in rng.integers(256, 4097, n_seq)]
     kv = nav.KVCache(model, n_seq, sum((n + 64) // 16 + 2 for n in lens))
     t0 = time.time()
     for s, n in enumerate(lens):
@@ -137,7 +137,7 @@ def batched(args, np, torch, I, nav):
     w_bytes = shape.n_params_streamed() * esz
     times, ks_sum, rows, alg = [], 0, [], 0.0
     for r in range(args.warmup + args.steps):
-        ks = [int(x) for x in rng.integers(1, 17, n_seq)]
+        ks = [args.k] * n_seq if args.k else [int(x) for x in rng.integers(1, 17, n_seq)]
         drafts, probs, us = [], [], []
         for s in range(n_seq):
             d, q = I.make_independent_drafts(ks[s], shape.vocab, seed + 1000 * r + s, seed + 1000 * r + 500 + s, scale=1.0)
@@ -161,8 +161,10 @@ def batched(args, np, torch, I, nav):
         "metric": "verified_tokens_per_sec", "value": ks_sum / total, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / len(times) * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
-        "config": {"workload": f"{shape.name}: {n_seq} clients per call, prefixes U[256,4096], k U[1,16] redrawn every "
-                               f"round, paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
+        "config": {"workload": f"{shape.name}: {n_seq} clients per call, prefixes "
+                               + (f"{args.prefix}" if args.prefix else "U[256,4096]") + ", k "
+                               + (f"{args.k}" if args.k else "U[1,16] redrawn every round")
+                               + ", paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
         "hbm_algorithmic_gbps": alg / total / 1e9, "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS,
         "ms_per_step_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)],
         "roofline": None,
@@ -185,8 +187,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prof", default="all_gemm", help="kernel class bracketed by HIP events")
     ap.add_argument("--batch", type=int, default=0,
-                    help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096], k U[1,16] "
-                         "redrawn every round; --steps rounds).  An auxiliary line: no roofline / cpu_baseline objects")
+                    help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096] unless --prefix, "
+                         "k U[1,16] redrawn every round unless --k; --steps rounds).  An auxiliary line: no roofline / "
+                         "cpu_baseline objects")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the NAV pass runs on ONE GPU; --gpus N with N > 1 is not supported")
