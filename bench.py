@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix-core peak of the device
 
 
 def log(*a):
@@ -172,6 +173,45 @@ def batched(args, np, torch, I, nav):
     print(json.dumps(out), flush=True)
 
 
+def prefill(args, np, torch, I, nav):
+    """Prompt ingestion (the step before the pass): n tokens into an empty sequence, which caches
+    n - 1 rows and leaves the last one pending.  No LM head, no decision."""
+    wl = I.WORKLOADS[args.workload]
+    shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
+    n = args.prefill
+    weights = I.make_weights(shape, wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+    model = nav.Model(shape, weights)
+    kv = nav.KVCache(model, 1, (n + 15) // 16 + 2)
+    toks = I.make_tokens(n, shape.vocab, wl["seed"] + I.SEED_PREFIX)
+    times = []
+    for r in range(args.warmup + args.steps):
+        kv.reset(0)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        kv.prefill(0, toks)
+        torch.cuda.synchronize()
+        if r >= args.warmup:
+            times.append(time.perf_counter() - t)
+    total = sum(times)
+    rows = n - 1
+    # 2 flop per weight element and row (layer matrices only) + causal attention: row r scores r + 1
+    # keys and weighs as many values, head_dim multiply-adds each, per query head and layer
+    per_layer = (shape.q_dim + 2 * shape.kv_dim) * shape.d_model + shape.d_model * shape.q_dim + 3 * shape.d_ffn * shape.d_model
+    flop = 2.0 * rows * shape.n_layers * per_layer + 4.0 * shape.n_layers * shape.q_dim * (rows * (rows + 1) / 2)
+    achieved = flop * len(times) / total / 1e12
+    out = {
+        "metric": "prefill_tokens_per_sec", "value": rows * len(times) / total, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / len(times) * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype != I.DTYPE_F32 else "f32", "data": "synthetic",
+        "config": {"workload": f"{shape.name}: ingestion of a {n}-token prompt into an empty sequence, passes of up to "
+                               f"128 rows, paged KV (16-token blocks)"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "all kernels of the call; algorithmic flop (each product counted once, not per bf16 half)"},
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -190,6 +230,9 @@ def main():
                     help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096] unless --prefix, "
                          "k U[1,16] redrawn every round unless --k; --steps rounds).  An auxiliary line: no roofline / "
                          "cpu_baseline objects")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="N > 0: time the ingestion of an N-token prompt instead (pipesd_prefill; --steps prompts).  "
+                         "An auxiliary line: matrix-core roofline of the whole call, no cpu_baseline object")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: the NAV pass runs on ONE GPU; --gpus N with N > 1 is not supported")
@@ -201,6 +244,8 @@ def main():
 
     if args.batch > 0:
         return batched(args, np, torch, I, nav)
+    if args.prefill > 0:
+        return prefill(args, np, torch, I, nav)
     wl = I.WORKLOADS[args.workload]
     shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
     k = args.k or wl["k"]
