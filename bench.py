@@ -137,8 +137,20 @@ def batched(args, np, torch, I, nav):
     esz = 4 if shape.dtype == I.DTYPE_F32 else 2
     w_bytes = shape.n_params_streamed() * esz
     times, ks_sum, rows, alg = [], 0, [], 0.0
+    traces = None
+    if args.trigger:
+        r1, r2 = (float(x) for x in args.trigger.split(","))
+        n_rounds = args.warmup + args.steps
+        traces = []
+        for s in range(n_seq):  # 16 = the longest draft a client sends in this workload
+            lens_s, _ = nav.trigger_rounds(I.make_confidences(16 * n_rounds, seed + 300 + s), r1, r2, 16, cap=n_rounds)
+            assert len(lens_s) == n_rounds
+            traces.append(lens_s)
     for r in range(args.warmup + args.steps):
-        ks = [args.k] * n_seq if args.k else [int(x) for x in rng.integers(1, 17, n_seq)]
+        if traces:
+            ks = [traces[s][r] for s in range(n_seq)]
+        else:
+            ks = [args.k] * n_seq if args.k else [int(x) for x in rng.integers(1, 17, n_seq)]
         drafts, probs, us = [], [], []
         for s in range(n_seq):
             d, q = I.make_independent_drafts(ks[s], shape.vocab, seed + 1000 * r + s, seed + 1000 * r + 500 + s, scale=1.0)
@@ -164,7 +176,8 @@ def batched(args, np, torch, I, nav):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "config": {"workload": f"{shape.name}: {n_seq} clients per call, prefixes "
                                + (f"{args.prefix}" if args.prefix else "U[256,4096]") + ", k "
-                               + (f"{args.k}" if args.k else "U[1,16] redrawn every round")
+                               + (f"from the dual-threshold trigger (R1,R2 = {args.trigger}) on Beta(8,1) confidences"
+                                  if args.trigger else f"{args.k}" if args.k else "U[1,16] redrawn every round")
                                + ", paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
         "hbm_algorithmic_gbps": alg / total / 1e9, "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS,
         "ms_per_step_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)],
@@ -230,6 +243,9 @@ def main():
                     help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096] unless --prefix, "
                          "k U[1,16] redrawn every round unless --k; --steps rounds).  An auxiliary line: no roofline / "
                          "cpu_baseline objects")
+    ap.add_argument("--trigger", default=None,
+                    help="with --batch: R1,R2 - every client's draft lengths come from the dual-threshold trigger "
+                         "(Sec. 3.3) run over a seeded stream of synthetic confidences instead of U[1,16]")
     ap.add_argument("--prefill", type=int, default=0,
                     help="N > 0: time the ingestion of an N-token prompt instead (pipesd_prefill; --steps prompts).  "
                          "An auxiliary line: matrix-core roofline of the whole call, no cpu_baseline object")

@@ -236,6 +236,44 @@ int pipesd_profile_read(pipesd_model *model, int32_t *n_launches, double *total_
  * the device. */
 int pipesd_profile_read_steps(pipesd_model *model, double *us_out, int32_t cap, int32_t *n_steps);
 
+/* ---- Edge-side scheduling of a speculative round: host arithmetic only, no GPU work ----------
+ *
+ * Token batching (Sec. 3.2).  The N draft tokens of a round leave the edge in K batches; B =
+ * (b_1..b_K), 1 = b_1 < .. < b_K <= N, holds the 1-based index of each batch's first token
+ * (Eq. (1)).  Generating one token takes gamma; sending a batch of n tokens takes alpha + beta n
+ * (Eqs. (2), (3)); a batch goes on the link when it has been generated and the batch before it has
+ * been delivered (Eqs. (4), (5)).  All times in one unit of the caller's choice, fp64, >= 0.
+ *
+ * pipesd_batching_time: *time_out = T of Eq. (6), from the start of generation to the delivery of
+ * the last batch, for the batching `first` (host, n_batches entries).  PIPESD_EINVAL: null
+ * pointer, n_tokens < 1, a sequence that breaks Eq. (1), a negative or non-finite cost. */
+int pipesd_batching_time(int32_t n_tokens, const int32_t *first, int32_t n_batches, double alpha,
+                         double beta, double gamma, double *time_out);
+
+/* The batching of minimal T for a scheduling window of n_tokens tokens (Sec. 4.1, Algorithm 1;
+ * optimal by Theorem 1).  Writes the K first-token indices to first_out (host, room for n_tokens
+ * entries), K to *n_batches_out and the minimal T to *time_out; pipesd_batching_time of the
+ * returned batching gives the same T bit for bit.  Where several batchings reach the minimum, the
+ * one whose last batch is longest is returned (and so on towards the front).  Quadratic in n_tokens:
+ * PIPESD_EINVAL above 16384 tokens, for a null pointer, n_tokens < 1, a negative or non-finite
+ * cost; PIPESD_ENOMEM if the tables cannot be allocated. */
+int pipesd_batching_optimal(int32_t n_tokens, double alpha, double beta, double gamma,
+                            int32_t *first_out, int32_t *n_batches_out, double *time_out);
+
+/* Dual-threshold NAV trigger (Sec. 3.3) over a stream of draft-token confidences P(D_1), P(D_2), ..
+ * (host, n values in [0, 1]).  C_1 is the product of the confidences drafted since the last NAV;
+ * token n ends the round when C_1 P(D_n) <= r1 or P(D_n) <= r2, and C_1 returns to 1 after either
+ * (the token that fires belongs to the round it ends).  max_len >= 1 also ends a round that has
+ * reached the longest draft one verification pass takes (not in the paper; pass a value above n to
+ * switch it off).  Writes the draft length of every complete round to lengths_out (host, room for
+ * lengths_cap entries; the walk stops in front of a round that does not fit), their number to
+ * *n_rounds_out and the number of confidences those rounds cover to *consumed_out: the tokens
+ * after them have not fired yet.  PIPESD_EINVAL: null pointer, negative size, max_len < 1, a
+ * threshold or confidence outside [0, 1] (NaN included). */
+int pipesd_trigger_rounds(const double *confidence, int64_t n, double r1, double r2, int32_t max_len,
+                          int32_t *lengths_out, int64_t lengths_cap, int64_t *n_rounds_out,
+                          int64_t *consumed_out);
+
 const char *pipesd_strerror(int status);
 /* Text of the HIP call that made this thread's most recent call return PIPESD_EHIP ("" if none). */
 const char *pipesd_last_hip_error(void);

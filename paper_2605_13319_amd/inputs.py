@@ -205,6 +205,14 @@ def make_noisy_target_drafts(target_logits_after: Callable[[List[int]], np.ndarr
     return np.array(d, dtype=np.int32), q
 
 
+def make_confidences(n: int, seed: int, a: float = 8.0, b: float = 1.0) -> np.ndarray:
+    """Stand-in for the draft model's per-token confidences P(D_n): n draws of Beta(a, b), fp64.
+    With Beta(8, 1), a single-token threshold R2 = 0.3 and a cap of 16 tokens, the dual-threshold
+    trigger of Sec. 3.3 cuts the stream into rounds of mean length 6.5 at R1 = 0.5, 5.1 at R1 = 0.6
+    and 4.4 at R1 = 0.65 (the paper's Table 7 reports mean draft lengths of 3.2 to 5.0)."""
+    return np.random.default_rng(seed).beta(a, b, n)
+
+
 def make_random_probs(rows: int, vocab: int, seed: int, scale: float = 1.0) -> np.ndarray:
     """Rows of a generic categorical distribution, fp32, for feeding the decision step alone."""
     return _softmax_rows_f32(np.float32(scale) * make_noise(rows, vocab, seed))

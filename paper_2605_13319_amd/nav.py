@@ -67,6 +67,12 @@ _SIGS = {
     "pipesd_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_profile_read": (C.c_int, [C.c_void_p, _i32p, C.POINTER(C.c_double)]),
     "pipesd_profile_read_steps": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_int32, _i32p]),
+    "pipesd_batching_time": (C.c_int, [C.c_int32, _i32p, C.c_int32, C.c_double, C.c_double, C.c_double,
+                                       C.POINTER(C.c_double)]),
+    "pipesd_batching_optimal": (C.c_int, [C.c_int32, C.c_double, C.c_double, C.c_double, _i32p, _i32p,
+                                          C.POINTER(C.c_double)]),
+    "pipesd_trigger_rounds": (C.c_int, [C.POINTER(C.c_double), C.c_int64, C.c_double, C.c_double, C.c_int32, _i32p,
+                                        C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
     "pipesd_strerror": (C.c_char_p, [C.c_int]),
     "pipesd_last_hip_error": (C.c_char_p, []),
 }
@@ -102,6 +108,35 @@ def _ptr(a: Optional[np.ndarray], typ):
 
 def _stream() -> int:
     return int(torch.cuda.current_stream().cuda_stream)
+
+
+def batching_time(n_tokens: int, first: Sequence[int], alpha: float, beta: float, gamma: float) -> float:
+    """T of Eq. (6) for the batching `first` (1-based first token of every batch)."""
+    b = _i32(first)
+    t = C.c_double()
+    _check(_lib.pipesd_batching_time(n_tokens, _ptr(b, _i32p), len(b), alpha, beta, gamma, C.byref(t)),
+           "pipesd_batching_time")
+    return t.value
+
+
+def batching_optimal(n_tokens: int, alpha: float, beta: float, gamma: float):
+    """(first, T): the batching of minimal T for a window of n_tokens tokens (Algorithm 1)."""
+    out = np.zeros(max(n_tokens, 1), dtype=np.int32)
+    nb, t = C.c_int32(), C.c_double()
+    _check(_lib.pipesd_batching_optimal(n_tokens, alpha, beta, gamma, _ptr(out, _i32p), C.byref(nb), C.byref(t)),
+           "pipesd_batching_optimal")
+    return tuple(int(x) for x in out[:nb.value]), t.value
+
+
+def trigger_rounds(confidence, r1: float, r2: float, max_len: int, cap: Optional[int] = None):
+    """(lengths, consumed): draft lengths of the rounds the dual-threshold trigger cuts the stream into."""
+    c = np.ascontiguousarray(confidence, dtype=np.float64)
+    cap = len(c) if cap is None else cap
+    out = np.zeros(max(cap, 1), dtype=np.int32)
+    nr, used = C.c_int64(), C.c_int64()
+    _check(_lib.pipesd_trigger_rounds(c.ctypes.data_as(C.POINTER(C.c_double)), len(c), r1, r2, max_len,
+                                      _ptr(out, _i32p), cap, C.byref(nr), C.byref(used)), "pipesd_trigger_rounds")
+    return [int(x) for x in out[:nr.value]], int(used.value)
 
 
 def config_of(shape) -> Config:
