@@ -26,18 +26,26 @@ def nav():
 RAGGED_BF16 = I.ModelShape("ragged-bf16", 2, 512, 8, 2, 64, 1024, 24581)
 
 
-@pytest.mark.parametrize("shape_name,n_seq,rounds", [("tiny", 5, 4), ("small-bf16", 5, 4), ("small-bf16", 16, 12),
-                                                      ("ragged-bf16", 16, 3)])
-def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds):
+# the 8B widths with two layers: the shapes the 16-client workload runs (K = 4096 in 8 slices, the
+# down projection's K = 14336 in 7 x 4, 128256 vocabulary columns) at its prefix lengths
+LLAMA_8B_L2 = I.WORKLOADS["llama-8b"]["shape"].truncated(2)
+
+
+@pytest.mark.parametrize("shape_name,n_seq,rounds,max_prefix", [("tiny", 5, 4, 150), ("small-bf16", 5, 4, 150),
+                                                                 ("small-bf16", 16, 12, 150), ("ragged-bf16", 16, 3, 150),
+                                                                 ("llama-8b-L2", 16, 2, 4096)])
+def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds, max_prefix):
     """bf16: the clients' rows share passes of up to 128 rows (16 clients with k ~ U[1,16] need two);
     a row's results must not depend on what else is in its pass."""
-    shape = {"tiny": I.WORKLOADS["tiny"]["shape"], "small-bf16": SMALL_BF16, "ragged-bf16": RAGGED_BF16}[shape_name]
+    shape = {"tiny": I.WORKLOADS["tiny"]["shape"], "small-bf16": SMALL_BF16, "ragged-bf16": RAGGED_BF16,
+             "llama-8b-L2": LLAMA_8B_L2}[shape_name]
     w = I.make_weights(shape, 9001)
     model = nav.Model(shape, w)
     rng = np.random.default_rng(9002)
-    lens = [int(x) for x in rng.integers(17, 150, n_seq)]
-    kv_b = nav.KVCache(model, max_seqs=n_seq, n_blocks=30 * n_seq)
-    kv_s = nav.KVCache(model, max_seqs=n_seq, n_blocks=30 * n_seq)
+    lens = [int(x) for x in rng.integers(17, max_prefix, n_seq)]
+    per_seq = (max_prefix + 17 * rounds) // 16 + 4
+    kv_b = nav.KVCache(model, max_seqs=n_seq, n_blocks=per_seq * n_seq)
+    kv_s = nav.KVCache(model, max_seqs=n_seq, n_blocks=per_seq * n_seq)
     for s, n in enumerate(lens):
         toks = I.make_tokens(n, shape.vocab, 9100 + s)
         kv_b.prefill(s, toks)
