@@ -136,7 +136,7 @@ def batched(args, np, torch, I, nav):
     log(f"[bench] {n_seq} prefixes ({sum(lens)} tokens) cached in {time.time() - t0:.1f}s")
     esz = 4 if shape.dtype == I.DTYPE_F32 else 2
     w_bytes = shape.n_params_streamed() * esz
-    times, ks_sum, rows, alg = [], 0, [], 0.0
+    times, ks_sum, rows, alg, committed = [], 0, [], 0.0, 0
     traces = None
     if args.trigger:
         r1, r2 = (float(x) for x in args.trigger.split(","))
@@ -166,6 +166,7 @@ def batched(args, np, torch, I, nav):
         if r >= args.warmup:
             times.append(dt)
             ks_sum += sum(ks)
+            committed += sum(a) + n_seq  # every client commits its accepted drafts and one more token
             rows.append(sum(ks) + n_seq)
             # weights once per call; per client the cached K/V read, the new rows written and q read
             alg += w_bytes + sum(shape.algorithmic_bytes(lens[s], ks[s]) - w_bytes for s in range(n_seq))
@@ -179,6 +180,7 @@ def batched(args, np, torch, I, nav):
                                + (f"from the dual-threshold trigger (R1,R2 = {args.trigger}) on Beta(8,1) confidences"
                                   if args.trigger else f"{args.k}" if args.k else "U[1,16] redrawn every round")
                                + ", paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
+        "committed_tokens_per_sec": committed / total,
         "hbm_algorithmic_gbps": alg / total / 1e9, "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS,
         "ms_per_step_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)],
         "roofline": None,
