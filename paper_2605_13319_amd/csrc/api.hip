@@ -117,6 +117,7 @@ static int check_config(const pipesd_config* c) {
 static void model_free(pipesd_model* m) {
   if (!m) return;
   for (void* p : m->owned) (void)hipFree(p);
+  if (m->attn_part) (void)hipFree(m->attn_part);  // (grown on demand, so not in `owned`)
   if (m->result_host) (void)hipHostFree(m->result_host);
   for (auto& e : m->prof_events) {
     (void)hipEventDestroy(e.first);
@@ -470,7 +471,12 @@ struct ProfScope {
     if (!on) return;
     if (m->prof_used == m->prof_events.size()) {
       hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+      if (hipEventCreate(&a) != hipSuccess) {
+        on = false;
+        return;
+      }
+      if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
         on = false;
         return;
       }
@@ -495,7 +501,12 @@ struct ProfGemm {
     if (!on) return;
     if (m->prof_used == m->prof_events.size()) {
       hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+      if (hipEventCreate(&a) != hipSuccess) {
+        on = false;
+        return;
+      }
+      if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
         on = false;
         return;
       }
@@ -1056,7 +1067,7 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
     }
   };
   for (int32_t i = 0; i < 2 * n_seqs; ++i) model->result_host[4 + i] = -1;
-  // bf16: clients are packed, in the order given, into passes of up to 32 rows and 16 clients, so
+  // bf16: clients are packed, in the order given, into passes of up to 128 rows and 16 clients, so
   // that the weights are streamed once per pass instead of once per client (a row's results do not
   // depend on which other rows share its pass); fp32: one pass per client
   const bool pack = model->cfg.dtype == PIPESD_BF16;
