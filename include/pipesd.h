@@ -175,6 +175,22 @@ int pipesd_spec_accept(const float *p, const float *q, const int32_t *draft_toke
                        int32_t vocab, const float *uniforms, int32_t *accepted_len, int32_t *next_token,
                        void *stream);
 
+/* For callers that cannot allocate device memory: code recorded under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The decision step of pipesd_spec_accept with no
+ * allocation, no copy and no synchronisation: the kernels' scratch (4096 bytes: the 64 partial sums
+ * of the integer CDF and the arrival counter) is a static device array inside the library, one copy
+ * per GPU, held until the process ends.
+ *   p, q, draft_tokens, uniforms as for pipesd_spec_accept; result_dev is DEVICE memory, int32[2]:
+ *   {accepted_len, next_token}, valid once the work enqueued on `stream` has completed.
+ * Limits: 1 <= k <= PIPESD_STATIC_MAX_K, 1 <= vocab <= PIPESD_STATIC_MAX_VOCAB; beyond them the call
+ * returns PIPESD_EINVAL and pipesd_last_hip_error() says which limit.  Every call on a GPU uses that
+ * GPU's one scratch array: calls that overlap on one GPU (two streams, two threads) race; calls on
+ * one stream are ordered and safe.  The arrival counter is cleared by a small kernel at the start
+ * of every call, so a graph that records this call records no memset node. */
+enum { PIPESD_STATIC_MAX_K = PIPESD_MAX_ROWS - 1, PIPESD_STATIC_MAX_VOCAB = 1 << 22 };
+int pipesd_spec_accept_static(const float *p, const float *q, const int32_t *draft_tokens, int32_t k,
+                              int32_t vocab, const float *uniforms, int32_t *result_dev, void *stream);
+
 /* Chained rounds on proactively sent drafts (Appendix B: while a round is being verified the edge
  * goes on drafting and sending; the cloud buffers those tokens and keeps them only if the round
  * accepts every draft AND its extra token equals the first buffered token).

@@ -1222,6 +1222,69 @@ extern "C" int pipesd_spec_accept(const float* p, const float* q, const int32_t*
   return PIPESD_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decision step for callers that cannot allocate: the scratch of the decision kernels (64 partial
+// sums of the integer CDF, the arrival counter of its workgroups) lives in a file-scope device
+// array.  The array's name is only a host-side stand-in; its device address is taken once per
+// device with hipGetSymbolAddress and that pointer is what the kernels get.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = 4096;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kStaticMaxDevices = 64;
+static void* g_static_scratch[kStaticMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call on that device)
+static int static_scratch_ptr(char** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "pipesd_spec_accept_static: device index %d beyond %d", dev, kStaticMaxDevices - 1);
+    return PIPESD_EHIP;
+  }
+  if (g_static_scratch[dev] == nullptr) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+    g_static_scratch[dev] = ptr;
+  }
+  *out = (char*)g_static_scratch[dev];
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_spec_accept_static(const float* p, const float* q, const int32_t* draft_tokens, int32_t k,
+                                         int32_t vocab, const float* uniforms, int32_t* result_dev, void* stream) {
+  if (!p || !q || !draft_tokens || !uniforms || !result_dev) return PIPESD_EINVAL;
+  if (k < 1 || k > PIPESD_STATIC_MAX_K || vocab < 1 || vocab > PIPESD_STATIC_MAX_VOCAB) {
+    snprintf(g_hip_msg, sizeof(g_hip_msg),
+             "pipesd_spec_accept_static: k = %d, vocab = %d outside 1..%d drafts, 1..%d tokens (the static scratch is sized for these)",
+             (int)k, (int)vocab, (int)PIPESD_STATIC_MAX_K, (int)PIPESD_STATIC_MAX_VOCAB);
+    return PIPESD_EINVAL;
+  }
+  for (int32_t i = 0; i < k; ++i)
+    if (draft_tokens[i] < 0 || draft_tokens[i] >= vocab) return PIPESD_EINVAL;
+  for (int32_t i = 0; i <= k; ++i)
+    if (!(uniforms[i] >= 0.f && uniforms[i] < 1.f)) return PIPESD_EINVAL;
+  char* sp = nullptr;
+  int rc = static_scratch_ptr(&sp);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  VerifyCall vc{};
+  vc.logits_or_p = const_cast<float*>(p);
+  vc.q = q;
+  vc.k = k;
+  vc.V = vocab;
+  for (int32_t i = 0; i < k; ++i) vc.drafts.tok[i] = draft_tokens[i];
+  for (int32_t i = 0; i <= k; ++i) vc.u[i] = uniforms[i];
+  vc.scan_partial = (unsigned long long*)sp;  // 64 x 8 bytes
+  vc.counter = (unsigned*)(sp + 1024);
+  vc.result = result_dev;
+  // the counter must start at zero whatever the call before left (a fill kernel, not a memset node:
+  // the caller may be recording a graph)
+  HIP_TRY(launch_clear_words(vc.counter, 1, st));
+  HIP_TRY(launch_spec_accept(vc, st));
+  return PIPESD_OK;
+}
+
 extern "C" int pipesd_kv_read(const pipesd_model* model, const pipesd_kv* kv, int32_t seq, int32_t layer, int32_t pos,
                               float* k_out, float* v_out) {
   if (!model || !kv || !k_out || !v_out || !seq_ok(kv, seq) || kv->model != model) return PIPESD_EINVAL;

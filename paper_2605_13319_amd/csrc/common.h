@@ -302,5 +302,7 @@ hipError_t launch_kv_trim(int dtype, const KvView& kv, int n_layers, int first_p
                           hipStream_t st);
 
 hipError_t launch_set_table(int32_t* table, int first, const int32_t* entries, int n, hipStream_t st);
+// words[0..n-1] = 0 by a small kernel (usable where a memset node is not: under graph capture)
+hipError_t launch_clear_words(unsigned* words, int n, hipStream_t st);
 
 }  // namespace pipesd

@@ -262,4 +262,14 @@ hipError_t launch_set_table(int32_t* table, int first, const int32_t* entries, i
   return hipSuccess;
 }
 
+__global__ void clear_words_kernel(unsigned* words, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) words[i] = 0u;
+}
+
+hipError_t launch_clear_words(unsigned* words, int n, hipStream_t st) {
+  if (n < 1) return hipSuccess;
+  clear_words_kernel<<<1, 64, 0, st>>>(words, n);
+  return hipGetLastError();
+}
+
 }  // namespace pipesd

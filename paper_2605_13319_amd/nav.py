@@ -58,6 +58,8 @@ _SIGS = {
     "pipesd_forward_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, _f32p, C.c_void_p]),
     "pipesd_spec_accept": (C.c_int, [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_int32, _f32p, _i32p, _i32p,
                                      C.c_void_p]),
+    "pipesd_spec_accept_static": (C.c_int, [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_int32, _f32p, C.c_void_p,
+                                            C.c_void_p]),
     "pipesd_kv_read": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _f32p, _f32p]),
     "pipesd_nav_verify_chain": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, _i32p,
                                           C.POINTER(C.c_void_p), _f32p, _i32p, _i32p, _i32p, C.c_void_p]),
@@ -392,3 +394,17 @@ def spec_accept(p, q, drafts: Sequence[int], uniforms) -> tuple:
     _check(_lib.pipesd_spec_accept(p.data_ptr(), q.data_ptr(), _ptr(d, _i32p), k, vocab, _ptr(u, _f32p), C.byref(a),
                                    C.byref(n), _stream()), "pipesd_spec_accept")
     return a.value, n.value
+
+
+def spec_accept_static(p, q, drafts: Sequence[int], uniforms, result) -> None:
+    """The decision step through the entry point that allocates nothing: enqueues the work on the
+    current stream and returns; `result` (torch CUDA int32 tensor of 2) holds {accepted_len,
+    next_token} once the stream has been synchronised."""
+    d = _i32(drafts)
+    u = _f32(uniforms)
+    k = len(d)
+    vocab = p.shape[-1]
+    assert p.is_contiguous() and q.is_contiguous() and p.shape[0] == k + 1 and q.shape[0] == k
+    assert result.dtype == torch.int32 and result.numel() >= 2 and result.is_cuda
+    _check(_lib.pipesd_spec_accept_static(p.data_ptr(), q.data_ptr(), _ptr(d, _i32p), k, vocab, _ptr(u, _f32p),
+                                          result.data_ptr(), _stream()), "pipesd_spec_accept_static")
