@@ -12,7 +12,9 @@ numpy arrays.
 Precision: fp32 arrays throughout (weights stored as bf16 are widened exactly), which is the
 precision the decision step is defined in; matmuls are numpy's.  The KV cache is part of the
 state's definition: a bf16 model keeps its keys and values in bf16, so the checker rounds them
-on append exactly as any bf16 cache must, and reads the rounded values.
+on append exactly as any bf16 cache must, and reads the rounded values.  OracleModel(...,
+kv_format="fp32") switches that rounding off: the checker is then fp32 throughout, and the GPU
+tests report the bf16 path's distance from it as well.
 
 Pins (tests/test_oracle_*.py): row block == sequential single-token forwards; greedy ==
 longest argmax-matching prefix; exact output law == target law on tiny vocabularies, measured

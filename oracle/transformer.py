@@ -62,9 +62,16 @@ def silu(t: np.ndarray) -> np.ndarray:
 
 
 class OracleModel:
-    def __init__(self, shape, weights):
+    """kv_format selects what the cache holds.  "model" (default): the model's storage type, i.e. a
+    bf16 model keeps keys and values rounded to bf16 (the cache is part of the sequence's state and
+    has a format).  "fp32": keys and values stay fp32 whatever the model's storage type; with it the
+    checker is fp32 throughout, which is the yardstick for how far a bf16 cache moves the logits."""
+
+    def __init__(self, shape, weights, kv_format: str = "model"):
+        assert kv_format in ("model", "fp32")
         self.s = shape
         self.w = weights
+        self.kv_bf16 = kv_format == "model" and shape.dtype == 1
 
     def forward_rows(self, tokens, start_pos: int, K: list, V: list) -> np.ndarray:
         """Rows r = 0..m-1 carry `tokens[r]` at position start_pos + r.  K[l], V[l] are
@@ -88,8 +95,8 @@ class OracleModel:
             v = (h @ widen(w["wv"][l]).T).reshape(m, s.n_kv_heads, s.head_dim)
             q = rope(q, cos, sin)
             k = rope(k, cos, sin)
-            K[l][start_pos:start_pos + m] = to_cache_format(k, s.dtype == 1)
-            V[l][start_pos:start_pos + m] = to_cache_format(v, s.dtype == 1)
+            K[l][start_pos:start_pos + m] = to_cache_format(k, self.kv_bf16)
+            V[l][start_pos:start_pos + m] = to_cache_format(v, self.kv_bf16)
             o = np.empty((m, s.n_q_heads, s.head_dim), dtype=F32)
             for g in range(s.n_q_heads):
                 kvh = g // group

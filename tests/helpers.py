@@ -6,8 +6,8 @@ from oracle.transformer import OracleModel
 from paper_2605_13319_amd import inputs as I
 
 
-def oracle_side(shape, weights, prefix_tokens, max_len):
-    om = OracleModel(shape, weights)
+def oracle_side(shape, weights, prefix_tokens, max_len, kv_format="model"):
+    om = OracleModel(shape, weights, kv_format=kv_format)
     seq = OracleSeq(om, max_len)
     seq.prefill(prefix_tokens)
     return seq

@@ -57,9 +57,12 @@ def test_causality_future_rows_do_not_change_earlier_logits():
     assert np.abs(z1[8:] - z2[8:]).max() > 1e-3
 
 
-def _torch_forward(shape, w, tokens):
+def _torch_forward(shape, w, tokens, bf16_cache=None):
     """The same model re-stated with torch.nn.functional primitives, fp64, rotary positions
-    as complex multiplication.  Shares nothing with the checker but the weights."""
+    as complex multiplication.  Shares nothing with the checker but the weights.
+    bf16_cache: whether keys and values are rounded to bf16 (default: iff the model is bf16)."""
+    if bf16_cache is None:
+        bf16_cache = shape.dtype == I.DTYPE_BF16
     t = lambda a: torch.from_numpy(np.array(widen(a), dtype=np.float64))
     n = len(tokens)
     x = Fn.embedding(torch.as_tensor(np.asarray(tokens, dtype=np.int64)), t(w["tok_emb"]))
@@ -79,7 +82,7 @@ def _torch_forward(shape, w, tokens):
         q = rotary(Fn.linear(h, t(w["wq"][l])).view(n, shape.n_q_heads, shape.head_dim))
         k = rotary(Fn.linear(h, t(w["wk"][l])).view(n, shape.n_kv_heads, shape.head_dim))
         v = Fn.linear(h, t(w["wv"][l])).view(n, shape.n_kv_heads, shape.head_dim)
-        if shape.dtype == I.DTYPE_BF16:  # a bf16 model keeps its cache in bf16
+        if bf16_cache:  # a bf16 model keeps its cache in bf16
             k = k.to(torch.float32).to(torch.bfloat16).to(torch.float64)
             v = v.to(torch.float32).to(torch.bfloat16).to(torch.float64)
         k = k.repeat_interleave(rep, dim=1)
@@ -104,6 +107,76 @@ def test_forward_matches_torch_restatement(shape):
     # two computations (fp32 here, fp64 there), which moves logits by ~1e-4; mistakes move them by O(1)
     tol = 2e-5 if shape.dtype == I.DTYPE_F32 else 2e-4
     assert np.abs(z - zt).max() < tol * max(1.0, np.abs(zt).max())
+
+
+def test_fp32_cache_switch_is_fp32_throughout():
+    """kv_format="fp32" on a bf16 model: no rounding anywhere after the weights, so the checker meets
+    the un-rounded fp64 restatement at the fp32 bar, and differs from its own bf16-cache run by the
+    cache rounding (visible, but small on this shape)."""
+    shape = SMALL_BF16
+    m16 = _model(shape)
+    m32 = OracleModel(shape, m16.w, kv_format="fp32")
+    toks = I.make_tokens(19, shape.vocab, 3)
+    s16, s32 = OracleSeq(m16, 32), OracleSeq(m32, 32)
+    z16 = m16.forward_rows(toks, 0, s16.K, s16.V)
+    z32 = m32.forward_rows(toks, 0, s32.K, s32.V)
+    zt = _torch_forward(shape, m16.w, toks, bf16_cache=False)
+    assert np.abs(z32 - zt).max() < 2e-5 * max(1.0, np.abs(zt).max())
+    gap = float(np.abs(z16 - z32).max())
+    assert 1e-5 < gap < 5e-2, gap
+    # the cache itself: fp32 run keeps more than 8 significand bits, the bf16 run exactly 8
+    k32, k16 = s32.K[0][:18].view(np.uint32), s16.K[0][:18].view(np.uint32)
+    assert (k32 & 0xFFFF).any() and not (k16 & 0xFFFF).any()
+    # an fp32 model ignores the switch
+    mf = _model(SMALL)
+    mf2 = OracleModel(SMALL, mf.w, kv_format="fp32")
+    a, b = OracleSeq(mf, 32), OracleSeq(mf2, 32)
+    np.testing.assert_array_equal(mf.forward_rows(toks, 0, a.K, a.V), mf2.forward_rows(toks, 0, b.K, b.V))
+
+
+def test_cache_format_is_bf16_round_to_nearest_even_bit_for_bit():
+    """to_cache_format against the format's definition on hand-picked patterns (ties go to the even
+    8-bit significand, subnormals, infinities, the largest finite value rounding up to infinity) and
+    against torch's independent float32 -> bfloat16 conversion on 10^6 random bit patterns."""
+    from oracle.transformer import to_cache_format
+
+    def bits(u):
+        return np.array(u, dtype=np.uint32).view(F32)
+
+    cases = {  # fp32 bits -> expected bf16 bits (upper half of the fp32 word)
+        0x3F800000: 0x3F80,  # 1.0 exactly
+        0x3F808000: 0x3F80,  # 1 + 2^-8: tie, even neighbour is 1.0
+        0x3F818000: 0x3F82,  # 1 + 3*2^-8: tie, even neighbour is 1 + 2^-6
+        0x3F808001: 0x3F81,  # just above the tie: up
+        0x3F807FFF: 0x3F80,  # just below the tie: down
+        0xBF808000: 0xBF80,  # the same tie, negative
+        0xBF818000: 0xBF82,
+        0x00000001: 0x0000,  # smallest fp32 subnormal -> +0
+        0x00008000: 0x0000,  # subnormal tie between 0 and the smallest bf16 subnormal: even is 0
+        0x00018000: 0x0002,  # subnormal tie, even neighbour above
+        0x00008001: 0x0001,  # above the tie: smallest bf16 subnormal
+        0x80008001: 0x8001,
+        0x007F8000: 0x0080,  # largest-subnormal region tie rounds into the smallest normal
+        0x7F7FFFFF: 0x7F80,  # largest finite fp32 rounds to +inf
+        0x7F7F7FFF: 0x7F7F,  # just below the tie under the largest bf16
+        0x7F800000: 0x7F80,  # +inf
+        0xFF800000: 0xFF80,  # -inf
+        0x00000000: 0x0000,
+        0x80000000: 0x8000,  # -0 keeps its sign
+    }
+    src = bits(list(cases.keys()))
+    got = to_cache_format(src, True).view(np.uint32)
+    want = np.array([v << 16 for v in cases.values()], dtype=np.uint32)
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(to_cache_format(src, False).view(np.uint32), src.view(np.uint32))  # fp32: untouched
+    rng = np.random.default_rng(123)
+    raw = rng.integers(0, 2 ** 32, 1_000_000, dtype=np.uint64).astype(np.uint32)
+    raw = raw[(raw & 0x7F800000) != 0x7F800000]  # finite values and both zeros; inf covered above, NaN never cached
+    x = raw.view(F32)
+    ref = torch.from_numpy(x.copy()).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(to_cache_format(x, True).view(np.uint32), ref.view(np.uint32))
+    # shape is kept
+    assert to_cache_format(np.zeros((3, 2, 4), F32), True).shape == (3, 2, 4)
 
 
 def test_gqa_with_repeated_kv_heads_equals_mha():
