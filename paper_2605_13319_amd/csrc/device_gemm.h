@@ -37,6 +37,8 @@
 // in the writer's caches.  Weights, gains and rotary tables are immutable.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace pipesd {
@@ -164,6 +166,14 @@ __device__ __forceinline__ void chunk_mfma(u32x4 (&af)[KSTEPS], const u32x4 (&bh
     }
     if constexpr (HAS_NEXT) af[KS] = stream_load<NT>(nxt + KS * 64);
     chunk_mfma<MT, KSTEPS, NT, HAS_NEXT, KS + 1>(af, bhi, blo, acc, nxt);
+  } else {
+    // The matrix cores deliver a product many cycles after issue and nothing but software keeps a
+    // later reader of the accumulator away until then.  The compiler pads for that inside a basic
+    // block, but the reader (the LDS store of the tile) may sit behind a block boundary where it was
+    // seen to pad too little: the store then wrote what the registers held before.  So the padding
+    // for the slowest product (16 passes: 19 wait states) is spelled out here, tied to the accumulators.
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[mt]));
   }
 }
 
@@ -176,12 +186,16 @@ __device__ __forceinline__ f32x4 shfl4(f32x4 v, int src) {
 // apart and the two halves of an 8-column group 16 lanes apart, so pairs are joined by shuffles.
 // Every lane of the wave must call this (rows beyond the pass only skip the stores).
 // RESID: `pre` says that pre_res / pre_gain already hold this quad's residual and gain values.
-template <bool CO>
+// EPI: the epilogue as a compile-time constant (the per-projection kernels: only that epilogue's code
+// and registers are in the kernel), or kEpiAny to pick by a.epi at run time (kernels that run several
+// kinds of products).
+constexpr int kEpiAny = -1;
+template <bool CO, int EPI = kEpiAny>
 __device__ __forceinline__ void epilogue_quad(const GemmArgs& a, int t, int row, int lane, f32x4 v, float rstd,
                                               bool pre, f32x4 pre_res, f32x4 pre_gain) {
   const int gg = lane >> 4;
   const bool live = row < a.m;
-  switch (a.epi) {
+  switch (EPI == kEpiAny ? a.epi : EPI) {
     case EPI_STORE: {  // logits: read by later kernels only
       if (!live) break;
       float* o = a.out + (size_t)row * a.ldo + t * 16 + gg * 4;
@@ -325,9 +339,12 @@ __host__ __device__ inline size_t gemm_lds_floats(int tg, int W, int MT, int tea
   return (size_t)teams_per_wg * tg * W * MT * 64 * 4 + 32;
 }
 
-// The GEMM proper.  `af` must hold the in-flight first chunk (gemm_prefetch).  All waves of the
-// workgroup must call this together (it contains workgroup barriers).
-template <int MT, int KSTEPS, bool CO, bool NT = true>
+// The GEMM proper.  All waves of the workgroup must call this together (it contains workgroup
+// barriers).  EPI == kEpiAny (a kernel that runs several kinds of products): `af` must hold the
+// in-flight first chunk (gemm_prefetch), the epilogue and the phase count are read from `a`.
+// Otherwise (one kernel per kind of product) the body requests the first chunk itself, P1 says at
+// compile time that a.P == 1, and the sums of squares are read iff the epilogue is not the residual one.
+template <int MT, int KSTEPS, bool CO, bool NT = true, int EPI = kEpiAny, bool P1 = false>
 __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, int teams_per_wg, int nwaves_wg,
                                           float* lds, u32x4 (&af)[KSTEPS]) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -381,11 +398,13 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
                        : "v"(a.ssq_in + (size_t)(tp.row_base + row) * a.ssq_stride + j));
       }
   };
-  auto ssq_finish = [&](int row0) {
+  // `younger` = a constant number of hand-issued loads requested after the sums (they may stay in flight)
+  auto ssq_finish = [&](int row0, auto younger) {
 #pragma unroll
     for (int r2 = 0; r2 < 2; ++r2)
 #pragma unroll
-      for (int j4 = 0; j4 < kSsqPerLane; ++j4) asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[r2][j4]));
+      for (int j4 = 0; j4 < kSsqPerLane; ++j4)
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(part[r2][j4]) : "n"(decltype(younger)::value));
 #pragma unroll
     for (int r2 = 0; r2 < 2; ++r2) {
       const int row = row0 + r2 * nwaves_wg;
@@ -398,31 +417,73 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
     }
   };
   // residual epilogue: residual and gain values of the first quad this lane will finish
-  // (ordinary loads: the compiler's own wait precedes whatever it does with the registers)
   f32x4 pre_res = f32x4{0.f, 0.f, 0.f, 0.f}, pre_gain = pre_res;
   bool have_pre = false;
-  if (working && a.epi == EPI_RESID) {
-    const int t0 = tp.team * a.tg, e_first = tp.wt * 64 + lane;
-    if (e_first < min(a.tg, a.ntiles - t0) * MT * 64) {
-      const int tt = e_first / (MT * 64), rem = e_first % (MT * 64), l = rem & 63;
-      const int row = tp.row_base + (rem >> 6) * 16 + (l & 15), col = (t0 + tt) * 16 + (l >> 4) * 4;
-      if (row < a.m) pre_res = *(const f32x4*)(a.res_in + (size_t)row * a.ldo + col);
+  typedef std::integral_constant<int, 0> none_younger;
+  if constexpr (EPI == kEpiAny) {
+    // (ordinary loads: the compiler's own wait precedes whatever it does with the registers)
+    if (working && a.epi == EPI_RESID) {
+      const int t0 = tp.team * a.tg, e_first = tp.wt * 64 + lane;
+      if (e_first < min(a.tg, a.ntiles - t0) * MT * 64) {
+        const int tt = e_first / (MT * 64), rem = e_first % (MT * 64), l = rem & 63;
+        const int row = tp.row_base + (rem >> 6) * 16 + (l & 15), col = (t0 + tt) * 16 + (l >> 4) * 4;
+        if (row < a.m) pre_res = *(const f32x4*)(a.res_in + (size_t)row * a.ldo + col);
+        pre_gain = *(const f32x4*)(a.gain_next + col);
+        have_pre = true;
+      }
+    }
+    ssq_request(w);
+    if (working && a.P == 1) {
+      request_act(tp.wt, 0, bhi);
+      request_act(tp.wt, 1, blo);
+      await_act();
+    }
+    ssq_finish(w, none_younger{});
+    if (norm)
+      for (int row0 = w + 2 * nwaves_wg; row0 < MT * 16; row0 += 2 * nwaves_wg) {
+        ssq_request(row0);
+        ssq_finish(row0, none_younger{});
+      }
+  } else {
+    // Everything the step before left for this one is requested first (sums of squares, residual
+    // operands), then the first weight chunk, then the activation fragments, all without a wait in
+    // between; the sums are awaited alone and folded while weights and fragments are on their way.
+    // Every wave issues the same hand-issued loads (a workgroup beyond the last tile group, which
+    // only a padded grid has, requests the last group's chunk and never uses it), so the number of
+    // loads younger than the sums is a constant.
+    constexpr bool NORM = EPI != EPI_RESID;
+    const int g0 = min(tp.team, ngroups - 1);
+    if constexpr (NORM) ssq_request(w);
+    if constexpr (EPI == EPI_RESID) {
+      // unconditional loads at clamped indices: no branch, hence no join at which the compiler would
+      // have to wait for them (a wait there would also drain the weight requests behind them)
+      const int t0 = g0 * a.tg, nq = min(a.tg, a.ntiles - t0) * MT * 64, e_first = tp.wt * 64 + lane;
+      const int e = min(e_first, nq - 1);
+      const int tt = e / (MT * 64), rem = e % (MT * 64), l = rem & 63;
+      const int row = min(tp.row_base + (rem >> 6) * 16 + (l & 15), a.m - 1), col = (t0 + tt) * 16 + (l >> 4) * 4;
+      pre_res = *(const f32x4*)(a.res_in + (size_t)row * a.ldo + col);
       pre_gain = *(const f32x4*)(a.gain_next + col);
-      have_pre = true;
+      have_pre = working && e_first < nq;
     }
-  }
-  ssq_request(w);
-  if (working && a.P == 1) {
-    request_act(tp.wt, 0, bhi);
-    request_act(tp.wt, 1, blo);
-    await_act();
-  }
-  ssq_finish(w);
-  if (norm)
-    for (int row0 = w + 2 * nwaves_wg; row0 < MT * 16; row0 += 2 * nwaves_wg) {
-      ssq_request(row0);
-      ssq_finish(row0);
+    {
+      const u32x4* first = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, g0 * a.tg, 0);
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load<NT>(first + ks * 64);
     }
+    if constexpr (P1) {
+      request_act(tp.wt, 0, bhi);
+      request_act(tp.wt, 1, blo);
+    }
+    if constexpr (NORM) {
+      ssq_finish(w, std::integral_constant<int, KSTEPS + (P1 ? 2 * KSTEPS * MT : 0)>{});
+      if (tp.row_base + 2 * nwaves_wg < a.m)  // (few waves and many rows: the remaining rows, awaited in full)
+        for (int row0 = w + 2 * nwaves_wg; row0 < MT * 16; row0 += 2 * nwaves_wg) {
+          ssq_request(row0);
+          ssq_finish(row0, none_younger{});
+        }
+    }
+    if constexpr (P1) await_act();
+  }
   for (int it = 0; it < iters; ++it) {
     const int grp = tp.team + it * tp.nteams;
     const bool on = tp.active && grp < ngroups;
@@ -431,8 +492,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
     const int e_first = tp.wt * 64 + lane;
     const bool pre = it == 0 && have_pre;
     if (on) {
-      for (int p = 0; p < a.P; ++p) {
-        if (a.P > 1) {
+      const int nphase = (EPI != kEpiAny && P1) ? 1 : a.P;
+      for (int p = 0; p < nphase; ++p) {
+        if ((EPI == kEpiAny || !P1) && a.P > 1) {
           request_act(p * a.W + tp.wt, 0, bhi);
           request_act(p * a.W + tp.wt, 1, blo);
           await_act();
@@ -440,7 +502,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         for (int t = 0; t < nt_g; ++t) {
           const u32x4* nxt = nullptr;
           if (t + 1 < nt_g) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0 + t + 1, p);
-          else if (p + 1 < a.P) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0, p + 1);
+          else if (p + 1 < nphase) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, t0, p + 1);
           else if (grp + tp.nteams < ngroups) nxt = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, (grp + tp.nteams) * a.tg, 0);
           f32x4 acc[MT];
 #pragma unroll
@@ -468,7 +530,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         for (int ww = 0; ww < a.W; ++ww) v += red[((size_t)(tt * a.W + ww) * MT + mt) * 64 + l];
         const int lrow = mt * 16 + (l & 15), row = tp.row_base + lrow;
         const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[lrow] : 1.0f;
-        epilogue_quad<CO>(a, t0 + tt, row, l, v, rstd, pre && e == e_first, pre_res, pre_gain);
+        epilogue_quad<CO, EPI>(a, t0 + tt, row, l, v, rstd, pre && e == e_first, pre_res, pre_gain);
       }
     }
     __syncthreads();  // red is free again

@@ -3,11 +3,16 @@
 // device_gemm.h.
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "device_gemm.h"
 
 namespace pipesd {
 
-template <int KSTEPS, bool NT>
+// EPI (the projection's epilogue) is a template parameter: every projection of a layer is a kernel
+// of its own name, with only its own epilogue's code and registers.
+// and P1 says that every wave has a single K slice (no phases).
+template <int KSTEPS, bool NT, int EPI, bool P1>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ float lds[];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -19,8 +24,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   TeamPos tp{(b / (8 * rt)) * 8 + (b & 7), (int)gridDim.x / rt, w, 0, true};
   tp.row_base = ((b >> 3) % rt) * 16;
   u32x4 af[KSTEPS];
-  gemm_prefetch<KSTEPS, NT>(a, tp, lane, af);
-  gemm_body<1, KSTEPS, false, NT>(a, tp, 1, a.W, lds, af);
+  gemm_body<1, KSTEPS, false, NT, EPI, P1>(a, tp, 1, a.W, lds, af);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -109,19 +113,35 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
     return launch_gemm_wide(c, a, st);
   const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);
   const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;
-  if (row_tiles == 1) {
+  auto launch = [&](auto kernel) {
     if (timed)
-      hipExtLaunchKernelGGL((gemm_bf16_kernel<16, true>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
-                            c.ev_stop, 0, a);
+      hipExtLaunchKernelGGL(kernel, dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start, c.ev_stop, 0, a);
     else
-      gemm_bf16_kernel<16, true><<<p.grid, p.W * 64, lds, st>>>(a);
-  } else {
-    if (timed)
-      hipExtLaunchKernelGGL((gemm_bf16_kernel<16, false>), dim3(p.grid), dim3(p.W * 64), (uint32_t)lds, st, c.ev_start,
-                            c.ev_stop, 0, a);
+      kernel<<<p.grid, p.W * 64, lds, st>>>(a);
+  };
+  auto launch_p = [&](auto nt, auto p1) {
+    constexpr bool NT = decltype(nt)::value, P1 = decltype(p1)::value;
+    switch (c.epi) {
+      case EPI_STORE: launch(gemm_bf16_kernel<16, NT, EPI_STORE, P1>); break;
+      case EPI_RESID: launch(gemm_bf16_kernel<16, NT, EPI_RESID, P1>); break;
+      case EPI_SWIGLU: launch(gemm_bf16_kernel<16, NT, EPI_SWIGLU, P1>); break;
+      default: launch(gemm_bf16_kernel<16, NT, EPI_QKV, P1>); break;
+    }
+  };
+  auto launch_nt = [&](auto nt) {
+    if (p.P == 1)
+      launch_p(nt, std::true_type{});
     else
-      gemm_bf16_kernel<16, false><<<p.grid, p.W * 64, lds, st>>>(a);
-  }
+      launch_p(nt, std::false_type{});
+  };
+  if (c.epi < EPI_STORE || c.epi > EPI_QKV) return hipErrorInvalidValue;
+  // the residual epilogue is the one without a fused norm in front of it (compile-time knowledge of the kernels)
+  if ((c.ssq_in != nullptr) != (c.epi != EPI_RESID)) return hipErrorInvalidValue;
+  if (c.ssq_in != nullptr && c.ssq_parts > 64 * kSsqPerLane) return hipErrorInvalidValue;
+  if (row_tiles == 1)
+    launch_nt(std::true_type{});
+  else
+    launch_nt(std::false_type{});
   return hipGetLastError();
 }
 

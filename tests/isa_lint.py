@@ -105,8 +105,81 @@ def check(path):
         total += len(report)
     print(path, "suspicious:", total)
     return total
+# ---------------------------------------------------------------------------------------------
+# Second check: results of the matrix cores read too early across a basic-block boundary.
+# A v_mfma delivers its destination registers many cycles after issue and only software (wait
+# states: independent instructions or s_nop) keeps a later reader away.  The compiler pads for that
+# inside a basic block; behind a block boundary it was seen to pad too little (an LDS store of an
+# accumulator right after a branch target stored what the registers held before).  Flagged: a
+# non-MFMA instruction in ANOTHER block than the v_mfma that touches its destination after fewer than
+# MFMA_WAIT_STATES wait states on some path (every instruction counts one, s_nop N counts N + 1).
+MFMA_WAIT_STATES = 18  # the slowest shape (16 passes) needs 18; the 16x16x32 products here need fewer
+def _states(op, rest):
+    if op == 's_nop':
+        try: return int(rest.strip(), 0) + 1
+        except ValueError: return 1
+    return 1
+def _touched(rest):
+    t = frozenset()
+    for o in rest.split(','): t |= regs(o)
+    return t
+def check_mfma(path):
+    raw = open(path).read().split('\n')
+    funcs = []; cur = []; name = None
+    for i, ln in enumerate(raw):
+        m = re.match(r'^([A-Za-z_][\w$.]*):', ln)
+        if m and not ln.startswith('.L'):
+            if cur: funcs.append((name, cur))
+            name = m.group(1); cur = []
+        cur.append((i + 1, ln))
+    if cur: funcs.append((name, cur))
+    total = 0
+    for name, lines in funcs:
+        if name is None: continue
+        blocks = parse_function(lines)
+        if not blocks: continue
+        idx = {b['label']: k for k, b in enumerate(blocks) if b['label']}
+        def succs(k):
+            out = []
+            for sname in blocks[k]['succ']:
+                j = k + 1 if sname == '+1' else idx.get(sname)
+                if j is not None and j < len(blocks): out.append(j)
+            return out
+        report = set()
+        for k, blk in enumerate(blocks):
+            ins = blk['ins']
+            for i, (no, in_asm, op, rest) in enumerate(ins):
+                if not op.startswith('v_mfma'): continue
+                dst = regs(rest.split(',')[0])
+                # rest of the own block: the compiler's own padding is trusted there
+                count = 0; alive = True
+                for (no2, _, op2, rest2) in ins[i + 1:]:
+                    if _touched(rest2) & dst: alive = False; break
+                    count += _states(op2, rest2)
+                if not alive or count >= MFMA_WAIT_STATES: continue
+                work = [(j, count) for j in succs(k)]; seen = {}
+                while work:
+                    j, c = work.pop()
+                    if seen.get(j, 1 << 30) <= c: continue
+                    seen[j] = c
+                    stop = False
+                    for (no2, _, op2, rest2) in blocks[j]['ins']:
+                        if c >= MFMA_WAIT_STATES: stop = True; break
+                        if _touched(rest2) & dst:
+                            if not op2.startswith('v_mfma'):
+                                report.add((no2, op2 + ' ' + rest2.strip(), no, c))
+                            stop = True; break
+                        c += _states(op2, rest2)
+                    if not stop and c < MFMA_WAIT_STATES:
+                        work.extend((jj, c) for jj in succs(j))
+        for no2, txt, no, c in sorted(report):
+            print(f"{path}:{no2}: '{txt}' touches the result of the v_mfma of line {no} after {c} wait states  [{name}]")
+        total += len(report)
+    print(path, "early reads of matrix-core results:", total)
+    return total
 if __name__ == "__main__":
     rc = 0
     for p in sys.argv[1:]:
         rc |= 1 if check(p) else 0
+        rc |= 1 if check_mfma(p) else 0
     sys.exit(rc)
