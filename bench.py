@@ -117,18 +117,16 @@ def cpu_baseline(shape, weights, prefix, k, layers):
                       f"per-layer time x {shape.n_layers} + head/decision time; median of 3"}
 
 
-def batched(args, np, torch, I, nav):
-    """Several clients per call (the multi-client setting of Appendix I): every round each client
-    brings k ~ U[1,16] drafts; the clients' rows share passes of up to 128 rows."""
-    wl = I.WORKLOADS[args.workload]
-    shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
-    seed = wl["seed"] + 1000
-    n_seq = args.batch
-    weights = I.make_weights(shape, wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
-    model = nav.Model(shape, weights)
-    rng = np.random.default_rng(seed + I.SEED_LENGTHS)
-    lens = [args.prefix] * n_seq if args.prefix else [int(x) for x in rng.integers(256, 4097, n_seq)]
-    kv = nav.KVCache(model, n_seq, sum((n + 64) // 16 + 2 for n in lens))
+def run_batched(np, torch, I, nav, model, shape, seed, lens, rounds, warmup, sigma, k_of, grow=True):
+    """Several clients per call (the multi-client setting of Appendix I) on a model that is already
+    on the device: client s starts from a prefix of lens[s] tokens; every round it brings k_of(round,
+    s) drafts with q_i = softmax(target logits + sigma N(0,1)), d_i ~ q_i (the target logits are the
+    library's own: draft generation is outside the timed region), all clients are verified by ONE
+    pipesd_nav_verify_batch call, and (grow) the sequences keep what the call committed, so they grow
+    by accepted + 1 tokens per round.  Returns the timing record of the `rounds` timed calls."""
+    n_seq = len(lens)
+    lens = list(lens)
+    kv = nav.KVCache(model, n_seq, sum((n + 17 * (rounds + warmup) + 64) // 16 + 2 for n in lens))
     t0 = time.time()
     for s, n in enumerate(lens):
         kv.prefill(s, I.make_tokens(n, shape.vocab, seed + 100 + s))
@@ -137,23 +135,16 @@ def batched(args, np, torch, I, nav):
     esz = 4 if shape.dtype == I.DTYPE_F32 else 2
     w_bytes = shape.n_params_streamed() * esz
     times, ks_sum, rows, alg, committed = [], 0, [], 0.0, 0
-    traces = None
-    if args.trigger:
-        r1, r2 = (float(x) for x in args.trigger.split(","))
-        n_rounds = args.warmup + args.steps
-        traces = []
-        for s in range(n_seq):  # 16 = the longest draft a client sends in this workload
-            lens_s, _ = nav.trigger_rounds(I.make_confidences(16 * n_rounds, seed + 300 + s), r1, r2, 16, cap=n_rounds)
-            assert len(lens_s) == n_rounds
-            traces.append(lens_s)
-    for r in range(args.warmup + args.steps):
-        if traces:
-            ks = [traces[s][r] for s in range(n_seq)]
-        else:
-            ks = [args.k] * n_seq if args.k else [int(x) for x in rng.integers(1, 17, n_seq)]
+    start_lens = list(lens)
+    for r in range(warmup + rounds):
+        ks = [k_of(r, s) for s in range(n_seq)]
         drafts, probs, us = [], [], []
         for s in range(n_seq):
-            d, q = I.make_independent_drafts(ks[s], shape.vocab, seed + 1000 * r + s, seed + 1000 * r + 500 + s, scale=1.0)
+            if sigma is None:
+                d, q = I.make_independent_drafts(ks[s], shape.vocab, seed + 1000 * r + s, seed + 1000 * r + 500 + s, scale=1.0)
+            else:
+                d, q = I.make_noisy_target_drafts(lambda ds, s=s: kv.forward_logits(s, ds)[-1], ks[s], shape.vocab, sigma,
+                                                  seed + 1000 * r + s, seed + 1000 * r + 500 + s)
             drafts.append([int(t) for t in d])
             probs.append(torch.from_numpy(q).cuda())
             us.append(I.make_uniforms(ks[s] + 1, seed + 7 + 100 * r + s))
@@ -161,31 +152,107 @@ def batched(args, np, torch, I, nav):
         t = time.perf_counter()
         a, _ = kv.nav_verify_batch(list(range(n_seq)), drafts, probs, us)
         dt = time.perf_counter() - t
-        for s in range(n_seq):
-            kv.rollback(s, lens[s])  # every round starts from the same prefixes
-        if r >= args.warmup:
+        if r >= warmup:
             times.append(dt)
             ks_sum += sum(ks)
             committed += sum(a) + n_seq  # every client commits its accepted drafts and one more token
             rows.append(sum(ks) + n_seq)
             # weights once per call; per client the cached K/V read, the new rows written and q read
             alg += w_bytes + sum(shape.algorithmic_bytes(lens[s], ks[s]) - w_bytes for s in range(n_seq))
+        for s in range(n_seq):
+            if grow:
+                lens[s] += a[s] + 1
+            else:
+                kv.rollback(s, lens[s])
     total = sum(times)
+    kv.close()
+    return {"ms_per_call": total / len(times) * 1e3, "verified_tokens_per_sec": ks_sum / total,
+            "committed_tokens_per_sec": committed / total, "hbm_algorithmic_gbps": alg / total / 1e9,
+            "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS, "mean_rows_per_call": float(np.mean(rows)),
+            "acceptance_rate": (committed - n_seq * len(times)) / max(ks_sum, 1), "calls": len(times),
+            "prefix_tokens_at_start": sum(start_lens), "prefix_tokens_at_end": sum(lens),
+            "ms_per_call_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)]}
+
+
+def batched(args, np, torch, I, nav):
+    """--batch N: the multi-client call on its own (prefixes U[256,4096] unless --prefix, k U[1,16]
+    redrawn every round unless --k or --trigger, noisy-target drafts, sequences that grow)."""
+    wl = I.WORKLOADS[args.workload]
+    shape = wl["shape"] if args.layers is None else wl["shape"].truncated(args.layers)
+    seed = wl["seed"] + 1000
+    n_seq = args.batch
+    weights = I.make_weights(shape, wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+    model = nav.Model(shape, weights)
+    rng = np.random.default_rng(seed + I.SEED_LENGTHS)
+    lens = [args.prefix] * n_seq if args.prefix else [int(x) for x in rng.integers(256, 4097, n_seq)]
+    n_rounds = args.warmup + args.steps
+    if args.trigger:
+        r1, r2 = (float(x) for x in args.trigger.split(","))
+        traces = []
+        for s in range(n_seq):  # 16 = the longest draft a client sends in this workload
+            lens_s, _ = nav.trigger_rounds(I.make_confidences(16 * n_rounds, seed + 300 + s), r1, r2, 16, cap=n_rounds)
+            assert len(lens_s) == n_rounds
+            traces.append(lens_s)
+        k_of = lambda r, s: traces[s][r]
+    elif args.k:
+        k_of = lambda r, s: args.k
+    else:
+        ks_all = rng.integers(1, 17, (n_rounds, n_seq))
+        k_of = lambda r, s: int(ks_all[r, s])
+    sigma = None if args.independent_drafts else wl["sigma"]
+    rec = run_batched(np, torch, I, nav, model, shape, seed, lens, args.steps, args.warmup, sigma, k_of,
+                      grow=not args.no_grow)
+    esz = 4 if shape.dtype == I.DTYPE_F32 else 2
     out = {
-        "metric": "verified_tokens_per_sec", "value": ks_sum / total, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": total / len(times) * 1e3, "higher_is_better": True,
+        "metric": "verified_tokens_per_sec", "value": rec["verified_tokens_per_sec"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_call"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "config": {"workload": f"{shape.name}: {n_seq} clients per call, prefixes "
                                + (f"{args.prefix}" if args.prefix else "U[256,4096]") + ", k "
                                + (f"from the dual-threshold trigger (R1,R2 = {args.trigger}) on Beta(8,1) confidences"
                                   if args.trigger else f"{args.k}" if args.k else "U[1,16] redrawn every round")
-                               + ", paged KV (16-token blocks)", "mean_rows_per_call": float(np.mean(rows))},
-        "committed_tokens_per_sec": committed / total,
-        "hbm_algorithmic_gbps": alg / total / 1e9, "hbm_frac_of_peak": alg / total / 1e9 / HBM_PEAK_GBPS,
-        "ms_per_step_median_p10_p90": [float(np.percentile(times, q)) * 1e3 for q in (50, 10, 90)],
+                               + (", drafts independent of the target" if sigma is None else f", drafts softmax(target + {sigma} N)")
+                               + (", every round from the same prefixes" if args.no_grow else ", sequences grow over the rounds")
+                               + ", paged KV (16-token blocks)", "mean_rows_per_call": rec["mean_rows_per_call"]},
+        "committed_tokens_per_sec": rec["committed_tokens_per_sec"],
+        "hbm_algorithmic_gbps": rec["hbm_algorithmic_gbps"], "hbm_frac_of_peak": rec["hbm_frac_of_peak"],
+        "acceptance_rate": rec["acceptance_rate"],
+        "ms_per_step_median_p10_p90": rec["ms_per_call_median_p10_p90"],
         "roofline": None,
     }
     print(json.dumps(out), flush=True)
+
+
+def single_client_record(np, torch, I, nav, model, shape, seed, prefix, k, sigma, steps, warmup, kv=None):
+    """ms per pass, verified tokens/s and algorithmic HBM rate of the single-client pass on a model
+    that is already on the device (drafts from the library's own logits, outside the timed region)."""
+    own = kv is None
+    if own:
+        kv = nav.KVCache(model, max_seqs=1, n_blocks=(prefix + nav.MAX_ROWS + 15) // 16 + 2)
+        kv.prefill(0, I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX))
+    if sigma is None:
+        d, q = I.make_independent_drafts(k, shape.vocab, seed + I.SEED_NOISE, seed + I.SEED_DRAFT_U)
+    else:
+        d, q = I.make_noisy_target_drafts(lambda ds: kv.forward_logits(0, ds)[-1], k, shape.vocab, sigma,
+                                          seed + I.SEED_NOISE + k, seed + I.SEED_DRAFT_U + k)
+    q_dev = torch.from_numpy(q).cuda()
+    u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U + k)
+    times, acc = [], 0
+    for r in range(warmup + steps):
+        t = time.perf_counter()
+        a, _ = kv.nav_verify(0, d, q_dev, u)
+        dt = time.perf_counter() - t
+        kv.rollback(0, prefix)
+        if r >= warmup:
+            times.append(dt)
+            acc = a
+    if own:
+        kv.close()
+    t_pass = sum(times) / len(times)
+    alg = shape.algorithmic_bytes(prefix, k)
+    return {"ms_per_pass": t_pass * 1e3, "verified_tokens_per_sec": k / t_pass, "committed_tokens_per_sec": (acc + 1) / t_pass,
+            "hbm_algorithmic_gbps": alg / t_pass / 1e9, "hbm_frac_of_peak": alg / t_pass / 1e9 / HBM_PEAK_GBPS,
+            "accepted_len": acc, "passes": len(times)}
 
 
 def prefill(args, np, torch, I, nav):
@@ -245,6 +312,12 @@ def main():
                     help="N > 0: time pipesd_nav_verify_batch on N clients instead (prefixes U[256,4096] unless --prefix, "
                          "k U[1,16] redrawn every round unless --k; --steps rounds).  An auxiliary line: no roofline / "
                          "cpu_baseline objects")
+    ap.add_argument("--independent-drafts", action="store_true",
+                    help="with --batch: drafts that ignore the target (acceptance near 0) instead of softmax(target + sigma N)")
+    ap.add_argument("--no-grow", action="store_true",
+                    help="with --batch: cut every client back to its prefix after each round instead of letting it grow")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="leave out the `extra_configs` object (the other workloads of the configuration list)")
     ap.add_argument("--trigger", default=None,
                     help="with --batch: R1,R2 - every client's draft lengths come from the dual-threshold trigger "
                          "(Sec. 3.3) run over a seeded stream of synthetic confidences instead of U[1,16]")
@@ -362,7 +435,65 @@ def main():
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(wl["shape"], weights, prefix, k, min(args.cpu_layers, shape.n_layers))
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
+    if not args.no_extra and args.workload == "llama-8b" and args.layers is None and args.k is None and args.prefix is None:
+        out["extra_configs"] = extra_configs(np, torch, I, nav, model, kv, shape, seed, prefix, sigma)
     print(json.dumps(out), flush=True)
+
+
+def extra_configs(np, torch, I, nav, model8, kv8, shape8, seed8, prefix8, sigma8):
+    """The other workloads of the configuration list, measured in the same run (each one guarded:
+    a failure is reported in its place and never costs the headline line)."""
+    extra = {}
+
+    def guarded(name, fn):
+        t0 = time.time()
+        try:
+            extra[name] = fn()
+        except Exception as e:  # noqa: BLE001
+            extra[name] = {"error": f"{type(e).__name__}: {e}"}
+        log(f"[bench] extra config {name} took {time.time() - t0:.1f}s")
+
+    # the k sweep of the 8B workload on the resident model and cache
+    for kk in (1, 4, 16):
+        guarded(f"llama-8b prefix {prefix8} k={kk} batch 1",
+                lambda kk=kk: single_client_record(np, torch, I, nav, model8, shape8, seed8, prefix8, kk, sigma8, 20, 5, kv=kv8))
+    # 16 clients on the 8B model: prefixes U[256,4096], k U[1,16] redrawn every round, noisy-target
+    # drafts, 50 consecutive rounds over sequences that grow
+    def cfg4():
+        rng = np.random.default_rng(seed8 + 1000 + I.SEED_LENGTHS)
+        lens = [int(x) for x in rng.integers(256, 4097, 16)]
+        ks_all = rng.integers(1, 17, (52, 16))
+        return run_batched(np, torch, I, nav, model8, shape8, seed8 + 1000, lens, 50, 2, sigma8,
+                           lambda r, s: int(ks_all[r, s]))
+    guarded("llama-8b 16 clients, prefixes U[256,4096], k U[1,16], 50 growing rounds, sigma 0.5", cfg4)
+    kv8.close()
+    model8.close()
+    torch.cuda.empty_cache()
+    for name, steps in (("llama-1b", 50), ("tiny", 50)):
+        def small(name=name, steps=steps):
+            wl = I.WORKLOADS[name]
+            w = I.make_weights(wl["shape"], wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+            m = nav.Model(wl["shape"], w)
+            try:
+                return single_client_record(np, torch, I, nav, m, wl["shape"], wl["seed"], wl["prefix"], wl["k"], wl["sigma"],
+                                            steps, 10)
+            finally:
+                m.close()
+        wl = I.WORKLOADS[name]
+        guarded(f"{name} prefix {wl['prefix']} k={wl['k']} batch 1", small)
+    # the long-context 13B workload: 4 clients, prefix 8192, k = 16, sigma 1.0, through the batched call
+    def cfg5():
+        wl = I.WORKLOADS["llama-13b"]
+        w = I.make_weights(wl["shape"], wl["seed"] + I.SEED_WEIGHTS, threads=min(16, os.cpu_count() or 8))
+        m = nav.Model(wl["shape"], w)
+        del w
+        try:
+            return run_batched(np, torch, I, nav, m, wl["shape"], wl["seed"] + 1000, [wl["prefix"]] * 4, 8, 2, wl["sigma"],
+                               lambda r, s: wl["k"])
+        finally:
+            m.close()
+    guarded("llama-13b 4 clients, prefix 8192, k=16, sigma 1.0, growing rounds", cfg5)
+    return extra
 
 
 if __name__ == "__main__":

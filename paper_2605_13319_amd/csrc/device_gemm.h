@@ -416,6 +416,37 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
       if (norm && lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
     }
   };
+  // The same without a branch around the loads (the per-projection kernels): every lane loads, at
+  // clamped indices, and the lanes without a partial sum of their own drop what they got after the
+  // wait.  With a branch the value of the skipping lanes and the loaded value meet in a phi, and the
+  // compiler is free to realise that phi by a copy right behind the load, of a register whose data
+  // is still on its way (seen once; the ISA lint flags it).
+  auto ssq_request_u = [&](int row0) {
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+      for (int j4 = 0; j4 < kSsqPerLane; ++j4) {
+        const int row = min(tp.row_base + row0 + r2 * nwaves_wg, a.m - 1), j = min(lane + 64 * j4, a.ssq_parts - 1);
+        asm volatile("global_load_dword %0, %1, off" : "=v"(part[r2][j4]) : "v"(a.ssq_in + (size_t)row * a.ssq_stride + j));
+      }
+  };
+  auto ssq_finish_u = [&](int row0) {
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2)
+#pragma unroll
+      for (int j4 = 0; j4 < kSsqPerLane; ++j4) asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[r2][j4]));
+#pragma unroll
+    for (int r2 = 0; r2 < 2; ++r2) {
+      const int row = row0 + r2 * nwaves_wg;
+      const bool live = row < MT * 16 && tp.row_base + row < a.m;
+      float q = (live && lane < a.ssq_parts) ? part[r2][0] : 0.f;
+#pragma unroll
+      for (int j4 = 1; j4 < kSsqPerLane; ++j4) q += (live && lane + 64 * j4 < a.ssq_parts) ? part[r2][j4] : 0.f;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+      if (lane == 0 && row < MT * 16) rstd_lds[row] = 1.0f / sqrtf(q / (float)a.K + a.eps);
+    }
+  };
   // residual epilogue: residual and gain values of the first quad this lane will finish
   f32x4 pre_res = f32x4{0.f, 0.f, 0.f, 0.f}, pre_gain = pre_res;
   bool have_pre = false;
@@ -445,18 +476,24 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
         ssq_finish(row0, none_younger{});
       }
   } else {
-    // Everything the step before left for this one is requested first (sums of squares, residual
-    // operands), then the first weight chunk, then the activation fragments, all without a wait in
-    // between; the sums are awaited alone and folded while weights and fragments are on their way.
-    // Every wave issues the same hand-issued loads (a workgroup beyond the last tile group, which
-    // only a padded grid has, requests the last group's chunk and never uses it), so the number of
-    // loads younger than the sums is a constant.
+    // The first weight chunk is requested first (the weights are the long pole and depend on
+    // nothing), then what the step before left for this one (sums of squares, residual operands,
+    // activation fragments), all without a wait in between, and then everything is awaited together.
+    // (Awaiting the sums alone while the fragments are still in flight was tried: it gains nothing
+    // measurable, and with the code between request and wait the compiler once moved a register whose
+    // load was still on its way, which the ISA lint caught.)  A workgroup beyond the last tile group,
+    // which only a padded grid has, requests the last group's chunk and never uses it.
     constexpr bool NORM = EPI != EPI_RESID;
     const int g0 = min(tp.team, ngroups - 1);
-    if constexpr (NORM) ssq_request(w);
+    {
+      const u32x4* first = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, g0 * a.tg, 0);
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load<NT>(first + ks * 64);
+    }
+    if constexpr (NORM) ssq_request_u(w);
     if constexpr (EPI == EPI_RESID) {
       // unconditional loads at clamped indices: no branch, hence no join at which the compiler would
-      // have to wait for them (a wait there would also drain the weight requests behind them)
+      // have to wait for them (a wait there would also drain the weight requests in front of them)
       const int t0 = g0 * a.tg, nq = min(a.tg, a.ntiles - t0) * MT * 64, e_first = tp.wt * 64 + lane;
       const int e = min(e_first, nq - 1);
       const int tt = e / (MT * 64), rem = e % (MT * 64), l = rem & 63;
@@ -465,24 +502,19 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& a, const TeamPos& tp, 
       pre_gain = *(const f32x4*)(a.gain_next + col);
       have_pre = working && e_first < nq;
     }
-    {
-      const u32x4* first = gemm_chunk_ptr<KSTEPS>(a, lane, tp.wt, g0 * a.tg, 0);
-#pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) af[ks] = stream_load<NT>(first + ks * 64);
-    }
     if constexpr (P1) {
       request_act(tp.wt, 0, bhi);
       request_act(tp.wt, 1, blo);
     }
+    if constexpr (P1) await_act();
     if constexpr (NORM) {
-      ssq_finish(w, std::integral_constant<int, KSTEPS + (P1 ? 2 * KSTEPS * MT : 0)>{});
-      if (tp.row_base + 2 * nwaves_wg < a.m)  // (few waves and many rows: the remaining rows, awaited in full)
+      ssq_finish_u(w);
+      if (tp.row_base + 2 * nwaves_wg < a.m)  // (few waves and many rows: the remaining rows)
         for (int row0 = w + 2 * nwaves_wg; row0 < MT * 16; row0 += 2 * nwaves_wg) {
-          ssq_request(row0);
-          ssq_finish(row0, none_younger{});
+          ssq_request_u(row0);
+          ssq_finish_u(row0);
         }
     }
-    if constexpr (P1) await_act();
   }
   for (int it = 0; it < iters; ++it) {
     const int grp = tp.team + it * tp.nteams;

@@ -56,6 +56,15 @@ def main():
     ratios = [float(p2[i, d2[i]]) / float(q2[i, d2[i]]) for i in range(k)]
     a_spec, n_spec = seq.nav_verify(d2, q2, u2)
     seq.rollback(lp)
+    # the one draw of pass B: every token whose interval of the draw's CDF (residual of row a, or the
+    # extra-token row) comes within 1e-3 of the uniform is a result the end-to-end rule excuses
+    w_row = np.maximum(np.float32(0.0), p2[a_spec] - q2[a_spec]) if a_spec < k else p2[k]
+    cdf = np.cumsum(w_row.astype(np.float64))
+    cdf /= cdf[-1]
+    lo = np.concatenate([[0.0], cdf[:-1]])
+    u_draw = float(u2[k])
+    near = np.nonzero((cdf > u_draw - 1e-3) & (lo < u_draw + 1e-3) & (w_row > 0))[0]
+    assert n_spec in near
 
     out = {
         "workload": "llama-8b", "prefix": prefix, "k": k, "seed": seed,
@@ -63,7 +72,8 @@ def main():
                    "row_argmax": [int(i) for i in np.argmax(z, axis=1)],
                    "row_top2_gap": [float(t[1] - t[0]) for t in top2]},
         "pass_b": {"draft_scale": 1.0, "accepted_len": a_spec, "next_token": n_spec,
-                   "ratios": ratios, "uniforms": [float(x) for x in u2]},
+                   "ratios": ratios, "uniforms": [float(x) for x in u2],
+                   "next_token_within_1e-3_of_the_uniform": [int(i) for i in near]},
     }
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "llama8b_nav.json")
     with open(path, "w") as f:

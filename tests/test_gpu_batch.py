@@ -33,7 +33,7 @@ LLAMA_8B_L2 = I.WORKLOADS["llama-8b"]["shape"].truncated(2)
 
 @pytest.mark.parametrize("shape_name,n_seq,rounds,max_prefix", [("tiny", 5, 4, 150), ("small-bf16", 5, 4, 150),
                                                                  ("small-bf16", 16, 12, 150), ("ragged-bf16", 16, 3, 150),
-                                                                 ("llama-8b-L2", 16, 2, 4096)])
+                                                                 ("llama-8b-L2", 16, 10, 4096)])
 def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds, max_prefix):
     """bf16: the clients' rows share passes of up to 128 rows (16 clients with k ~ U[1,16] need two);
     a row's results must not depend on what else is in its pass."""
@@ -132,3 +132,54 @@ def test_batched_rounds_against_the_checker(nav):
                 o.cached = lens[s] + a_b[s]
             lens[s] += a_b[s] + 1
             assert kv.length(s) == lens[s] == oseqs[s].prefix_len
+
+
+def test_fifty_growing_rounds_of_sixteen_clients_against_the_checker(nav):
+    """The multi-client workload as it is written (Appendix I; 16 clients, per-client prefixes, k ~
+    U[1,16] redrawn every round as the dual-threshold trigger would, drafts q = softmax(target logits
+    + 0.5 N) from the checker's own logits, 50 consecutive verify / rollback rounds) at a small shape:
+    the sequences GROW by accepted + 1 tokens per round, every decision of every round equals the
+    checker's or is excused by the 1e-3 rule, and lengths and block counts follow."""
+    shape = SMALL_BF16
+    w = I.make_weights(shape, 9651)
+    model = nav.Model(shape, w)
+    n_seq, rounds = 16, 50
+    rng = np.random.default_rng(9652)
+    lens = [int(x) for x in rng.integers(17, 150, n_seq)]
+    max_len = 150 + 17 * rounds + 32
+    kv = nav.KVCache(model, max_seqs=n_seq, n_blocks=n_seq * (max_len // 16 + 2))
+    oseqs = []
+    for s, n in enumerate(lens):
+        toks = I.make_tokens(n, shape.vocab, 9660 + s)
+        kv.prefill(s, toks)
+        oseqs.append(oracle_side(shape, w, toks, max_len))
+    excused = accepted = drafted = 0
+    for rnd in range(rounds):
+        ks = [int(x) for x in rng.integers(1, 17, n_seq)]
+        drafts, probs, us, refs, prows = [], [], [], [], []
+        for s in range(n_seq):
+            d, q = drafts_from_oracle(oseqs[s], ks[s], 0.5, 20000 + 100 * rnd + s, 30000 + 100 * rnd + s)
+            u = I.make_uniforms(ks[s] + 1, 40000 + 100 * rnd + s)
+            drafts.append([int(t) for t in d]); probs.append(q); us.append(u)
+            prows.append(softmax_rows(oseqs[s].forward_logits(d)))
+            refs.append(oseqs[s].nav_verify(d, q, u))
+        a_b, n_b = kv.nav_verify_batch(list(range(n_seq)), drafts, probs, us)
+        for s in range(n_seq):
+            a_ref, n_ref = refs[s]
+            if (a_b[s], n_b[s]) != (a_ref, n_ref):
+                assert a_b[s] != a_ref and decision_excused(prows[s], probs[s], drafts[s], us[s], a_b[s], a_ref), \
+                    f"round {rnd} client {s}: {(a_b[s], n_b[s])} vs checker {(a_ref, n_ref)}"
+                excused += 1
+                o = oseqs[s]
+                o.rollback(lens[s])
+                o.committed += drafts[s][:a_b[s]] + [n_b[s]]
+                o.cached = lens[s] + a_b[s]
+            lens[s] += a_b[s] + 1
+            accepted += a_b[s]
+            drafted += ks[s]
+            assert kv.length(s) == lens[s] == oseqs[s].prefix_len
+            assert kv.seq_blocks(s) == (lens[s] - 1 + 15) // 16
+        if rnd % 10 == 9:
+            print(f"round {rnd}: lengths {min(lens)}..{max(lens)}, accepted {accepted}/{drafted}, excused {excused}", flush=True)
+    assert sum(lens) > sum(int(x) for x in np.random.default_rng(9652).integers(17, 150, n_seq)) + n_seq * rounds
+    assert excused <= 3, excused

@@ -390,7 +390,11 @@ def test_llama_8b_full_depth_against_stored_checker_values(nav):
         i = min(a, b_ref["accepted_len"])
         assert abs(min(1.0, b_ref["ratios"][i]) - b_ref["uniforms"][i]) < 1e-3
     else:
+        # the one draw at full depth: the checker's token, or a token whose interval of the draw's CDF
+        # (according to the checker) comes within 1e-3 of the uniform
         print(f"pass B: accepted {a}, next {n} (checker {b_ref['next_token']})", flush=True)
+        assert n == b_ref["next_token"] or n in b_ref["next_token_within_1e-3_of_the_uniform"], \
+            (n, b_ref["next_token"], b_ref["next_token_within_1e-3_of_the_uniform"])
     assert kv.length(0) == prefix + a + 1
 
 
@@ -458,37 +462,46 @@ def _chain_by_hand(kv, seq, rounds):
 def test_chained_rounds_on_proactive_buffers(nav, wl_name, tol):
     """Appendix B, cloud side: a buffer of proactively sent drafts is kept iff the round before it
     accepted everything and produced the guessed extra token.  The chained call equals single calls
-    with the rule applied by hand, bit for bit; and where the checker's argmax margins are clear of
-    the logit tolerance (the fp32 model) the rounds that run, their decisions and the state they
-    leave equal the checker's.  Drafts: the target's own greedy text according to the checker, a
+    with the rule applied by hand, bit for bit; and on a prompt whose greedy continuation the checker
+    decides by argmax margins clear of the logit tolerance, the rounds that run, their decisions and
+    the state they leave equal the checker's.  Drafts: the target's own greedy text according to the checker, a
     wrong guess at the end; then the sampling rule."""
     if wl_name == "tiny":
         shape, seed, prefix = I.WORKLOADS["tiny"]["shape"], 5100, 40
     else:
         shape, seed, prefix = SMALL_BF16, 5200, 70
-    oseq, model, kv = _both(nav, shape, seed, prefix, n_blocks=16)
-    toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX)
+    # a prompt whose 12-token greedy continuation (according to the checker) is decided by margins
+    # that clear the logit tolerance, so that the chain can be held to the checker's
+    w = I.make_weights(shape, seed + I.SEED_WEIGHTS)
+    for attempt in range(400):
+        toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX + 100 * attempt)
+        probe = oracle_side(shape, w, toks, prefix + 64)
+        margins = []
+        for _ in range(12):
+            z = probe.forward_logits([])[0]
+            top = np.sort(z)[-2:]
+            margins.append(float(top[1] - top[0]))
+            probe.cached += 1
+            probe.committed.append(int(np.argmax(z)))
+        margins = margins[:9]  # the decisions the chain depends on: 3 drafts, the guess, 4 drafts, the extra token
+        if min(margins) > 2.5 * tol:
+            break
+    assert min(margins) > 2.5 * tol, f"no prompt with clear argmax margins among 400 (last attempt {min(margins):.4f})"
+    print(f"prompt {attempt}: smallest argmax margin {min(margins):.4f}", flush=True)
+    oseq = oracle_side(shape, w, toks, prefix + 64)
+    model = nav.Model(shape, w)
+    kv = nav.KVCache(model, max_seqs=2, n_blocks=16)
+    kv.prefill(0, toks)
     kv.prefill(1, toks)
-    probe = oracle_side(shape, I.make_weights(shape, seed + I.SEED_WEIGHTS), toks, prefix + 64)
-    margins = []
-    for _ in range(12):
-        z = probe.forward_logits([])[0]
-        top = np.sort(z)[-2:]
-        margins.append(float(top[1] - top[0]))
-        probe.cached += 1
-        probe.committed.append(int(np.argmax(z)))
     ref, n0 = probe.committed, prefix
     rounds = [(ref[n0:n0 + 3], None, None), (ref[n0 + 3:n0 + 8], None, None),
               ([(ref[n0 + 8] + 1) % shape.vocab] + ref[n0 + 9:n0 + 11], None, None)]  # third buffer: wrong guess
     out = kv.nav_verify_chain(0, rounds)
     assert out == _chain_by_hand(kv, 1, rounds) and kv.length(0) == kv.length(1)
     assert 1 <= len(out) <= 2
-    if min(margins) > 2.5 * tol:
-        out_ref = oseq.nav_verify_chain(rounds)
-        assert out == out_ref and [a for a, _ in out] == [3, 4]
-        assert kv.length(0) == oseq.prefix_len == n0 + 9
-    else:
-        print(f"checker comparison skipped: smallest argmax margin {min(margins):.4f} within the tolerance", flush=True)
+    out_ref = oseq.nav_verify_chain(rounds)
+    assert out == out_ref and [a for a, _ in out] == [3, 4]
+    assert kv.length(0) == oseq.prefix_len == n0 + 9
     # sampling rule: a round whose drafts are all accepted (q far below p: every ratio exceeds 1),
     # then a buffer whose guess is the extra token the GPU itself draws (kept) or another token
     # (dropped); chain == single calls
