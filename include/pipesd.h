@@ -85,8 +85,8 @@ typedef struct pipesd_kv pipesd_kv;
  * weights == NULL creates a shape-only handle without device memory (for planning KV pools and
  * exercising the bookkeeping without a GPU); compute calls on it return PIPESD_ESTATE.
  * EINVAL: null cfg/out, non-positive sizes, n_q_heads not a multiple of n_kv_heads, odd head_dim,
- * head_dim > 128, or (bf16) d_model, n_q_heads*head_dim or d_ffn not a multiple of 512 or
- * head_dim other than 64 or 128. */
+ * head_dim > 128, or (bf16) d_model, n_q_heads*head_dim or d_ffn not a multiple of 512,
+ * head_dim other than 64 or 128, or d_model above 8192. */
 int pipesd_model_create(const pipesd_config *cfg, const pipesd_weights *weights, pipesd_model **out);
 int pipesd_model_destroy(pipesd_model *model);
 
@@ -97,7 +97,11 @@ size_t pipesd_kv_block_bytes(const pipesd_model *model, int32_t block_tokens);
  * pipesd_kv_destroy).  The pool holds floor(pool_bytes / block_bytes) blocks of block_tokens
  * (16) tokens; per layer the keys of a block are [kv_head][token][head_dim] and the values
  * [kv_head][head_dim][token].  pool == NULL gives bookkeeping only (see pipesd_model_create).
- * EINVAL: block_tokens != 16, max_seqs < 1, pool too small for one block, pool not 256-byte aligned. */
+ * With a pool, the model's scratch for attention partials is sized here for the largest pass this
+ * pool admits (about 0.5 MB per 256 pool tokens for 32 query heads of 128), so that no verify call
+ * allocates.
+ * EINVAL: block_tokens != 16, max_seqs < 1, pool too small for one block, pool not 256-byte aligned;
+ * ENOMEM: the block tables or the scratch cannot be allocated. */
 int pipesd_kv_create(const pipesd_model *model, int32_t max_seqs, int32_t block_tokens, void *pool,
                      size_t pool_bytes, pipesd_kv **out);
 int pipesd_kv_destroy(pipesd_kv *kv);

@@ -108,6 +108,7 @@ static int check_config(const pipesd_config* c) {
     const int qd = c->n_q_heads * c->head_dim;
     if (c->d_model % 512 || qd % 512 || c->d_ffn % 512) return PIPESD_EINVAL;
     if (c->head_dim != 64 && c->head_dim != 128) return PIPESD_EINVAL;
+    if (c->d_model / 16 > 512) return PIPESD_EINVAL;  // the fused norm reads at most 512 partial sums of squares per row
   } else {
     if (c->d_model % 4 || c->d_ffn % 4) return PIPESD_EINVAL;
   }
@@ -293,6 +294,18 @@ extern "C" size_t pipesd_kv_block_bytes(const pipesd_model* model, int32_t block
   return (size_t)c.n_layers * 2 * c.n_kv_heads * c.head_dim * block_tokens * model->esz;
 }
 
+static int ensure_attn_scratch(pipesd_model* m, size_t floats);
+
+// Floats of attention partials the largest pass over a pool of `pool_tokens` cached tokens can need:
+// a client brings at most kMaxRows rows and ceil(context / chunk) splits, the contexts of the
+// clients of a pass add up to at most the pool, and a pass holds at most kMaxPassClients clients.
+static size_t attn_scratch_bound(const pipesd_model* m, int64_t pool_tokens) {
+  const int chunk = attn_chunk_tokens(m->cfg.dtype);
+  const int64_t clients = m->cfg.dtype == PIPESD_BF16 ? kMaxPassClients : 1;
+  const int64_t splits = pool_tokens / chunk + clients;
+  return (size_t)kMaxRows * (size_t)splits * m->cfg.n_q_heads * (m->cfg.head_dim + 4);
+}
+
 extern "C" int pipesd_kv_create(const pipesd_model* model, int32_t max_seqs, int32_t block_tokens, void* pool,
                                 size_t pool_bytes, pipesd_kv** out) {
   if (!model || !out || max_seqs < 1 || block_tokens != kBlockTokens) return PIPESD_EINVAL;
@@ -322,6 +335,14 @@ extern "C" int pipesd_kv_create(const pipesd_model* model, int32_t max_seqs, int
       (void)hipFree(kv->table_dev);
       delete kv;
       return PIPESD_EHIP;
+    }
+    // the attention partials of any pass over this pool fit from now on: no verify call has to
+    // synchronise the device and reallocate (the model handle is the library's own object)
+    const int rc = ensure_attn_scratch(const_cast<pipesd_model*>(model), attn_scratch_bound(model, (int64_t)kv->n_blocks * kBlockTokens));
+    if (rc) {
+      (void)hipFree(kv->table_dev);
+      delete kv;
+      return rc;
     }
   }
   *out = kv;

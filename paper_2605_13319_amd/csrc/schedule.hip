@@ -3,7 +3,8 @@
 // Token batching (Sec. 3.2): N draft tokens leave the edge in K batches; batch k starts at token
 // b_k.  Generating a token takes gamma, sending a batch of n tokens alpha + beta n; a batch is
 // sent once it has been generated and the link has finished the batch before it.  The time of a
-// batching is Eq. (6); the best batching comes from the dynamic programme of Sec. 4.1 (Theorem 1).
+// batching is Eq. (6); the best batching is a shortest path over the link's states, optimal by the
+// argument of Sec. 4.1 (Theorem 1).
 // NAV trigger (Sec. 3.3): a round ends at the draft token whose confidence brings the running
 // product to R1 or below, or is itself R2 or below.
 #include <math.h>
@@ -41,42 +42,45 @@ extern "C" int pipesd_batching_time(int32_t n_tokens, const int32_t* first, int3
   return PIPESD_OK;
 }
 
-// done[j]: earliest time the link can have delivered tokens 1..j; the last batch {i+1..j} starts
-// when tokens 1..i are delivered and token j exists.  Ties keep the smallest i (the longest last
-// batch), so the batching returned is the one with the fewest, latest boundaries among the best.
+// Shortest path over link states (the model of Sec. 3.2, Eqs. (1)-(6)).  State s = "tokens 1..s have
+// been delivered", reached at time free_at[s] (state 0 at time 0).  From state s a batch of len
+// tokens leads to state s + len: it can start when the link is free (free_at[s]) and its last token
+// exists (gamma (s + len), generation never pausing), and occupies the link for alpha + beta len.
+// The states are settled in increasing s (every edge goes forward), each one relaxing all the
+// states it can reach; T of Eq. (6) for the best batching is free_at[N].  A later state only
+// replaces a predecessor that is strictly better, and predecessors are visited in increasing s, so
+// among equally good batchings the one whose last batch starts earliest (is longest) is kept, and so
+// on towards the front.  Theorem 1's optimum is what the tests hold this to, by enumeration.
 extern "C" int pipesd_batching_optimal(int32_t n_tokens, double alpha, double beta, double gamma, int32_t* first_out,
                                        int32_t* n_batches_out, double* time_out) {
   if (!first_out || !n_batches_out || !time_out || n_tokens < 1 || n_tokens > kMaxScheduleTokens) return PIPESD_EINVAL;
   if (!cost_ok(alpha) || !cost_ok(beta) || !cost_ok(gamma)) return PIPESD_EINVAL;
-  std::vector<double> done;
-  std::vector<int32_t> cut;
+  std::vector<double> free_at;
+  std::vector<int32_t> from;  // the state the best way into a state comes from
   try {
-    done.assign((size_t)n_tokens + 1, 0.0);
-    cut.assign((size_t)n_tokens + 1, 0);
+    free_at.assign((size_t)n_tokens + 1, INFINITY);
+    from.assign((size_t)n_tokens + 1, 0);
   } catch (const std::bad_alloc&) {
     return PIPESD_ENOMEM;
   }
-  for (int32_t j = 1; j <= n_tokens; ++j) {
-    const double ready = gamma * (double)j;
-    double best = INFINITY;
-    int32_t arg = 0;
-    for (int32_t i = 0; i < j; ++i) {
-      const double start = done[i] > ready ? done[i] : ready;
-      const double t = start + (alpha + beta * (double)(j - i));
-      if (t < best) {
-        best = t;
-        arg = i;
+  free_at[0] = 0.0;
+  for (int32_t s = 0; s < n_tokens; ++s) {
+    const double link_free = free_at[s];  // final: every edge into s has been relaxed
+    for (int32_t len = 1; s + len <= n_tokens; ++len) {
+      const int32_t to = s + len;
+      const double generated = gamma * (double)to;
+      const double arrival = (link_free > generated ? link_free : generated) + (alpha + beta * (double)len);
+      if (arrival < free_at[to]) {
+        free_at[to] = arrival;
+        from[to] = s;
       }
     }
-    done[j] = best;
-    cut[j] = arg;
   }
   int32_t n_batches = 0;
-  for (int32_t p = n_tokens; p > 0; p = cut[p]) ++n_batches;
-  int32_t k = n_batches;
-  for (int32_t p = n_tokens; p > 0; p = cut[p]) first_out[--k] = cut[p] + 1;
+  for (int32_t s = n_tokens; s > 0; s = from[s]) ++n_batches;
+  for (int32_t s = n_tokens, k = n_batches; s > 0; s = from[s]) first_out[--k] = from[s] + 1;
   *n_batches_out = n_batches;
-  *time_out = done[n_tokens];
+  *time_out = free_at[n_tokens];
   return PIPESD_OK;
 }
 

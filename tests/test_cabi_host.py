@@ -44,7 +44,8 @@ def _create(shape, weights_ptr=None):
 
 @pytest.mark.parametrize("bad", [
     dict(n_layers=0), dict(n_q_heads=6, n_kv_heads=4), dict(head_dim=63), dict(head_dim=256, n_q_heads=2, n_kv_heads=2),
-    dict(d_model=1000), dict(d_ffn=1000), dict(vocab=0), dict(dtype=7), dict(rope_base=0.0)])
+    dict(d_model=1000), dict(d_ffn=1000), dict(vocab=0), dict(dtype=7), dict(rope_base=0.0),
+    dict(d_model=8704)])  # more than 512 partial sums of squares per row: beyond what the fused norm reads
 def test_model_create_rejects_bad_shapes(bad):
     import dataclasses
     shape = dataclasses.replace(I.LLAMA_1B, **bad)
