@@ -34,7 +34,7 @@ def log(*a):
 
 
 GEMM_SOURCES = ("device_gemm.h", "kernels_gemm.hip", "common.h")
-TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "gemm_bf16_llama8b_k8_hbm_traffic.md")
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "nav_pass_llama8b_k8_per_projection.md")
 
 
 def gemm_sources_sha():
@@ -45,14 +45,15 @@ def gemm_sources_sha():
     return h.hexdigest()
 
 
-def committed_traffic(workload):
-    """HBM bytes per GEMM launch from the committed counter summary, or None if there is none for
-    this workload or the GEMM sources have changed since the counters were taken."""
+def committed_traffic(workload, projection):
+    """HBM bytes per launch of the given projection's kernel from the committed counter summary, or
+    None if there is none for this workload or the GEMM sources have changed since the counters
+    were taken."""
     if workload != "llama-8b" or not os.path.exists(TRAFFIC_SUMMARY):
         return None
     txt = open(TRAFFIC_SUMMARY).read()
     sha = re.search(r"sources-sha256:\s*([0-9a-f]{64})", txt)
-    val = re.search(r"traffic-bytes-per-launch:\s*([0-9.eE+]+)", txt)
+    val = re.search(r"traffic-bytes-per-launch\[" + re.escape(projection) + r"\]:\s*([0-9.eE+]+)", txt)
     if not sha or not val or sha.group(1) != gemm_sources_sha():
         return None
     return float(val.group(1))
@@ -389,7 +390,8 @@ def main():
         assert res == first, "the pass is not reproducible"
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    n_launch, kern_ms = model.profile_read()
+    each_us = model.profile_read_each()
+    n_launch, kern_ms = len(each_us), sum(each_us) / 1e3
     model.profile_select("off")
     # the same steps without event bracketing, to show what the events cost
     per_step_plain = []
@@ -411,11 +413,38 @@ def main():
         per_launch_bytes = gemm_bytes / launches_per_pass
         avg_ms = kern_ms / n_launch
         achieved = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+        all_gemm = {"achieved": achieved, "frac": achieved / HBM_PEAK_GBPS, "launches_per_pass": launches_per_pass,
+                    "avg_launch_us": avg_ms * 1e3, "algorithmic_bytes_per_launch": per_launch_bytes}
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": committed_traffic(args.workload) if args.layers is None else None,
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                 "kernel": "gemm_bf16_kernel (all weight-streaming GEMMs of the pass)" if esz == 2 else "gemm_f32_kernel",
-                "launches_per_pass": launches_per_pass, "avg_launch_us": avg_ms * 1e3,
-                "algorithmic_bytes_per_launch": per_launch_bytes}
+                **{k_: v_ for k_, v_ in all_gemm.items() if k_ not in ("achieved", "frac")}}
+        per_pass = 4 * shape.n_layers + 1
+        if esz == 2 and args.prof == "all_gemm" and n_launch == per_pass * args.steps:
+            # every projection is a kernel of its own (the epilogue is a template parameter): the
+            # roofline object is for the one the pass spends most of its time in; all five are listed
+            qd, kvd, d_, F_ = shape.q_dim, shape.kv_dim, shape.d_model, shape.d_ffn
+            proj = [("qkv", "gemm_bf16_kernel<16, true, EPI_QKV, ..>", (qd + 2 * kvd) * d_, lambda i: i < per_pass - 1 and i % 4 == 0),
+                    ("o", "gemm_bf16_kernel<16, true, EPI_RESID, P1>", d_ * qd, lambda i: i < per_pass - 1 and i % 4 == 1),
+                    ("gate_up", "gemm_bf16_kernel<16, true, EPI_SWIGLU, ..>", 2 * F_ * d_, lambda i: i < per_pass - 1 and i % 4 == 2),
+                    ("down", "gemm_bf16_kernel<16, true, EPI_RESID, phases>", d_ * F_, lambda i: i < per_pass - 1 and i % 4 == 3),
+                    ("lm_head", "gemm_bf16_kernel<16, true, EPI_STORE, ..>", shape.vocab * d_, lambda i: i == per_pass - 1)]
+            table = {}
+            for name, kname, elems, sel in proj:
+                us = [t for j, t in enumerate(each_us) if sel(j % per_pass)]
+                mean_us = sum(us) / len(us)
+                gbps = elems * esz / (mean_us * 1e-6) / 1e9
+                table[name] = {"kernel": kname, "launches_per_pass": len(us) / args.steps, "avg_launch_us": mean_us,
+                               "algorithmic_bytes_per_launch": elems * esz, "achieved": gbps, "frac": gbps / HBM_PEAK_GBPS,
+                               "us_per_pass": sum(us) / args.steps}
+            dom = max(table, key=lambda n: table[n]["us_per_pass"])
+            t_dom = table[dom]
+            roof = {"bound": "hbm", "achieved": t_dom["achieved"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": t_dom["frac"],
+                    "traffic": committed_traffic(args.workload, dom) if args.layers is None else None,
+                    "kernel": t_dom["kernel"] + f" ({dom} projection: the kernel the pass spends most of its time in)",
+                    "launches_per_pass": t_dom["launches_per_pass"], "avg_launch_us": t_dom["avg_launch_us"],
+                    "algorithmic_bytes_per_launch": t_dom["algorithmic_bytes_per_launch"],
+                    "per_projection": table, "all_weight_streaming_gemms": all_gemm}
 
     out = {
         "metric": "verified_tokens_per_sec", "value": k / t_pass, "unit": "tokens/s", "n_gpus": 1,

@@ -249,6 +249,11 @@ enum { PIPESD_PROF_OFF = 0, PIPESD_PROF_GEMM_QKV = 1, PIPESD_PROF_GEMM_O = 2, PI
        PIPESD_PROF_ALL_GEMM = 8, PIPESD_PROF_LAYERS = 9 };
 int pipesd_profile_select(pipesd_model *model, int32_t kernel_class);
 int pipesd_profile_read(pipesd_model *model, int32_t *n_launches, double *total_ms);
+/* The same, launch by launch: copies the durations (microseconds, in launch order) of the timed
+ * launches since the last read into host array us_out (at most `cap` values) and sets *n_launches
+ * to their number.  With PIPESD_PROF_ALL_GEMM a bf16 pass yields QKV, O, gate/up, down per layer,
+ * then the LM head. */
+int pipesd_profile_read_each(pipesd_model *model, double *us_out, int32_t cap, int32_t *n_launches);
 /* While PIPESD_PROF_LAYERS is selected the fused layer kernel also records a device clock at the
  * start of each of its 4*n_layers steps (QKV + attention, O, gate/up, down per layer).  Copies the
  * step durations of the most recent fused launch, in microseconds, into host array us_out (at most

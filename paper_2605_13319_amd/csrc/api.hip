@@ -463,6 +463,19 @@ extern "C" int pipesd_profile_read(pipesd_model* model, int32_t* n_launches, dou
   return PIPESD_OK;
 }
 
+extern "C" int pipesd_profile_read_each(pipesd_model* model, double* us_out, int32_t cap, int32_t* n_launches) {
+  if (!model || !n_launches || cap < 0 || (cap > 0 && !us_out)) return PIPESD_EINVAL;
+  for (size_t i = 0; i < model->prof_used; ++i) {
+    HIP_TRY(hipEventSynchronize(model->prof_events[i].second));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, model->prof_events[i].first, model->prof_events[i].second));
+    if ((int64_t)i < cap) us_out[i] = (double)ms * 1e3;
+  }
+  *n_launches = (int32_t)model->prof_used;
+  model->prof_used = 0;
+  return PIPESD_OK;
+}
+
 extern "C" int pipesd_profile_read_steps(pipesd_model* model, double* us_out, int32_t cap, int32_t* n_steps) {
   if (!model || !us_out || !n_steps || cap < 0) return PIPESD_EINVAL;
   *n_steps = 0;

@@ -68,6 +68,7 @@ _SIGS = {
     "pipesd_model_fused_launches": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64)]),
     "pipesd_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
     "pipesd_profile_read": (C.c_int, [C.c_void_p, _i32p, C.POINTER(C.c_double)]),
+    "pipesd_profile_read_each": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_int32, _i32p]),
     "pipesd_profile_read_steps": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_int32, _i32p]),
     "pipesd_batching_time": (C.c_int, [C.c_int32, _i32p, C.c_int32, C.c_double, C.c_double, C.c_double,
                                        C.POINTER(C.c_double)]),
@@ -206,6 +207,13 @@ class Model:
         n, ms = C.c_int32(), C.c_double()
         _check(_lib.pipesd_profile_read(self.handle, C.byref(n), C.byref(ms)), "pipesd_profile_read")
         return n.value, ms.value
+
+    def profile_read_each(self, cap: int = 1 << 16):
+        """Durations (us) of the timed launches since the last read, in launch order."""
+        buf = (C.c_double * cap)()
+        n = C.c_int32()
+        _check(_lib.pipesd_profile_read_each(self.handle, buf, cap, C.byref(n)), "pipesd_profile_read_each")
+        return [buf[i] for i in range(min(n.value, cap))]
 
     def profile_read_steps(self):
         """Durations (us) of the 4 * n_layers steps of the most recent fused launch."""
