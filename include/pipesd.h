@@ -299,6 +299,33 @@ int pipesd_trigger_rounds(const double *confidence, int64_t n, double r1, double
                           int32_t *lengths_out, int64_t lengths_cap, int64_t *n_rounds_out,
                           int64_t *consumed_out);
 
+/* ---- Autotuner of the trigger thresholds (Sec. 3.3 "BO autotuner"; appendix "Design and
+ * Performance Evaluation of BO"): host arithmetic only, no GPU work ------------------------------
+ *
+ * The thresholds (R1, R2) in (0,1)^2 are tuned by Bayesian optimisation of the measured time per
+ * accepted token (to be MINIMISED): Gaussian-process regression with a Matern kernel, Expected
+ * Improvement with exploration parameter xi (0.1 in the paper), one random initial sample, 16
+ * samples in all, each the mean over 20 accepted tokens.  The caller owns the loop and the
+ * measurements: it keeps the samples x (host, n pairs (R1, R2), row-major) and their measured values
+ * y (host, n), and asks for the next pair to try.  Fixed beyond what the paper names: Matern
+ * smoothness 5/2 with length scale `length_scale` on the Euclidean distance and unit variance,
+ * `noise` >= 0 added to the diagonal, observations standardised (zero mean, unit population
+ * standard deviation; scale 1 if they are all equal), no hyper-parameter fit, fp64.
+ *
+ * pipesd_bo_posterior (test hook and building block): posterior mean and standard deviation, in the
+ * units of y, at m query points q (host, m pairs) into mean_out / std_out (host, m).
+ * pipesd_bo_suggest: the maximiser of EI over the midpoints ((i + 0.5) / grid, (j + 0.5) / grid) of a
+ * uniform grid x grid raster (the first in raster order, R1 slowest, among equal values) into
+ * next_out (host, 2), and its EI on the standardised scale into *ei_out (may be NULL).
+ * EI = I Phi(I / s) + s phi(I / s) with I = min(y_s) - mu_s - xi; max(I, 0) where s = 0.
+ * PIPESD_EINVAL: null pointer, n < 1 or n > 4096, grid < 1 or > 1024, non-finite values, length_scale
+ * <= 0, negative noise or xi, or a kernel matrix that is not positive definite (the same point
+ * twice with noise 0); PIPESD_ENOMEM if the tables cannot be allocated. */
+int pipesd_bo_posterior(const double *x, const double *y, int32_t n, double length_scale, double noise,
+                        const double *q, int32_t m, double *mean_out, double *std_out);
+int pipesd_bo_suggest(const double *x, const double *y, int32_t n, double length_scale, double noise,
+                      double xi, int32_t grid, double *next_out, double *ei_out);
+
 const char *pipesd_strerror(int status);
 /* Text of the HIP call that made this thread's most recent call return PIPESD_EHIP ("" if none). */
 const char *pipesd_last_hip_error(void);

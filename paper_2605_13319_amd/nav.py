@@ -76,6 +76,10 @@ _SIGS = {
                                           C.POINTER(C.c_double)]),
     "pipesd_trigger_rounds": (C.c_int, [C.POINTER(C.c_double), C.c_int64, C.c_double, C.c_double, C.c_int32, _i32p,
                                         C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "pipesd_bo_posterior": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int32, C.c_double, C.c_double,
+                                      C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "pipesd_bo_suggest": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int32, C.c_double, C.c_double,
+                                    C.c_double, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "pipesd_strerror": (C.c_char_p, [C.c_int]),
     "pipesd_last_hip_error": (C.c_char_p, []),
 }
@@ -140,6 +144,33 @@ def trigger_rounds(confidence, r1: float, r2: float, max_len: int, cap: Optional
     _check(_lib.pipesd_trigger_rounds(c.ctypes.data_as(C.POINTER(C.c_double)), len(c), r1, r2, max_len,
                                       _ptr(out, _i32p), cap, C.byref(nr), C.byref(used)), "pipesd_trigger_rounds")
     return [int(x) for x in out[:nr.value]], int(used.value)
+
+
+_f64p = C.POINTER(C.c_double)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def bo_posterior(x, y, length_scale: float, noise: float, q):
+    """GP posterior (mean, std) of the autotuner's surrogate at the query points q [m][2]."""
+    x, y, q = _f64(x).reshape(-1, 2), _f64(y), _f64(q).reshape(-1, 2)
+    mean, std = np.empty(len(q)), np.empty(len(q))
+    _check(_lib.pipesd_bo_posterior(x.ctypes.data_as(_f64p), y.ctypes.data_as(_f64p), len(y), length_scale, noise,
+                                    q.ctypes.data_as(_f64p), len(q), mean.ctypes.data_as(_f64p),
+                                    std.ctypes.data_as(_f64p)), "pipesd_bo_posterior")
+    return mean, std
+
+
+def bo_suggest(x, y, length_scale: float, noise: float, xi: float, grid: int):
+    """((R1, R2), EI): the thresholds the autotuner tries next, given the samples so far."""
+    x, y = _f64(x).reshape(-1, 2), _f64(y)
+    nxt = np.empty(2)
+    ei = C.c_double()
+    _check(_lib.pipesd_bo_suggest(x.ctypes.data_as(_f64p), y.ctypes.data_as(_f64p), len(y), length_scale, noise, xi,
+                                  grid, nxt.ctypes.data_as(_f64p), C.byref(ei)), "pipesd_bo_suggest")
+    return (float(nxt[0]), float(nxt[1])), ei.value
 
 
 def config_of(shape) -> Config:
