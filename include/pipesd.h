@@ -209,9 +209,16 @@ int pipesd_spec_accept_static(const float *p, const float *q, const int32_t *dra
  * token; each round that runs is exactly a pipesd_nav_verify call on the state the round before
  * left.  *rounds_run (>= 1 on success) tells how many ran; accepted_len / next_token (host,
  * [n_rounds]) are filled for those.  1 <= n_rounds <= 16.
+ * bf16 models: every round is enqueued at once for the state its buffer presumes, the rule above is
+ * applied on the device (a small step behind each round's decision sets a word that gates the next
+ * round's launches: a round whose buffer is invalid streams no weights and writes no result), and
+ * the call synchronises ONCE; the host then books the rounds that ran.  fp32 models and the fused
+ * layer path apply the rule on the host between single calls (one synchronisation per round).
+ * Both give bit for bit what single calls give.
  * Errors: all argument checks (PIPESD_EINVAL), the state check (PIPESD_ESTATE) and the check that the
  * pool can hold the longest possible outcome (PIPESD_ENOMEM) come before anything changes.  A HIP
- * failure in round r > 0 leaves rounds 0..r-1 committed and *rounds_run = r.  Synchronises. */
+ * failure on the bf16 path leaves the sequence as it was before the call (*rounds_run = 0); on the
+ * host-rule path a failure in round r > 0 leaves rounds 0..r-1 committed and *rounds_run = r. */
 int pipesd_nav_verify_chain(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t prefix_len,
                             int32_t n_rounds, const int32_t *k_per_round, const int32_t *tokens_concat,
                             const float *const *draft_probs_per_round, const float *uniforms_concat,

@@ -54,6 +54,8 @@ struct pipesd_model {
   RowMap* rowmap_dev = nullptr;  // bf16 path: per-row placement of a pass that holds several clients
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
+  int32_t* chain_alive = nullptr;  // bf16 path: one word per round of a chain (round r runs iff word r holds 1)
+  const int32_t* gate = nullptr;   // the word the launches being enqueued are gated by (nullptr: they always run)
   float* row_stats = nullptr;
   unsigned long long* scan_partial = nullptr;
   int32_t* result_dev = nullptr;
@@ -253,6 +255,8 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     if (m->wide_ws_bytes && (rc = dev_alloc(m, &m->wide_ws, m->wide_ws_bytes))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->rowmap_dev, sizeof(RowMap)))) return rc;
+    if ((rc = dev_alloc(m, (void**)&m->chain_alive, 64 * sizeof(int32_t)))) return rc;
+    HIP_TRY(hipMemset(m->chain_alive, 0, 64 * sizeof(int32_t)));
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
     HIP_TRY(hipMemset(m->bar, 0, 4096));
   }
@@ -618,6 +622,7 @@ static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int row
   c.wide_ws = m->wide_ws;
   c.wide_ws_bytes = m->wide_ws_bytes;
   c.wide_mode = m->wide_mode;
+  c.gate = m->gate;
   return c;
 }
 
@@ -686,7 +691,7 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
                             bf ? ar.sa(0) : nullptr, ar.ssq_stride, single ? nullptr : m->rowmap_dev, st));
   int norm_parts = 1;  // the row setup leaves one sum of squares per row, residual epilogues one per n-tile
   bool fused = false;
-  if (bf && single && m->fused_enabled) {
+  if (bf && single && m->fused_enabled && m->gate == nullptr) {
     LayersCall lc{};
     lc.slabs = m->slabs;
     lc.final_norm = m->final_norm;
@@ -728,6 +733,7 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
     at.outp = bf ? ar.ap(l) : nullptr;
     at.act_tiles = act_tiles;
     at.batch = ab;
+    at.gate = m->gate;
     if (c.dtype == PIPESD_F32) {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);
@@ -1040,18 +1046,80 @@ extern "C" int pipesd_nav_verify_chain(pipesd_model* model, pipesd_kv* kv, int32
     if (need > (int64_t)s.blocks.size() + (int64_t)kv->free_list.size()) return PIPESD_ENOMEM;
   }
   *rounds_run = 0;
-  int32_t lp = prefix_len;
-  for (int32_t r = 0; r < n_rounds; ++r) {
-    const int32_t k = k_per_round[r];
-    if (r > 0) {  // Appendix B: the buffer survives iff all of round r-1 was accepted and the guess was right
-      if (accepted_len[r - 1] != k_per_round[r - 1] || next_token[r - 1] != tokens_concat[tok_off[r] - 1]) break;
+  hipStream_t st = (hipStream_t)stream;
+  SeqState& s = kv->seqs[seq];
+  if (model->cfg.dtype != PIPESD_BF16 || model->fused_enabled) {
+    // one synchronisation per round: the rule is applied on the host between single calls
+    int32_t lp = prefix_len;
+    for (int32_t r = 0; r < n_rounds; ++r) {
+      const int32_t k = k_per_round[r];
+      if (r > 0) {  // Appendix B: the buffer survives iff all of round r-1 was accepted and the guess was right
+        if (accepted_len[r - 1] != k_per_round[r - 1] || next_token[r - 1] != tokens_concat[tok_off[r] - 1]) break;
+      }
+      const float* qr = draft_probs_per_round ? draft_probs_per_round[r] : nullptr;
+      const int rc = pipesd_nav_verify(model, kv, seq, lp, tokens_concat + tok_off[r], k, qr,
+                                       uniforms_concat ? uniforms_concat + u_off[r] : nullptr, accepted_len + r,
+                                       next_token + r, stream);
+      if (rc) return rc;
+      lp += accepted_len[r] + 1;
+      *rounds_run = r + 1;
     }
+    return PIPESD_OK;
+  }
+  // bf16: every round is enqueued at once and the rule is applied on the device.  Round r >= 1 is
+  // enqueued for the state its buffer presumes (everything before it accepted, every guess right:
+  // its rows, positions and blocks are then known on the host) and its launches are gated by a
+  // device word that the step behind round r-1's decision sets: a round whose buffer turned out to
+  // be invalid streams no weights and reports (-1, -1).  One synchronisation for the whole chain.
+  const size_t text0 = s.text.size();
+  auto give_up = [&]() {  // back to the state before the call
+    s.text.resize(text0);
+    release_beyond(kv, s, (int32_t)text0 - 1);
+  };
+  for (int32_t r = 0; r < n_rounds; ++r) model->result_host[4 + 2 * r] = model->result_host[4 + 2 * r + 1] = -1;
+  int rc = PIPESD_OK;
+  for (int32_t r = 0; r < n_rounds && rc == PIPESD_OK; ++r) {
+    const int32_t k = k_per_round[r];
     const float* qr = draft_probs_per_round ? draft_probs_per_round[r] : nullptr;
-    const int rc = pipesd_nav_verify(model, kv, seq, lp, tokens_concat + tok_off[r], k, qr,
-                                     uniforms_concat ? uniforms_concat + u_off[r] : nullptr, accepted_len + r,
-                                     next_token + r, stream);
+    model->gate = r == 0 ? nullptr : model->chain_alive + r;
+    rc = enqueue_verify(model, kv, seq, tokens_concat + tok_off[r], k, qr, uniforms_concat ? uniforms_concat + u_off[r] : nullptr,
+                        model->result_dev + 2 * r, model->result_host + 4 + 2 * r, st);
+    model->gate = nullptr;
+    if (rc) break;
+    const bool more = r + 1 < n_rounds;
+    const hipError_t e = launch_chain_step(model->result_dev + 2 * r, model->result_host + 4 + 2 * r, k,
+                                           more ? tokens_concat[tok_off[r + 1] - 1] : -1,
+                                           r == 0 ? nullptr : model->chain_alive + r, more ? model->chain_alive + r + 1 : nullptr, st);
+    if (e != hipSuccess) {
+      rc = hip_fail(e, "chain step");
+      break;
+    }
+    if (more) {  // the state round r + 1 presumes
+      s.text.insert(s.text.end(), tokens_concat + tok_off[r], tokens_concat + tok_off[r] + k);
+      s.text.push_back(tokens_concat[tok_off[r + 1] - 1]);
+    }
+  }
+  const hipError_t es = hipStreamSynchronize(st);
+  if (rc || es != hipSuccess) {
+    give_up();
+    return rc ? rc : hip_fail(es, "chained verify");
+  }
+  s.text.resize(text0);  // (the blocks reserved for the presumed states stay until the rounds are booked)
+  // book the rounds that ran, one after the other, exactly as single calls would have
+  for (int32_t r = 0; r < n_rounds; ++r) {
+    const int32_t a = model->result_host[4 + 2 * r], nxt = model->result_host[4 + 2 * r + 1];
+    if (r > 0 && (accepted_len[r - 1] != k_per_round[r - 1] || next_token[r - 1] != tokens_concat[tok_off[r] - 1])) {
+      if (a != -1) return hip_fail(hipErrorLaunchFailure, "a round of the chain ran although its buffer was invalid");
+      break;
+    }
+    // booking a round gives back the blocks beyond the rows it kept, those of later rounds included;
+    // a later round that ran kept all rows before it, so its own blocks are reserved again (the free
+    // list hands back the very blocks it was given last)
+    rc = ensure_blocks(kv, seq, (int32_t)s.text.size() + k_per_round[r], st);
+    if (rc == PIPESD_OK)
+      rc = commit_verify(model, kv, seq, tokens_concat + tok_off[r], k_per_round[r], model->result_host + 4 + 2 * r,
+                         accepted_len + r, next_token + r);
     if (rc) return rc;
-    lp += accepted_len[r] + 1;
     *rounds_run = r + 1;
   }
   return PIPESD_OK;

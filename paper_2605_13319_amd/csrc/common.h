@@ -161,6 +161,9 @@ struct GemmCall {
   int wide_mode = 0;  // 0: kernel chosen by shape, 1: narrow kernel, 2: wide kernel
   // optional: events that take the kernel's own start and end (no marker packets around it)
   hipEvent_t ev_start = nullptr, ev_stop = nullptr;
+  // optional device word: the launch does nothing if it holds 0 (a round of a chain whose buffer
+  // turned out to be invalid; narrow kernel only)
+  const int32_t* gate = nullptr;
 };
 hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st);
 int device_cu_count();
@@ -240,6 +243,7 @@ struct AttnCall {
   void* outp;      // bf16 cache: packed output (ActPack with n_q_heads*head_dim columns)
   int act_tiles;   // bf16 cache: row tiles of outp
   AttnBatch batch; // bf16 cache: the clients of the pass
+  const int32_t* gate = nullptr;  // bf16 cache: optional device word, the launches do nothing if it holds 0
 };
 int attn_nsplit(int total_tokens, int chunk);
 int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type
@@ -302,6 +306,12 @@ hipError_t launch_kv_trim(int dtype, const KvView& kv, int n_layers, int first_p
                           hipStream_t st);
 
 hipError_t launch_set_table(int32_t* table, int first, const int32_t* entries, int n, hipStream_t st);
+// One step of a chain of rounds on proactively sent drafts: if the round was not alive (alive_in
+// holds 0; nullptr = alive), its decision is replaced by (-1, -1); alive_out (if not null) tells
+// whether the next round's buffer is valid: this round alive, all k drafts accepted and the extra
+// token equal to `guess`.
+hipError_t launch_chain_step(int32_t* result, int32_t* result_copy, int k, int guess, const int32_t* alive_in,
+                             int32_t* alive_out, hipStream_t st);
 // words[0..n-1] = 0 by a small kernel (usable where a memset node is not: under graph capture)
 hipError_t launch_clear_words(unsigned* words, int n, hipStream_t st);
 

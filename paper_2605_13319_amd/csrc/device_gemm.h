@@ -63,6 +63,7 @@ struct GemmArgs {
   int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1..8)
   int act_tiles;          // row tiles of the pass's ActPack buffers
   float eps;
+  const int32_t* gate;    // optional: the launch does nothing if this device word holds 0
 };
 
 // passes of at least this many row tiles take the wide kernel (kernels_gemm_wide.hip); `a` comes

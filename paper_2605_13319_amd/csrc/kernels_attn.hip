@@ -96,8 +96,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(const float*
 // largest client / qpw); a workgroup takes qpw query tiles (MULTI) or one
 template <int HD, bool MULTI>
 __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float* q, KvView kv, int layer, int n_q_heads,
-                                                                    AttnBatch batch, float* part, int qpw) {
+                                                                    AttnBatch batch, float* part, int qpw,
+                                                                    const int32_t* gate) {
   extern __shared__ float lds[];
+  if (gate != nullptr && *gate == 0) return;  // (uniform: a round of a chain that does not run)
   const int kvh = blockIdx.x;
   int ci = 0, split = blockIdx.y;
   while (ci + 1 < batch.n && split >= batch.c[ci].nsplit) split -= batch.c[ci++].nsplit;
@@ -111,7 +113,8 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 
 // grid = (threads of the largest client / 64, clients)
 __global__ __launch_bounds__(64) void attn_merge_packed_kernel(const float* part, int n_q_heads, int h, AttnBatch batch,
-                                                              uint4* outp, int act_tiles) {
+                                                              uint4* outp, int act_tiles, const int32_t* gate) {
+  if (gate != nullptr && *gate == 0) return;
   const AttnClient c = batch.c[blockIdx.y];
   attn_merge_thread<false>(part + c.part_off, c.m, n_q_heads, h, c.nsplit, (u32x4*)outp,
                            blockIdx.x * blockDim.x + threadIdx.x, c.row_off, act_tiles);
@@ -191,13 +194,13 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     }
     const dim3 block(kAttnWaves * 64);
     if (h == 128 && qpw > 1)
-      attn_mfma_kernel<128, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+      attn_mfma_kernel<128, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw, c.gate);
     else if (h == 128)
-      attn_mfma_kernel<128, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+      attn_mfma_kernel<128, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw, c.gate);
     else if (qpw > 1)
-      attn_mfma_kernel<64, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+      attn_mfma_kernel<64, true><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw, c.gate);
     else
-      attn_mfma_kernel<64, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw);
+      attn_mfma_kernel<64, false><<<grid, block, lds, st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, qpw, c.gate);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -209,7 +212,7 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     for (int i = 0; i < c.batch.n; ++i) max_m = c.batch.c[i].m > max_m ? c.batch.c[i].m : max_m;
     const int threads = max_m * c.n_q_heads * (h / 8);
     attn_merge_packed_kernel<<<dim3((threads + 63) / 64, c.batch.n), 64, 0, st>>>(c.part, c.n_q_heads, h, c.batch,
-                                                                                   (uint4*)c.outp, c.act_tiles);
+                                                                                   (uint4*)c.outp, c.act_tiles, c.gate);
   }
   return hipGetLastError();
 }

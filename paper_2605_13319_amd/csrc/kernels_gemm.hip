@@ -15,7 +15,8 @@ namespace pipesd {
 template <int KSTEPS, bool NT, int EPI, bool P1>
 __global__ __launch_bounds__(512) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ float lds[];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (a.gate != nullptr && *a.gate == 0) return;  // (uniform: a round of a chain that does not run)
+  const int w = threadIdx.x >> 6;
   // One team per workgroup: all W waves of the workgroup.  With rt row tiles the workgroups b,
   // b + 8, .. b + 8 (rt - 1) form a group on the same tiles (16 rows of the pass each): workgroups
   // are dealt to the 8 chiplets round robin, so a group shares an L2 and the weights cross the
@@ -108,6 +109,8 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.eps = c.eps;
   a.row_tiles = row_tiles;
   a.act_tiles = c.act_tiles;
+  a.gate = c.gate;
+  if (c.gate != nullptr && row_tiles >= kWideMinRowTiles) return hipErrorInvalidValue;  // the wide kernel has no gate
   if (row_tiles >= kWideMinRowTiles && c.act_tiles == 8 &&
       (c.wide_mode == 2 || (c.wide_mode == 0 && gemm_wide_preferred(c.N, c.K))))
     return launch_gemm_wide(c, a, st);

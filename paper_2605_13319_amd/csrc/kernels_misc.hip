@@ -262,6 +262,23 @@ hipError_t launch_set_table(int32_t* table, int first, const int32_t* entries, i
   return hipSuccess;
 }
 
+__global__ void chain_step_kernel(int32_t* result, int32_t* result_copy, int k, int guess, const int32_t* alive_in,
+                                  int32_t* alive_out) {
+  if (threadIdx.x != 0) return;
+  const bool alive = alive_in == nullptr || *alive_in != 0;
+  if (!alive) {
+    result[0] = result[1] = -1;
+    if (result_copy != nullptr) result_copy[0] = result_copy[1] = -1;
+  }
+  if (alive_out != nullptr) *alive_out = (alive && result[0] == k && result[1] == guess) ? 1 : 0;
+}
+
+hipError_t launch_chain_step(int32_t* result, int32_t* result_copy, int k, int guess, const int32_t* alive_in,
+                             int32_t* alive_out, hipStream_t st) {
+  chain_step_kernel<<<1, 64, 0, st>>>(result, result_copy, k, guess, alive_in, alive_out);
+  return hipGetLastError();
+}
+
 __global__ void clear_words_kernel(unsigned* words, int n) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) words[i] = 0u;
 }

@@ -520,3 +520,63 @@ def test_chained_rounds_on_proactive_buffers(nav, wl_name, tol):
     kv.rollback(0, lp)
     out = kv.nav_verify_chain(0, [(d0, q0, u0), ([(x0 + 1) % shape.vocab] + d1, q1, u1)])
     assert out == [(a0, x0)] and kv.length(0) == lp + 4
+
+
+def test_device_chained_rounds_at_the_8b_width(nav):
+    """The chain whose rule runs on the device (bf16: every round enqueued at once, launches of a
+    round gated by a device word, one synchronisation) against single calls with the rule applied by
+    hand, at the 8B widths (2 layers): four rounds that all run (the target's own greedy text), a
+    wrong guess in the third buffer, a rejected draft in the second round; bit for bit, and the
+    sequences end in the same state.  Prints what the chain saves over synchronising every round."""
+    import time
+    import torch
+    wl = I.WORKLOADS["llama-8b"]
+    shape, seed = wl["shape"].truncated(2), wl["seed"]
+    model = nav.Model(shape, I.make_weights(shape, seed + I.SEED_WEIGHTS))
+    prefix = 300
+    kv = nav.KVCache(model, max_seqs=2, n_blocks=2 * 24)
+    toks = I.make_tokens(prefix, shape.vocab, seed + I.SEED_PREFIX)
+    kv.prefill(0, toks)
+    kv.prefill(1, toks)
+    # the target's own greedy continuation according to the GPU: 20 tokens
+    text = []
+    for _ in range(20):
+        z = kv.forward_logits(1, text)
+        text.append(int(np.argmax(z[-1])))
+    good = [(text[0:4], None, None), (text[4:9], None, None), (text[9:14], None, None), (text[14:19], None, None)]
+    wrong_guess = [(text[0:4], None, None), (text[4:9], None, None), ([(text[9] + 1) % shape.vocab] + text[10:14], None, None),
+                   (text[14:19], None, None)]
+    rejected = [(text[0:4], None, None), ([text[4], text[5], (text[6] + 7) % shape.vocab, text[7], text[8]], None, None),
+                (text[9:14], None, None)]
+    q = I.make_random_probs(4, shape.vocab, 91)
+    sampling = [(text[0:4], np.full((4, shape.vocab), 1e-30, dtype=np.float32), I.make_uniforms(5, 92)),
+                ([0] + [int(t) for t in I.make_tokens(4, shape.vocab, 93)], q, I.make_uniforms(5, 94))]
+    for name, rounds, want_rounds in (("good", good, 4), ("wrong guess", wrong_guess, 2), ("rejected draft", rejected, 2),
+                                      ("sampling", sampling, None)):
+        if name == "sampling":  # the guess of round 1 = whatever round 0 draws on the GPU
+            a0, x0 = kv.nav_verify(1, rounds[0][0], rounds[0][1], rounds[0][2])
+            kv.rollback(1, prefix)
+            rounds = [rounds[0], ([x0] + rounds[1][0][1:], rounds[1][1], rounds[1][2])]
+        out = kv.nav_verify_chain(0, rounds)
+        ref = _chain_by_hand(kv, 1, rounds)
+        assert out == ref, (name, out, ref)
+        assert want_rounds is None or len(out) == want_rounds, (name, out)
+        assert kv.length(0) == kv.length(1) and kv.seq_blocks(0) == kv.seq_blocks(1)
+        probe = I.make_tokens(3, shape.vocab, 95)
+        np.testing.assert_array_equal(kv.forward_logits(0, probe), kv.forward_logits(1, probe))  # same cache behind
+        kv.rollback(0, prefix)
+        kv.rollback(1, prefix)
+    # timing: the four-round chain against four single calls (a synchronisation per round)
+    t_chain, t_single = [], []
+    for _ in range(10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        kv.nav_verify_chain(0, good)
+        t_chain.append(time.perf_counter() - t0)
+        t0 = time.perf_counter()
+        _chain_by_hand(kv, 1, good)
+        t_single.append(time.perf_counter() - t0)
+        kv.rollback(0, prefix)
+        kv.rollback(1, prefix)
+    print(f"4 chained rounds (2 layers): {np.median(t_chain) * 1e3:.3f} ms with one synchronisation, "
+          f"{np.median(t_single) * 1e3:.3f} ms as single calls", flush=True)
