@@ -485,7 +485,7 @@ def extra_configs(np, torch, I, nav, model8, kv8, shape8, seed8, prefix8, sigma8
     # the k sweep of the 8B workload on the resident model and cache
     for kk in (1, 4, 16):
         guarded(f"llama-8b prefix {prefix8} k={kk} batch 1",
-                lambda kk=kk: single_client_record(np, torch, I, nav, model8, shape8, seed8, prefix8, kk, sigma8, 20, 5, kv=kv8))
+                lambda kk=kk: single_client_record(np, torch, I, nav, model8, shape8, seed8, prefix8, kk, sigma8, 20, 20, kv=kv8))
     # 16 clients on the 8B model: prefixes U[256,4096], k U[1,16] redrawn every round, noisy-target
     # drafts, 50 consecutive rounds over sequences that grow
     def cfg4():

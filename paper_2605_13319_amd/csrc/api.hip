@@ -54,6 +54,7 @@ struct pipesd_model {
   RowMap* rowmap_dev = nullptr;  // bf16 path: per-row placement of a pass that holds several clients
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
+  unsigned* attn_count = nullptr;  // arrival counters of the streaming attention kernel (zero between launches)
   int32_t* chain_alive = nullptr;  // bf16 path: one word per round of a chain (round r runs iff word r holds 1)
   const int32_t* gate = nullptr;   // the word the launches being enqueued are gated by (nullptr: they always run)
   float* row_stats = nullptr;
@@ -255,6 +256,8 @@ static int build_device_model(pipesd_model* m, const pipesd_weights* w) {
     if (m->wide_ws_bytes && (rc = dev_alloc(m, &m->wide_ws, m->wide_ws_bytes))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->step_clock, ((size_t)4 * L + 1) * 8))) return rc;
     if ((rc = dev_alloc(m, (void**)&m->rowmap_dev, sizeof(RowMap)))) return rc;
+    if ((rc = dev_alloc(m, (void**)&m->attn_count, kAttnCounters * sizeof(unsigned)))) return rc;
+    HIP_TRY(hipMemset(m->attn_count, 0, kAttnCounters * sizeof(unsigned)));
     if ((rc = dev_alloc(m, (void**)&m->chain_alive, 64 * sizeof(int32_t)))) return rc;
     HIP_TRY(hipMemset(m->chain_alive, 0, 64 * sizeof(int32_t)));
     if ((rc = dev_alloc(m, (void**)&m->bar, 4096))) return rc;
@@ -307,7 +310,9 @@ static size_t attn_scratch_bound(const pipesd_model* m, int64_t pool_tokens) {
   const int chunk = attn_chunk_tokens(m->cfg.dtype);
   const int64_t clients = m->cfg.dtype == PIPESD_BF16 ? kMaxPassClients : 1;
   const int64_t splits = pool_tokens / chunk + clients;
-  return (size_t)kMaxRows * (size_t)splits * m->cfg.n_q_heads * (m->cfg.head_dim + 4);
+  // (the streaming kernel splits no finer but rounds a head group's rows up to whole pairs of 16-row tiles)
+  const int64_t group_rows = (int64_t)(m->cfg.n_q_heads / m->cfg.n_kv_heads) * kMaxRows + 31;
+  return (size_t)splits * (size_t)(group_rows * m->cfg.n_kv_heads) * (m->cfg.head_dim + 4);
 }
 
 extern "C" int pipesd_kv_create(const pipesd_model* model, int32_t max_seqs, int32_t block_tokens, void* pool,
@@ -678,7 +683,12 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
   }
   // per-layer partial buffers only where the all-layers kernel may run (one client); otherwise one, reused
   const bool part_per_layer = bf && single && rows <= 16;
-  int rc = ensure_attn_scratch(m, part_floats * (part_per_layer ? c.n_layers : 1));
+  // passes of few rows per client: the streaming attention kernel with its own split of every context
+  AttnBatch ab_stream = ab;
+  size_t stream_floats = 0;
+  const bool may_fuse = bf && single && m->fused_enabled && m->gate == nullptr;
+  const int stream_tiles = bf && !may_fuse ? attn_stream_plan(c.n_q_heads, c.n_kv_heads, c.head_dim, ab_stream, &stream_floats) : 0;
+  int rc = ensure_attn_scratch(m, std::max(part_floats * (part_per_layer ? c.n_layers : 1), stream_tiles ? stream_floats : 0));
   if (rc) return rc;
   ActArena& ar = rows <= 2 * 16 ? m->arena : m->arena_big;
   const int act_tiles = rows <= 2 * 16 ? 2 : kMaxPassRows / 16;
@@ -732,8 +742,11 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
     at.out = m->attn_out;
     at.outp = bf ? ar.ap(l) : nullptr;
     at.act_tiles = act_tiles;
-    at.batch = ab;
+    at.batch = stream_tiles ? ab_stream : ab;
     at.gate = m->gate;
+    at.stream_tiles = stream_tiles;
+    at.counters = m->attn_count;
+    if (stream_tiles) at.part = m->attn_part;
     if (c.dtype == PIPESD_F32) {
       {
         ProfScope ps(m, PIPESD_PROF_GEMM_QKV, st);

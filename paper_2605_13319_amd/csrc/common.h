@@ -55,7 +55,8 @@ constexpr int kMaxPassClients = 16;  // clients whose rows share one pass (each 
 struct AttnClient {
   int32_t row_off, m, start_pos;  // the client's rows in the pass; position of its first row
   int32_t table_off;              // entries from KvView::table to the client's block table
-  int32_t nsplit, part_off;       // 256-token splits; floats from the partial buffer's start to the client's partials
+  int32_t nsplit, part_off;       // splits of its context; floats from the partial buffer's start to the client's partials
+  int32_t span, count_off;        // streaming kernel: tokens per split, the client's first arrival counter
 };
 struct AttnBatch {
   int32_t n;
@@ -244,9 +245,18 @@ struct AttnCall {
   int act_tiles;   // bf16 cache: row tiles of outp
   AttnBatch batch; // bf16 cache: the clients of the pass
   const int32_t* gate = nullptr;  // bf16 cache: optional device word, the launches do nothing if it holds 0
+  int stream_tiles = 0;           // bf16 cache: 0, or the query tiles per workgroup of the streaming kernel (batch planned by attn_stream_plan)
+  unsigned* counters = nullptr;   // streaming kernel: kAttnCounters arrival counters, zero between launches
 };
 int attn_nsplit(int total_tokens, int chunk);
 int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type
+// Passes of at most kMaxRows rows per client (bf16 cache) take the streaming kernel.  Fills span,
+// nsplit, part_off and count_off of every client of `b` (row_off, m, start_pos, table_off given) and
+// returns the query tiles per workgroup, or 0 if the pass does not fit (then the split kernels run);
+// *part_floats = size of the partial buffer the launch needs.  A client's split depends on its own
+// context only, so its results do not depend on who shares the pass.
+constexpr int kAttnCounters = kMaxPassClients * 512;
+int attn_stream_plan(int n_q_heads, int n_kv_heads, int head_dim, AttnBatch& b, size_t* part_floats);
 hipError_t launch_attention(const AttnCall& c, hipStream_t st);
 
 // ---- vocabulary-wide decision ----

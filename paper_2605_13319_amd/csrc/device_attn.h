@@ -216,27 +216,20 @@ __device__ __forceinline__ void attn_task(const float* q, const KvView& kv, int 
   }
 }
 
-// Merge the splits of one (row, head): one thread per 8 consecutive elements, all of a batch's loads
-// issued before any is used; the result is written packed for the O projection.  `gt` numbers the
-// threads over all (pair, segment) tasks.
-// `row_off`: the client's first row in the pass (rows of the packed output).
-template <bool CO>
-__device__ __forceinline__ void attn_merge_thread(const float* part, int m, int n_q_heads, int h, int nsplit,
-                                                  u32x4* outp, int gt, int row_off = 0, int act_tiles = 2) {
+// Merge the splits of one (row, head) for 8 consecutive elements e0..e0+7: o = sum_s e^{m_s - M} o_s /
+// sum_s e^{m_s - M} l_s, splits taken in index order, all of a batch's loads issued before any is
+// used.  `row_of(s)` points at split s's partial row [h values, max, sum, 2 unused].
+template <typename RowOf>
+__device__ __forceinline__ void attn_merge_rows(RowOf row_of, int nsplit, int h, int e0, float (&acc)[8]) {
   constexpr int BATCH = 9;
-  const int segs = h / 8;
-  const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
-  if (pair >= m * n_q_heads) return;
-  const int head = pair / m, r = pair % m;
-  const float* p = part + (size_t)pair * nsplit * (h + kPartPad);
-  float M = -INFINITY, L = 0.f, acc[8];
+  float M = -INFINITY, L = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
   for (int s0 = 0; s0 < nsplit; s0 += BATCH) {
     au32x4 mlr[BATCH], oar[BATCH], obr[BATCH];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const float* ps = p + (size_t)min(s0 + j, nsplit - 1) * (h + kPartPad);
+      const float* ps = row_of(min(s0 + j, nsplit - 1));
       mlr[j] = *(const au32x4*)(ps + h);
       oar[j] = *(const au32x4*)(ps + e0);
       obr[j] = *(const au32x4*)(ps + e0 + 4);
@@ -271,6 +264,21 @@ __device__ __forceinline__ void attn_merge_thread(const float* part, int m, int 
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] /= L;
+}
+
+// One thread of the merge of a pass's partials [(head*m + r)*nsplit + split][h + 4]; the result is
+// written packed for the O projection.  `gt` numbers the threads over all (pair, segment) tasks.
+// `row_off`: the client's first row in the pass (rows of the packed output).
+template <bool CO>
+__device__ __forceinline__ void attn_merge_thread(const float* part, int m, int n_q_heads, int h, int nsplit,
+                                                  u32x4* outp, int gt, int row_off = 0, int act_tiles = 2) {
+  const int segs = h / 8;
+  const int pair = gt / segs, e0 = (gt % segs) * 8;  // pair = head * m + r
+  if (pair >= m * n_q_heads) return;
+  const int head = pair / m, r = pair % m;
+  const float* p = part + (size_t)pair * nsplit * (h + kPartPad);
+  float acc[8];
+  attn_merge_rows([&](int s) { return p + (size_t)s * (h + kPartPad); }, nsplit, h, e0, acc);
   store_act8x<CO>(outp, row_off + r, head * h + e0, acc, act_tiles);
 }
 

@@ -315,9 +315,12 @@ def test_llama_13b_width_long_context_consistency(nav):
 
 @pytest.mark.parametrize("shape,prefix,k", [(SMALL_BF16, 70, 8), (SMALL_MHA, 300, 15),
                                             (I.WORKLOADS["llama-8b"]["shape"].truncated(2), 600, 8)])
-def test_fused_layer_kernel_is_bit_identical_to_per_projection_launches(nav, shape, prefix, k):
-    """One cooperative kernel for all layers vs one kernel per projection: same device code, same
-    tiles, same order, so the logits and the cache must agree bit for bit."""
+def test_fused_layer_kernel_agrees_with_per_projection_launches(nav, shape, prefix, k):
+    """One cooperative kernel for all layers (opt-in) vs one kernel per projection: the projections
+    run the same device code on the same tiles in the same order; attention sums the context in
+    256-token splits there and in the streaming kernel's order here, so logits agree to rounding
+    (1e-4) and the cached keys and values to a bf16 rounding step; the fused kernel itself is
+    reproducible bit for bit."""
     w = I.make_weights(shape, 77)
     toks = I.make_tokens(prefix, shape.vocab, 78)
     d = I.make_tokens(k, shape.vocab, 79)
@@ -331,14 +334,14 @@ def test_fused_layer_kernel_is_bit_identical_to_per_projection_launches(nav, sha
     kv.prefill(1, toks)
     z_fused = kv.forward_logits(1, d)
     assert model.fused_launches() > 0
-    np.testing.assert_array_equal(z_plain, z_fused)
+    np.testing.assert_array_equal(z_fused, kv.forward_logits(1, d))
+    np.testing.assert_allclose(z_plain, z_fused, rtol=0, atol=1e-4)
     for layer in range(shape.n_layers):
-        for pos in (0, prefix // 2, prefix - 2, prefix - 1 + k):
-            k0, v0 = kv.read_kv(0, layer, pos) if pos < prefix - 1 else (None, None)
-            if k0 is not None:
-                k1, v1 = kv.read_kv(1, layer, pos)
-                np.testing.assert_array_equal(k0, k1)
-                np.testing.assert_array_equal(v0, v1)
+        for pos in (0, prefix // 2, prefix - 2):
+            k0, v0 = kv.read_kv(0, layer, pos)
+            k1, v1 = kv.read_kv(1, layer, pos)
+            np.testing.assert_allclose(k0, k1, rtol=2 ** -7, atol=1e-6)
+            np.testing.assert_allclose(v0, v1, rtol=2 ** -7, atol=1e-6)
     # and the whole pass, twice (the barrier counters are reset per launch)
     q = I.make_random_probs(k, shape.vocab, 80)
     u = I.make_uniforms(k + 1, 81)
