@@ -3,12 +3,16 @@
 // At this many rows the activations of a K slice no longer fit a wave's registers, and spreading the
 // rows over workgroups that re-read the weights from the L2 (the narrow kernel's way) moves eight
 // times the weights through it.  Here a workgroup of four waves multiplies ALL rows of the pass with
-// 8 n-tiles of weights: the activations of four k-steps at a time are staged in LDS in the lane
-// order the matrix cores consume (double buffered, one barrier per stage; all 8 row tiles of the
-// buffers are staged and multiplied, rows past the pass are just never stored), every weight fragment
-// comes straight from memory into the A-operand registers of the one pair of waves that needs it,
-// and each wave owns a 64-column x 64-row block of the product (4 x 4 accumulator tiles), so every
-// LDS read feeds four MFMAs.
+// 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they get there
+// without passing through registers: every wave asks for its share of a stage's fragments (two
+// k-steps: 8 weight fragments and the live row tiles' activation fragments, hi and lo, per k-step)
+// with loads that write straight into LDS, into a ring of three stage buffers, two stages ahead of
+// the multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
+// consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this
+// wave's loads of the stage have landed (they return in order: all but the next stage's may be
+// outstanding), one workgroup barrier, request the stage after next into the buffer the barrier
+// has just freed, multiply.  Each wave owns a 64-column x (live row tiles / 2)-tile block of the
+// product (row tiles r*2 + wm), so every weight fragment read from LDS feeds up to eight MFMAs.
 //
 // Results are bit-identical to the narrow kernel's, row by row: K is cut into the same W * P slices
 // of 512 columns, every slice is accumulated from zero in the same k-step order (hi half, then lo
@@ -24,12 +28,15 @@
 
 namespace pipesd {
 
-constexpr int kWideStage = 4;       // k-steps per LDS stage
-constexpr int kWideRowTiles = 8;    // row tiles of the staged activations (= ActPack row tiles of a wide pass)
+constexpr int kWideStage = 2;       // k-steps per ring stage
+constexpr int kWideRing = 3;        // stage buffers
+constexpr int kWideRowTiles = 8;    // row tiles of the packed activations of a wide pass (ActPack row tiles)
 constexpr int kWideWgTiles = 8;     // n-tiles per workgroup: 2 wave columns x 4
-constexpr int kWideAhead = 3;       // blocks of LDS operand reads in flight ahead of the multiplies
-constexpr int kWideFrags = kWideStage * kWideRowTiles * 2;  // 1 KB fragments per stage
-constexpr size_t kWideLdsBytes = 2 * kWideFrags * 1024 + kWideRowTiles * 16 * sizeof(float);
+constexpr int kWideSliceStages = 16 / kWideStage;  // stages per 512-column slice
+// 1 KB fragments of one k-step in a stage buffer: the 8 weight fragments, then (row tile, half)
+constexpr int wide_kstep_frags(int rtl) { return kWideWgTiles + 2 * rtl; }
+constexpr size_t kWideLdsBytes =
+    (size_t)kWideRing * kWideStage * wide_kstep_frags(kWideRowTiles) * 1024 + kWideRowTiles * 16 * sizeof(float);
 
 struct WideArgs {
   f32x4* partials;  // split: [W][ntiles][8][64] running sums of role w
@@ -62,119 +69,137 @@ __device__ __forceinline__ void wide_rstd_rows(const GemmArgs& a, int row0, int 
   }
 }
 
-template <bool WHOLE, bool P1>
+// one 1 KB fragment from memory straight into LDS: lane i's 16 bytes land at dst + 16 i (dst is the
+// same for the whole wave); the load counts as one outstanding vector-memory load until it has landed
+__device__ __forceinline__ void frag_to_lds(const u32x4* src_lane, u32x4* dst_wave) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_lane,
+                                   (void __attribute__((address_space(3)))*)dst_wave, 16, 0, 0);
+}
+
+// RTL: live row tiles of the pass rounded up to even (4, 6 or 8)
+template <bool WHOLE, bool P1, int RTL>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
   extern __shared__ float lds_f[];
-  u32x4* bl = (u32x4*)lds_f;                          // [2 stages][kWideFrags][64 lanes]
-  float* rstd_lds = lds_f + 2 * kWideFrags * 64 * 4;  // [128]
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int wm = w & 1, wn = w >> 1;  // this wave: row tiles wm*4..+3, n-tiles wn*4..+3 of the group
+  constexpr int KF = wide_kstep_frags(RTL);           // fragments per k-step
+  constexpr int SF = kWideStage * KF;                 // fragments per stage buffer
+  constexpr int NPER = kWideStage * (2 + RTL / 2);    // fragments this wave requests per stage
+  constexpr int RW = RTL / 2;                         // row tiles per wave
+  u32x4* bl = (u32x4*)lds_f;                          // [kWideRing][SF][64 lanes]
+  float* rstd_lds = lds_f + (kWideLdsBytes - kWideRowTiles * 16 * sizeof(float)) / sizeof(float);  // [128]
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = w & 1, wn = w >> 1;  // this wave: row tiles r*2 + wm, n-tiles wn*4..+3 of the group
   const int nrole = WHOLE ? 1 : a.W;
   const int cg = (int)blockIdx.x / nrole, role = (int)blockIdx.x % nrole;
   const int nsl = (WHOLE ? a.W : 1) * a.P;  // slices this workgroup walks
-  constexpr int kStages = 16 / kWideStage;  // stages per slice (even: the LDS buffer of a stage is its parity)
-  constexpr int nblk = kWideStage * 4;      // (k-step, row tile) blocks per stage
 
-  const u32x4* wbase[4];
+  // the two weight fragments per k-step this wave brings in: n-tiles w and w + 4 of the group
+  const u32x4* wsrc[2];
 #pragma unroll
-  for (int ra = 0; ra < 4; ++ra) {
-    const int t = min(cg * kWideWgTiles + wn * 4 + ra, a.ntiles - 1);
-    wbase[ra] = a.wp + lane + (size_t)t * a.kst * 64;
+  for (int i = 0; i < 2; ++i) {
+    const int t = min(cg * kWideWgTiles + w + 4 * i, a.ntiles - 1);
+    wsrc[i] = a.wp + lane + (size_t)t * a.kst * 64;
   }
   // first k-step of stage s of the j-th slice this workgroup walks
   auto kstep0 = [&](int j, int s) {
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
     return (p * a.W + wj) * 16 + s * kWideStage;
   };
-  // wave w stages k-step w of a stage: 16 fragments (row tile, half); ActPack fragments are already
-  // in consumer lane order
-  auto b_src = [&](int k0) { return a.actp + (size_t)(k0 + w) * (kWideRowTiles * 2 * 64) + lane; };
-  u32x4 areg[2][4][kWideStage], breg[2 * kWideRowTiles];
-  auto store_b = [&](int buf) {
-    u32x4* dst = bl + ((size_t)buf * kWideFrags + w * (2 * kWideRowTiles)) * 64 + lane;
+  // request this wave's share of the stage whose first k-step is k0 into ring buffer `buf`
+  auto request = [&](int k0, int buf) {
+    u32x4* dst = bl + (size_t)buf * SF * 64;
 #pragma unroll
-    for (int i = 0; i < 2 * kWideRowTiles; ++i) dst[i * 64] = breg[i];
+    for (int ks = 0; ks < kWideStage; ++ks) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) frag_to_lds(wsrc[i] + (size_t)(k0 + ks) * 64, dst + (ks * KF + w + 4 * i) * 64);
+      // activation fragments (row tile, half) = w + 4 i of the k-step (ActPack is in consumer lane order)
+      const u32x4* asrc = a.actp + (size_t)(k0 + ks) * (kWideRowTiles * 2 * 64) + lane;
+#pragma unroll
+      for (int i = 0; i < RTL / 2; ++i)
+        frag_to_lds(asrc + (w + 4 * i) * 64, dst + (ks * KF + kWideWgTiles + w + 4 * i) * 64);
+    }
   };
 
   // acc: the slice being accumulated; run: running sum of this role's slices (P > 1); tot: sum of
   // the finished roles (WHOLE)
-  f32x4 acc[4][4], run[4][4], tot[4][4];
+  f32x4 acc[4][RW], run[4][RW], tot[4][RW];
   const f32x4 zero = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int ra = 0; ra < 4; ++ra)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) acc[ra][r] = run[ra][r] = tot[ra][r] = zero;
+    for (int r = 0; r < RW; ++r) acc[ra][r] = run[ra][r] = tot[ra][r] = zero;
 
-  {
-    const int k0 = kstep0(0, 0);
+  // The multiplies run as one stream of blocks (k-step, row tile of this wave): 8 MFMAs on a pair of
+  // activation fragments (hi, lo) and the k-step's 4 weight fragments.  Operands are read from LDS
+  // kAhead blocks ahead of their block.  When the block to read is the first of a stage, that stage
+  // must have landed: this wave's loads of it have once at most the next stage's are outstanding,
+  // and behind the workgroup barrier every wave's have.  The same wait covers this wave's own LDS
+  // reads, so behind the barrier nobody reads the stage before any more, and its buffer takes the
+  // stage after next.  Past the end of the walk the workgroup's first stages are requested and read
+  // again (and never used), so the counts hold to the end.
+  constexpr int kAhead = 3;
+  constexpr int BPS = kWideStage * RW;           // blocks per stage (>= 4 > kAhead)
+  constexpr int BPSL = kWideSliceStages * BPS;   // blocks per slice (a multiple of 4)
+  u32x4 bq[kAhead + 1][2];                       // ring of activation operand pairs
+  u32x4 wfb[4][4];                               // weight fragments of the last 4 k-steps
+  int rb = 0;                                    // ring buffer of the stage being read
+  // read the operands of block b of the stage in buffer `buf`; kq = its k-step within the slice
+  auto read_block = [&](int buf, int b, int kq, int slot) {
+    const u32x4* sb = bl + (size_t)buf * SF * 64 + lane;
+    const int ks = b / RW, rt = (b % RW) * 2 + wm;
+    if (b % RW == 0) {
 #pragma unroll
-    for (int ks = 0; ks < kWideStage; ++ks)
-#pragma unroll
-      for (int ra = 0; ra < 4; ++ra) areg[0][ra][ks] = wbase[ra][(size_t)(k0 + ks) * 64];
-    const u32x4* src = b_src(k0);
-#pragma unroll
-    for (int i = 0; i < 2 * kWideRowTiles; ++i) breg[i] = src[i * 64];
-  }
+      for (int ra = 0; ra < 4; ++ra) wfb[kq & 3][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
+    }
+    bq[slot][0] = sb[(ks * KF + kWideWgTiles + rt * 2) * 64];
+    bq[slot][1] = sb[(ks * KF + kWideWgTiles + rt * 2 + 1) * 64];
+  };
+  // the stage (j, s) has landed for every wave and the stage before it is no longer read; ask for
+  // the stage after next
+  auto stage_ready = [&](int j, int s) {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER) : "memory");
+    __builtin_amdgcn_s_barrier();
+    const int s2 = (s + 2) % kWideSliceStages, j2 = j + (s + 2) / kWideSliceStages;
+    request(j2 < nsl ? kstep0(j2, s2) : kstep0(0, s2), rb == 0 ? kWideRing - 1 : rb - 1);
+  };
+
+  request(kstep0(0, 0), 0);
+  request(kstep0(0, 1), 1);
   if (WHOLE && a.ssq_in != nullptr) {
     wide_rstd_rows<16>(a, w, 4, lane, rstd_lds, w);
     wide_rstd_rows<16>(a, w + 64, 4, lane, rstd_lds, w + 64);
   }
-  store_b(0);
-  __syncthreads();
+  stage_ready(0, 0);
+#pragma unroll
+  for (int b = 0; b < kAhead; ++b) read_block(0, b, b / RW, b);
 
   for (int j = 0; j < nsl; ++j) {
 #pragma unroll
-    for (int s = 0; s < kStages; ++s) {
-      // While stage s is multiplied out of LDS buffer s & 1 and areg[s & 1], the next stage is
-      // requested, two loads per block so that the wave never sits in a long run of load issues:
-      // first its activations (written to LDS at the end of this stage), then its weights.  After
-      // the very last stage the workgroup's first stage is requested again (and never used).
-      const bool last = s == kStages - 1 && j + 1 == nsl;
-      const int k1 = last ? kstep0(0, 0) : (s == kStages - 1 ? kstep0(j + 1, 0) : kstep0(j, s + 1));
-      const u32x4* src = b_src(k1);
-      const u32x4* bp = bl + ((size_t)(s & 1) * kWideFrags + wm * 4 * 2) * 64 + lane;
-      u32x4 bq[kWideAhead + 1][2];
-      auto fetch = [&](int blk) {
-        const int ks = blk >> 2, r = blk & 3;
-        bq[blk % (kWideAhead + 1)][0] = bp[((ks * kWideRowTiles + r) * 2) * 64];
-        bq[blk % (kWideAhead + 1)][1] = bp[((ks * kWideRowTiles + r) * 2 + 1) * 64];
-      };
-#pragma unroll
-      for (int blk = 0; blk < kWideAhead; ++blk) fetch(blk);
-#pragma unroll
-      for (int blk = 0; blk < nblk; ++blk) {
-        const int ks = blk >> 2, r = blk & 3;
-        if (blk + kWideAhead < nblk) fetch(blk + kWideAhead);
-        if (blk < nblk / 2) {
-          breg[2 * blk] = src[(2 * blk) * 64];
-          breg[2 * blk + 1] = src[(2 * blk + 1) * 64];
-        } else {
-#pragma unroll
-          for (int q = (blk - nblk / 2) * 2; q < (blk - nblk / 2) * 2 + 2; ++q)
-            areg[(s + 1) & 1][q & 3][q >> 2] = wbase[q & 3][(size_t)(k1 + (q >> 2)) * 64];
+    for (int bn = 0; bn < BPSL; ++bn) {
+      {  // operands of the block kAhead ahead
+        const int pn = (bn + kAhead) % BPSL, jn = j + (bn + kAhead) / BPSL;
+        const int sn = pn / BPS, b = pn % BPS;
+        if (b == 0) {
+          rb = rb == kWideRing - 1 ? 0 : rb + 1;
+          stage_ready(jn, sn);
         }
-        // (keeps the requests where they are written: spread over the blocks, LDS reads kWideAhead
-        // blocks ahead of their use)
-        __builtin_amdgcn_sched_barrier(0);
-        const bf16x8 bh = as_bf16x8(bq[blk % (kWideAhead + 1)][0]), bo = as_bf16x8(bq[blk % (kWideAhead + 1)][1]);
-        const bool first = s == 0 && ks == 0;  // a slice starts from zero
-#pragma unroll
-        for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(areg[s & 1][ra][ks]), bh,
-                                                               first ? zero : acc[ra][r], 0, 0, 0);
-#pragma unroll
-        for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(areg[s & 1][ra][ks]), bo, acc[ra][r], 0, 0, 0);
+        read_block(rb, b, pn / RW, pn & kAhead);
       }
-      store_b((s + 1) & 1);
-      __syncthreads();
+      const int kq = bn / RW, r = bn % RW;
+      const bool first = kq == 0;  // a slice starts from zero
+      const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
+#pragma unroll
+      for (int ra = 0; ra < 4; ++ra)
+        acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
+#pragma unroll
+      for (int ra = 0; ra < 4; ++ra)
+        acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bo, acc[ra][r], 0, 0, 0);
     }
     // the slice is complete: fold it into the role's running sum, a complete role into the total
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
 #pragma unroll
     for (int ra = 0; ra < 4; ++ra)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < RW; ++r) {
         if constexpr (P1) {
           if constexpr (WHOLE) tot[ra][r] = tot[ra][r] + acc[ra][r];  // (zero + first role)
         } else {
@@ -185,13 +210,16 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
         }
       }
   }
+  // the requests past the end of the walk must have landed before the workgroup gives its LDS back
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (WHOLE && a.ssq_in != nullptr) __syncthreads();  // (rstd_lds of the other waves)
 
 #pragma unroll
   for (int ra = 0; ra < 4; ++ra) {
     const int t = cg * kWideWgTiles + wn * 4 + ra;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int rt = wm * 4 + r;
+    for (int r = 0; r < RW; ++r) {
+      const int rt = r * 2 + wm;
       if (t < a.ntiles && rt < x.row_tiles) {
         if constexpr (WHOLE) {
           const int row = rt * 16 + (lane & 15);
@@ -256,12 +284,12 @@ size_t gemm_wide_workspace_bytes(int N, int K) {
   return (size_t)W * ntiles * kWideRowTiles * 64 * sizeof(f32x4);
 }
 
-template <bool WHOLE, bool P1>
-static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
-                                      hipEvent_t e1, hipStream_t st) {
+template <bool WHOLE, bool P1, int RTL>
+static hipError_t launch_wide_rtl(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
+                                  hipEvent_t e1, hipStream_t st) {
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1, RTL>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -269,11 +297,19 @@ static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int 
   // whole mode: the kernel's own start and end are the GEMM's; split mode: start of the first
   // kernel, end of the second
   if (timed)
-    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1>), dim3(grid), dim3(256), (uint32_t)kWideLdsBytes, st, e0,
+    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, RTL>), dim3(grid), dim3(256), (uint32_t)kWideLdsBytes, st, e0,
                           WHOLE ? e1 : nullptr, 0, a, x);
   else
-    gemm_wide_kernel<WHOLE, P1><<<grid, 256, kWideLdsBytes, st>>>(a, x);
+    gemm_wide_kernel<WHOLE, P1, RTL><<<grid, 256, kWideLdsBytes, st>>>(a, x);
   return hipGetLastError();
+}
+
+template <bool WHOLE, bool P1>
+static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
+                                      hipEvent_t e1, hipStream_t st) {
+  if (x.row_tiles <= 4) return launch_wide_rtl<WHOLE, P1, 4>(a, x, grid, timed, e0, e1, st);
+  if (x.row_tiles <= 6) return launch_wide_rtl<WHOLE, P1, 6>(a, x, grid, timed, e0, e1, st);
+  return launch_wide_rtl<WHOLE, P1, 8>(a, x, grid, timed, e0, e1, st);
 }
 
 hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st) {
