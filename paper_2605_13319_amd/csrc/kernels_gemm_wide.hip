@@ -76,29 +76,29 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_lane, u32x4* dst_wa
                                    (void __attribute__((address_space(3)))*)dst_wave, 16, 0, 0);
 }
 
-// RTL: live row tiles of the pass rounded up to even (4, 6 or 8)
-template <bool WHOLE, bool P1, int RTL>
-__global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
+// Eight waves, two per SIMD (one wave alone issues a matrix-core instruction only every ~30 cycles):
+// wave (wm, wn) owns row tiles r*4 + wm (r = 0, 1) x n-tiles wn*4 .. +3 of the group.  Waves w and
+// w + 4 share a SIMD; with wm = w/2 the two of a SIMD hold row tiles {wm, wm + 4} and {wm + 2, wm + 6},
+// so a pass of 5 live row tiles costs every SIMD at most 3 of its 4 blocks.
+constexpr int kWideWaves = 8;
+template <bool WHOLE, bool P1>
+__global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
   extern __shared__ float lds_f[];
+  constexpr int RTL = kWideRowTiles;
   constexpr int KF = wide_kstep_frags(RTL);           // fragments per k-step
   constexpr int SF = kWideStage * KF;                 // fragments per stage buffer
-  constexpr int NPER = kWideStage * (2 + RTL / 2);    // fragments this wave requests per stage
-  constexpr int RW = RTL / 2;                         // row tiles per wave
+  constexpr int NPER = kWideStage * (1 + RTL / 4);    // fragments this wave requests per stage
+  constexpr int RW = RTL / 4;                         // row tiles per wave
   u32x4* bl = (u32x4*)lds_f;                          // [kWideRing][SF][64 lanes]
   float* rstd_lds = lds_f + (kWideLdsBytes - kWideRowTiles * 16 * sizeof(float)) / sizeof(float);  // [128]
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = w & 1, wn = w >> 1;  // this wave: row tiles r*2 + wm, n-tiles wn*4..+3 of the group
+  const int wm = w >> 1, wn = w & 1;
   const int nrole = WHOLE ? 1 : a.W;
   const int cg = (int)blockIdx.x / nrole, role = (int)blockIdx.x % nrole;
   const int nsl = (WHOLE ? a.W : 1) * a.P;  // slices this workgroup walks
 
-  // the two weight fragments per k-step this wave brings in: n-tiles w and w + 4 of the group
-  const u32x4* wsrc[2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int t = min(cg * kWideWgTiles + w + 4 * i, a.ntiles - 1);
-    wsrc[i] = a.wp + lane + (size_t)t * a.kst * 64;
-  }
+  // the weight fragment per k-step this wave brings in: n-tile w of the group
+  const u32x4* wsrc = a.wp + lane + (size_t)min(cg * kWideWgTiles + w, a.ntiles - 1) * a.kst * 64;
   // first k-step of stage s of the j-th slice this workgroup walks
   auto kstep0 = [&](int j, int s) {
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
@@ -109,13 +109,12 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
     u32x4* dst = bl + (size_t)buf * SF * 64;
 #pragma unroll
     for (int ks = 0; ks < kWideStage; ++ks) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) frag_to_lds(wsrc[i] + (size_t)(k0 + ks) * 64, dst + (ks * KF + w + 4 * i) * 64);
-      // activation fragments (row tile, half) = w + 4 i of the k-step (ActPack is in consumer lane order)
+      frag_to_lds(wsrc + (size_t)(k0 + ks) * 64, dst + (ks * KF + w) * 64);
+      // activation fragments (row tile, half) = w + 8 i of the k-step (ActPack is in consumer lane order)
       const u32x4* asrc = a.actp + (size_t)(k0 + ks) * (kWideRowTiles * 2 * 64) + lane;
 #pragma unroll
-      for (int i = 0; i < RTL / 2; ++i)
-        frag_to_lds(asrc + (w + 4 * i) * 64, dst + (ks * KF + kWideWgTiles + w + 4 * i) * 64);
+      for (int i = 0; i < RTL / 4; ++i)
+        frag_to_lds(asrc + (w + kWideWaves * i) * 64, dst + (ks * KF + kWideWgTiles + w + kWideWaves * i) * 64);
     }
   };
 
@@ -145,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
   // read the operands of block b of the stage in buffer `buf`; kq = its k-step within the slice
   auto read_block = [&](int buf, int b, int kq, int slot) {
     const u32x4* sb = bl + (size_t)buf * SF * 64 + lane;
-    const int ks = b / RW, rt = (b % RW) * 2 + wm;
+    const int ks = b / RW, rt = (b % RW) * 4 + wm;
     if (b % RW == 0) {
 #pragma unroll
       for (int ra = 0; ra < 4; ++ra) wfb[kq & 3][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
@@ -164,10 +163,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
 
   request(kstep0(0, 0), 0);
   request(kstep0(0, 1), 1);
-  if (WHOLE && a.ssq_in != nullptr) {
-    wide_rstd_rows<16>(a, w, 4, lane, rstd_lds, w);
-    wide_rstd_rows<16>(a, w + 64, 4, lane, rstd_lds, w + 64);
-  }
+  if (WHOLE && a.ssq_in != nullptr) wide_rstd_rows<16>(a, w, kWideWaves, lane, rstd_lds, w);
   stage_ready(0, 0);
 #pragma unroll
   for (int b = 0; b < kAhead; ++b) read_block(0, b, b / RW, b);
@@ -186,15 +182,23 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
       }
       const int kq = bn / RW, r = bn % RW;
       const bool first = kq == 0;  // a slice starts from zero
-      const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
+      if (r * 4 + wm < x.row_tiles) {  // (wave-uniform) a row tile past the pass is not multiplied
+        const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
 #pragma unroll
-      for (int ra = 0; ra < 4; ++ra)
-        acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
+        for (int ra = 0; ra < 4; ++ra)
+          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
 #pragma unroll
-      for (int ra = 0; ra < 4; ++ra)
-        acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bo, acc[ra][r], 0, 0, 0);
+        for (int ra = 0; ra < 4; ++ra)
+          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bo, acc[ra][r], 0, 0, 0);
+      }
     }
-    // the slice is complete: fold it into the role's running sum, a complete role into the total
+    // The slice is complete: fold it into the role's running sum, a complete role into the total.
+    // (The last products may have been issued in another basic block, where the compiler pads no
+    // wait states for the adds below: spell them out.)
+    static_assert(RW == 2, "the operand list below names every accumulator tile");
+    asm volatile("s_nop 15\n\ts_nop 7"
+                 : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]), "+v"(acc[2][1]),
+                   "+v"(acc[3][0]), "+v"(acc[3][1]));
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
 #pragma unroll
     for (int ra = 0; ra < 4; ++ra)
@@ -219,7 +223,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(GemmArgs a, WideArgs x) 
     const int t = cg * kWideWgTiles + wn * 4 + ra;
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-      const int rt = r * 2 + wm;
+      const int rt = r * 4 + wm;
       if (t < a.ntiles && rt < x.row_tiles) {
         if constexpr (WHOLE) {
           const int row = rt * 16 + (lane & 15);
@@ -284,32 +288,25 @@ size_t gemm_wide_workspace_bytes(int N, int K) {
   return (size_t)W * ntiles * kWideRowTiles * 64 * sizeof(f32x4);
 }
 
-template <bool WHOLE, bool P1, int RTL>
-static hipError_t launch_wide_rtl(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
-                                  hipEvent_t e1, hipStream_t st) {
+template <bool WHOLE, bool P1>
+static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
+                                      hipEvent_t e1, hipStream_t st) {
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1, RTL>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   // whole mode: the kernel's own start and end are the GEMM's; split mode: start of the first
   // kernel, end of the second
+  const dim3 block(kWideWaves * 64);
   if (timed)
-    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, RTL>), dim3(grid), dim3(256), (uint32_t)kWideLdsBytes, st, e0,
+    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
                           WHOLE ? e1 : nullptr, 0, a, x);
   else
-    gemm_wide_kernel<WHOLE, P1, RTL><<<grid, 256, kWideLdsBytes, st>>>(a, x);
+    gemm_wide_kernel<WHOLE, P1><<<grid, block, kWideLdsBytes, st>>>(a, x);
   return hipGetLastError();
-}
-
-template <bool WHOLE, bool P1>
-static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
-                                      hipEvent_t e1, hipStream_t st) {
-  if (x.row_tiles <= 4) return launch_wide_rtl<WHOLE, P1, 4>(a, x, grid, timed, e0, e1, st);
-  if (x.row_tiles <= 6) return launch_wide_rtl<WHOLE, P1, 6>(a, x, grid, timed, e0, e1, st);
-  return launch_wide_rtl<WHOLE, P1, 8>(a, x, grid, timed, e0, e1, st);
 }
 
 hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st) {
