@@ -146,7 +146,7 @@ int pipesd_nav_verify(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t p
  * token matching).  Per client the computation, the result and the state afterwards are those of
  * pipesd_nav_verify.  All arguments and the pool's free blocks are checked before anything
  * changes: an error leaves every client as it was.  On a bf16 model the clients' rows are packed,
- * in the order given, into passes of up to 128 rows and 16 clients, so that the weights are
+ * in the order given, into passes of up to 256 rows and 16 clients, so that the weights are
  * streamed once per pass and not once per client (a row's result does not depend on which rows
  * share its pass: the results are bit-identical to single calls); an fp32 model runs one pass per
  * client.  All work is enqueued on `stream`, which is synchronised once; accepted_len and

@@ -47,7 +47,7 @@ struct pipesd_model {
   unsigned* counters = nullptr;
   ActArena arena{};  // bf16 path: per-layer activation buffers (passes of up to 32 rows)
   int pass_act_tiles = 2;  // row tiles of the buffers of the pass being enqueued
-  ActArena arena_big{};  // bf16 path: one buffer of each kind, 8 row tiles (passes of several clients, up to 128 rows)
+  ActArena arena_big{};  // bf16 path: one buffer of each kind, 16 row tiles (passes of several clients, up to 256 rows; 33..128 rows use 8 of them)
   int wide_mode = 0;        // GEMM kernel of passes of more than 64 rows: 0 by shape, 1 narrow, 2 wide
   void* wide_ws = nullptr;  // bf16 path: running sums of the K-split workgroups of passes of more than 64 rows
   size_t wide_ws_bytes = 0;
@@ -633,6 +633,7 @@ static GemmCall gemm_call(pipesd_model* m, const void* wp, int N, int K, int row
 
 // The rows of one pass: one client's k + 1 rows, or (bf16) the rows of up to 16 clients one after
 // the other, at most 128 in all.
+constexpr int kPrefillRows = 128;  // rows per pass of prompt ingestion (bf16)
 struct PassClient {
   int32_t seq, rows, start_pos;
 };
@@ -641,7 +642,7 @@ struct PassLayout {
   PassClient client[kMaxPassClients];
   PassTokens tok{};
 };
-constexpr int kPassRowsCap = 128;  // rows the batched call puts into one pass (<= kMaxPassRows)
+constexpr int kPassRowsCap = 256;  // rows the batched call puts into one pass (<= kMaxPassRows)
 
 static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool want_logits, hipStream_t st) {
   const pipesd_config& c = m->cfg;
@@ -691,7 +692,7 @@ static int run_pass(pipesd_model* m, pipesd_kv* kv, const PassLayout& pl, bool w
   int rc = ensure_attn_scratch(m, std::max(part_floats * (part_per_layer ? c.n_layers : 1), stream_tiles ? stream_floats : 0));
   if (rc) return rc;
   ActArena& ar = rows <= 2 * 16 ? m->arena : m->arena_big;
-  const int act_tiles = rows <= 2 * 16 ? 2 : kMaxPassRows / 16;
+  const int act_tiles = rows <= 2 * 16 ? 2 : rows <= 8 * 16 ? 8 : kMaxPassRows / 16;
   m->pass_act_tiles = act_tiles;
   ar.part = m->attn_part;
   ar.part_stride = part_per_layer ? part_floats : 0;
@@ -879,7 +880,7 @@ extern "C" int pipesd_prefill(pipesd_model* model, pipesd_kv* kv, int32_t seq, c
   const int32_t cached_before = start;
   int rc = ensure_blocks(kv, seq, start + (int32_t)rows.size(), st);
   if (rc) return rc;
-  const size_t block = model->cfg.dtype == PIPESD_BF16 ? kMaxPassRows : kMaxRows;  // rows per pass
+  const size_t block = model->cfg.dtype == PIPESD_BF16 ? kPrefillRows : kMaxRows;  // rows per pass
   for (size_t i = 0; i < rows.size(); i += block) {
     const int nr = (int)((rows.size() - i < block) ? rows.size() - i : block);
     rc = run_rows(model, kv, seq, rows.data() + i, nr, start + (int)i, false, st);
@@ -1182,7 +1183,7 @@ extern "C" int pipesd_nav_verify_batch(pipesd_model* model, pipesd_kv* kv, int32
     }
   };
   for (int32_t i = 0; i < 2 * n_seqs; ++i) model->result_host[4 + i] = -1;
-  // bf16: clients are packed, in the order given, into passes of up to 128 rows and 16 clients, so
+  // bf16: clients are packed, in the order given, into passes of up to 256 rows and 16 clients, so
   // that the weights are streamed once per pass instead of once per client (a row's results do not
   // depend on which other rows share its pass); fp32: one pass per client
   const bool pack = model->cfg.dtype == PIPESD_BF16;

@@ -9,7 +9,7 @@
 namespace pipesd {
 
 constexpr int kMaxRows = PIPESD_MAX_ROWS;  // rows of one client per pass (k + 1)
-constexpr int kMaxPassRows = 128;          // rows of all clients that share a pass (bf16)
+constexpr int kMaxPassRows = 256;          // rows of all clients that share a pass (bf16)
 constexpr int kBlockTokens = 16;           // tokens per KV block
 constexpr int kWave = 64;
 

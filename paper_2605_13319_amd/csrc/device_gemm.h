@@ -60,7 +60,7 @@ struct GemmArgs {
   const RowMap* rows;     // QKV: per-row position and block table (several clients in the pass), or nullptr
   KvView kv;
   int m, K, N, ntiles, kst, W, P, tg, ldo, epi, layer, start_pos, n_q_heads;
-  int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1..8)
+  int row_tiles;          // workgroups that share a team's tiles, one per 16 rows of the pass (1..16)
   int act_tiles;          // row tiles of the pass's ActPack buffers
   float eps;
   const int32_t* gate;    // optional: the launch does nothing if this device word holds 0
@@ -71,6 +71,7 @@ struct GemmArgs {
 constexpr int kWideMinRowTiles = 5;
 hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st);
 bool gemm_wide_preferred(int N, int K);
+bool gemm_wide_supported(int N, int K, int act_tiles);  // the wide kernel can run this product on ActPack buffers of that many row tiles
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 

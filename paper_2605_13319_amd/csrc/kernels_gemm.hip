@@ -111,7 +111,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.act_tiles = c.act_tiles;
   a.gate = c.gate;
   if (c.gate != nullptr && row_tiles >= kWideMinRowTiles) return hipErrorInvalidValue;  // the wide kernel has no gate
-  if (row_tiles >= kWideMinRowTiles && c.act_tiles == 8 &&
+  if (row_tiles >= kWideMinRowTiles && gemm_wide_supported(c.N, c.K, c.act_tiles) &&
       (c.wide_mode == 2 || (c.wide_mode == 0 && gemm_wide_preferred(c.N, c.K))))
     return launch_gemm_wide(c, a, st);
   const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);

@@ -1,18 +1,21 @@
-// GEMM for passes of 65..128 rows (batched verification of many clients, prompt ingestion).
+// GEMM for passes of 65..256 rows (batched verification of many clients, prompt ingestion).
 //
 // At this many rows the activations of a K slice no longer fit a wave's registers, and spreading the
-// rows over workgroups that re-read the weights from the L2 (the narrow kernel's way) moves eight
-// times the weights through it.  Here a workgroup of four waves multiplies ALL rows of the pass with
-// 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they get there
-// without passing through registers: every wave asks for its share of a stage's fragments (two
-// k-steps: 8 weight fragments and the live row tiles' activation fragments, hi and lo, per k-step)
-// with loads that write straight into LDS, into a ring of three stage buffers, two stages ahead of
-// the multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
-// consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this
-// wave's loads of the stage have landed (they return in order: all but the next stage's may be
-// outstanding), one workgroup barrier, request the stage after next into the buffer the barrier
-// has just freed, multiply.  Each wave owns a 64-column x (live row tiles / 2)-tile block of the
-// product (row tiles r*2 + wm), so every weight fragment read from LDS feeds up to eight MFMAs.
+// rows over workgroups that re-read the weights from the L2 (the narrow kernel's way) moves many
+// times the weights through it.  Here a workgroup of eight waves, two per SIMD, multiplies ALL rows
+// of the pass with 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they
+// get there without passing through registers: every wave asks for its share of a stage's fragments
+// (per k-step the 8 weight fragments and the row tiles' activation fragments, hi and lo) with loads
+// that write straight into LDS, into a ring of three stage buffers, two stages ahead of the
+// multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
+// consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this wave's
+// loads of the stage have landed (they return in order: all but the next stage's may be outstanding)
+// and its own LDS reads have returned, one workgroup barrier, request the stage after next into the
+// buffer the barrier has just freed.  The multiplies run as a stream of blocks (k-step, row tile)
+// whose operands are read from LDS three blocks ahead, across stage boundaries.  Wave (wm, wn) owns
+// row tiles wm, wm + 4, .. x n-tiles wn*4 .. +3; row tiles past the pass are neither read nor
+// multiplied.  Up to 128 rows the packed activations have 8 row tiles and a stage is two k-steps;
+// up to 256 rows they have 16 and a stage is one.
 //
 // Results are bit-identical to the narrow kernel's, row by row: K is cut into the same W * P slices
 // of 512 columns, every slice is accumulated from zero in the same k-step order (hi half, then lo
@@ -28,20 +31,21 @@
 
 namespace pipesd {
 
-constexpr int kWideStage = 2;       // k-steps per ring stage
+// Two shapes: ROWT = 8 row tiles (passes of 65..128 rows; the packed activations have 8 row tiles)
+// with stages of two k-steps, and ROWT = 16 (129..256 rows; 16 row tiles) with stages of one.
 constexpr int kWideRing = 3;        // stage buffers
-constexpr int kWideRowTiles = 8;    // row tiles of the packed activations of a wide pass (ActPack row tiles)
 constexpr int kWideWgTiles = 8;     // n-tiles per workgroup: 2 wave columns x 4
-constexpr int kWideSliceStages = 16 / kWideStage;  // stages per 512-column slice
+constexpr int wide_stage_ksteps(int rowt) { return rowt == 16 ? 1 : 2; }
 // 1 KB fragments of one k-step in a stage buffer: the 8 weight fragments, then (row tile, half)
-constexpr int wide_kstep_frags(int rtl) { return kWideWgTiles + 2 * rtl; }
-constexpr size_t kWideLdsBytes =
-    (size_t)kWideRing * kWideStage * wide_kstep_frags(kWideRowTiles) * 1024 + kWideRowTiles * 16 * sizeof(float);
+constexpr int wide_kstep_frags(int rowt) { return kWideWgTiles + 2 * rowt; }
+constexpr size_t wide_ring_bytes(int rowt) { return (size_t)kWideRing * wide_stage_ksteps(rowt) * wide_kstep_frags(rowt) * 1024; }
+constexpr size_t kWideLdsBytes = (wide_ring_bytes(8) > wide_ring_bytes(16) ? wide_ring_bytes(8) : wide_ring_bytes(16)) + 256 * sizeof(float);
 
 struct WideArgs {
-  f32x4* partials;  // split: [W][ntiles][8][64] running sums of role w
+  f32x4* partials;  // split: [W][ntiles][ROWT][64] running sums of role w
   int ncg;          // column groups of kWideWgTiles n-tiles
   int row_tiles;    // live row tiles of the pass
+  int rowt;         // 8 or 16: row tiles of the packed activations (and of the partials)
 };
 
 // rstd of the rows row0 + i*row_step, i < NR (one wave; all partial sums are requested before any is
@@ -81,16 +85,18 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_lane, u32x4* dst_wa
 // w + 4 share a SIMD; with wm = w/2 the two of a SIMD hold row tiles {wm, wm + 4} and {wm + 2, wm + 6},
 // so a pass of 5 live row tiles costs every SIMD at most 3 of its 4 blocks.
 constexpr int kWideWaves = 8;
-template <bool WHOLE, bool P1>
+template <bool WHOLE, bool P1, int ROWT>
 __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
   extern __shared__ float lds_f[];
-  constexpr int RTL = kWideRowTiles;
+  constexpr int RTL = ROWT;
+  constexpr int kWideStage = wide_stage_ksteps(ROWT); // k-steps per ring stage
+  constexpr int kWideSliceStages = 16 / kWideStage;   // stages per 512-column slice
   constexpr int KF = wide_kstep_frags(RTL);           // fragments per k-step
   constexpr int SF = kWideStage * KF;                 // fragments per stage buffer
   constexpr int NPER = kWideStage * (1 + RTL / 4);    // fragments this wave requests per stage
   constexpr int RW = RTL / 4;                         // row tiles per wave
   u32x4* bl = (u32x4*)lds_f;                          // [kWideRing][SF][64 lanes]
-  float* rstd_lds = lds_f + (kWideLdsBytes - kWideRowTiles * 16 * sizeof(float)) / sizeof(float);  // [128]
+  float* rstd_lds = lds_f + (kWideLdsBytes - 256 * sizeof(float)) / sizeof(float);  // [ROWT * 16]
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = w >> 1, wn = w & 1;
   const int nrole = WHOLE ? 1 : a.W;
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
     for (int ks = 0; ks < kWideStage; ++ks) {
       frag_to_lds(wsrc + (size_t)(k0 + ks) * 64, dst + (ks * KF + w) * 64);
       // activation fragments (row tile, half) = w + 8 i of the k-step (ActPack is in consumer lane order)
-      const u32x4* asrc = a.actp + (size_t)(k0 + ks) * (kWideRowTiles * 2 * 64) + lane;
+      const u32x4* asrc = a.actp + (size_t)(k0 + ks) * (ROWT * 2 * 64) + lane;
 #pragma unroll
       for (int i = 0; i < RTL / 4; ++i)
         frag_to_lds(asrc + (w + kWideWaves * i) * 64, dst + (ks * KF + kWideWgTiles + w + kWideWaves * i) * 64);
@@ -139,7 +145,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
   constexpr int BPS = kWideStage * RW;           // blocks per stage (>= 4 > kAhead)
   constexpr int BPSL = kWideSliceStages * BPS;   // blocks per slice (a multiple of 4)
   u32x4 bq[kAhead + 1][2];                       // ring of activation operand pairs
-  u32x4 wfb[4][4];                               // weight fragments of the last 4 k-steps
+  constexpr int WR = RW >= kAhead ? 2 : 4;       // k-steps whose weight fragments are held (reads run at most that far ahead)
+  u32x4 wfb[WR][4];                              // weight fragments of the last WR k-steps
   int rb = 0;                                    // ring buffer of the stage being read
   // read the operands of block b of the stage in buffer `buf`; kq = its k-step within the slice
   auto read_block = [&](int buf, int b, int kq, int slot) {
@@ -147,10 +154,12 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
     const int ks = b / RW, rt = (b % RW) * 4 + wm;
     if (b % RW == 0) {
 #pragma unroll
-      for (int ra = 0; ra < 4; ++ra) wfb[kq & 3][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
+      for (int ra = 0; ra < 4; ++ra) wfb[kq & (WR - 1)][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
     }
-    bq[slot][0] = sb[(ks * KF + kWideWgTiles + rt * 2) * 64];
-    bq[slot][1] = sb[(ks * KF + kWideWgTiles + rt * 2 + 1) * 64];
+    if (rt < x.row_tiles) {  // (wave-uniform) a row tile past the pass is neither read nor multiplied
+      bq[slot][0] = sb[(ks * KF + kWideWgTiles + rt * 2) * 64];
+      bq[slot][1] = sb[(ks * KF + kWideWgTiles + rt * 2 + 1) * 64];
+    }
   };
   // the stage (j, s) has landed for every wave and the stage before it is no longer read; ask for
   // the stage after next
@@ -163,7 +172,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
 
   request(kstep0(0, 0), 0);
   request(kstep0(0, 1), 1);
-  if (WHOLE && a.ssq_in != nullptr) wide_rstd_rows<16>(a, w, kWideWaves, lane, rstd_lds, w);
+  if (WHOLE && a.ssq_in != nullptr) {
+#pragma unroll
+    for (int h = 0; h < ROWT / 8; ++h) wide_rstd_rows<16>(a, w + 128 * h, kWideWaves, lane, rstd_lds, w + 128 * h);
+  }
   stage_ready(0, 0);
 #pragma unroll
   for (int b = 0; b < kAhead; ++b) read_block(0, b, b / RW, b);
@@ -186,19 +198,18 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
         const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
 #pragma unroll
         for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
+          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
 #pragma unroll
         for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & 3][ra]), bo, acc[ra][r], 0, 0, 0);
+          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bo, acc[ra][r], 0, 0, 0);
       }
     }
     // The slice is complete: fold it into the role's running sum, a complete role into the total.
     // (The last products may have been issued in another basic block, where the compiler pads no
     // wait states for the adds below: spell them out.)
-    static_assert(RW == 2, "the operand list below names every accumulator tile");
-    asm volatile("s_nop 15\n\ts_nop 7"
-                 : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]), "+v"(acc[2][1]),
-                   "+v"(acc[3][0]), "+v"(acc[3][1]));
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0][r]), "+v"(acc[1][r]), "+v"(acc[2][r]), "+v"(acc[3][r]));
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
 #pragma unroll
     for (int ra = 0; ra < 4; ++ra)
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
           const float rstd = (a.ssq_in != nullptr && row < a.m) ? rstd_lds[row] : 1.0f;
           epilogue_quad<false>(a, t, row, lane, tot[ra][r], rstd, false, zero, zero);
         } else {
-          x.partials[(((size_t)role * a.ntiles + t) * kWideRowTiles + rt) * 64 + lane] = P1 ? acc[ra][r] : run[ra][r];
+          x.partials[(((size_t)role * a.ntiles + t) * ROWT + rt) * 64 + lane] = P1 ? acc[ra][r] : run[ra][r];
         }
       }
     }
@@ -250,7 +261,7 @@ __global__ __launch_bounds__(256) void gemm_wide_finish_kernel(GemmArgs a, WideA
   f32x4 pv[kWideMaxRoles];
 #pragma unroll
   for (int ww = 0; ww < kWideMaxRoles; ++ww)
-    if (ww < a.W && t < a.ntiles) pv[ww] = x.partials[(((size_t)ww * a.ntiles + t) * kWideRowTiles + rt) * 64 + lane];
+    if (ww < a.W && t < a.ntiles) pv[ww] = x.partials[(((size_t)ww * a.ntiles + t) * x.rowt + rt) * 64 + lane];
   if (norm) wide_rstd_rows<4>(a, rt * 16 + w * 4, 1, lane, rstd_lds, w * 4);
   __syncthreads();
   if (t >= a.ntiles) return;
@@ -285,15 +296,15 @@ size_t gemm_wide_workspace_bytes(int N, int K) {
   int W = 1;
   for (int cand = 8; cand >= 1; --cand)
     if ((K / 512) % cand == 0) { W = cand; break; }
-  return (size_t)W * ntiles * kWideRowTiles * 64 * sizeof(f32x4);
+  return (size_t)W * ntiles * 16 * 64 * sizeof(f32x4);  // (sized for the 16-row-tile shape)
 }
 
-template <bool WHOLE, bool P1>
-static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
-                                      hipEvent_t e1, hipStream_t st) {
+template <bool WHOLE, bool P1, int ROWT>
+static hipError_t launch_wide_rowt(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
+                                   hipEvent_t e1, hipStream_t st) {
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1, ROWT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -302,19 +313,46 @@ static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int 
   // kernel, end of the second
   const dim3 block(kWideWaves * 64);
   if (timed)
-    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
+    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, ROWT>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
                           WHOLE ? e1 : nullptr, 0, a, x);
   else
-    gemm_wide_kernel<WHOLE, P1><<<grid, block, kWideLdsBytes, st>>>(a, x);
+    gemm_wide_kernel<WHOLE, P1, ROWT><<<grid, block, kWideLdsBytes, st>>>(a, x);
   return hipGetLastError();
+}
+
+template <bool WHOLE, bool P1>
+static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
+                                      hipEvent_t e1, hipStream_t st) {
+  if (x.rowt == 16) {
+    // (a whole-K walk with phases needs three accumulator sets of 64 registers: not built for 16 row tiles)
+    if constexpr (WHOLE && !P1) return hipErrorInvalidValue;
+    else return launch_wide_rowt<WHOLE, P1, 16>(a, x, grid, timed, e0, e1, st);
+  }
+  return launch_wide_rowt<WHOLE, P1, 8>(a, x, grid, timed, e0, e1, st);
+}
+
+// whether the wide kernel can run this product on `act_tiles` row tiles
+bool gemm_wide_supported(int N, int K, int act_tiles) {
+  if (act_tiles == 8) return true;
+  if (act_tiles != 16) return false;
+  const int n_cu = device_cu_count();
+  const int ntiles = (N + 15) / 16;
+  if (n_cu <= 0 || K % 512 != 0) return false;
+  // the narrow kernel's split of K: W waves x P phases; whole-K walks need P == 1 here
+  int W = 1;
+  for (int cand = 8; cand >= 1; --cand)
+    if ((K / 512) % cand == 0) { W = cand; break; }
+  const int P = K / 512 / W;
+  return !(wide_whole(ntiles, n_cu) && P != 1);
 }
 
 hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st) {
   const int n_cu = device_cu_count();
-  if (c.act_tiles != kWideRowTiles || a.K % 512 != 0 || a.W > kWideMaxRoles) return hipErrorInvalidValue;
+  if ((c.act_tiles != 8 && c.act_tiles != 16) || a.K % 512 != 0 || a.W > kWideMaxRoles) return hipErrorInvalidValue;
   WideArgs x{};
   x.ncg = (a.ntiles + kWideWgTiles - 1) / kWideWgTiles;
   x.row_tiles = (c.m + 15) / 16;
+  x.rowt = c.act_tiles;
   const bool whole = wide_whole(a.ntiles, n_cu);
   const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;
   hipError_t e;
@@ -323,7 +361,7 @@ hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st) {
                  : launch_wide_variant<true, false>(a, x, x.ncg, timed, c.ev_start, c.ev_stop, st);
     return e;
   }
-  const size_t need = (size_t)a.W * a.ntiles * kWideRowTiles * 64 * sizeof(f32x4);
+  const size_t need = (size_t)a.W * a.ntiles * x.rowt * 64 * sizeof(f32x4);
   if (c.wide_ws == nullptr || c.wide_ws_bytes < need) return hipErrorInvalidValue;
   x.partials = (f32x4*)c.wide_ws;
   e = a.P == 1 ? launch_wide_variant<false, true>(a, x, x.ncg * a.W, timed, c.ev_start, c.ev_stop, st)
