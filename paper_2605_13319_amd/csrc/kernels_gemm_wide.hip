@@ -84,27 +84,29 @@ __device__ __forceinline__ void frag_to_lds(const u32x4* src_lane, u32x4* dst_wa
 // wave (wm, wn) owns row tiles r*4 + wm (r = 0, 1) x n-tiles wn*4 .. +3 of the group.  Waves w and
 // w + 4 share a SIMD; with wm = w/2 the two of a SIMD hold row tiles {wm, wm + 4} and {wm + 2, wm + 6},
 // so a pass of 5 live row tiles costs every SIMD at most 3 of its 4 blocks.
-constexpr int kWideWaves = 8;
+constexpr int wide_waves(int rowt) { return rowt == 8 ? 16 : 8; }
 template <bool WHOLE, bool P1, int ROWT>
-__global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
+__global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
   extern __shared__ float lds_f[];
+  constexpr int kWideWaves = wide_waves(ROWT), WMS = kWideWaves / 2;  // waves, wave rows
   constexpr int RTL = ROWT;
   constexpr int kWideStage = wide_stage_ksteps(ROWT); // k-steps per ring stage
   constexpr int kWideSliceStages = 16 / kWideStage;   // stages per 512-column slice
   constexpr int KF = wide_kstep_frags(RTL);           // fragments per k-step
   constexpr int SF = kWideStage * KF;                 // fragments per stage buffer
-  constexpr int NPER = kWideStage * (1 + RTL / 4);    // fragments this wave requests per stage
-  constexpr int RW = RTL / 4;                         // row tiles per wave
+  constexpr int NPER = kWideStage * (kWideWgTiles + 2 * RTL) / kWideWaves;  // fragments this wave requests per stage
+  constexpr int RW = RTL / WMS;                       // row tiles per wave
   u32x4* bl = (u32x4*)lds_f;                          // [kWideRing][SF][64 lanes]
   float* rstd_lds = lds_f + (kWideLdsBytes - 256 * sizeof(float)) / sizeof(float);  // [ROWT * 16]
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = w >> 1, wn = w & 1;
+  const int wm = w >> 1, wn = w & 1;  // row tiles r * WMS + wm, n-tiles wn*4 .. +3
   const int nrole = WHOLE ? 1 : a.W;
   const int cg = (int)blockIdx.x / nrole, role = (int)blockIdx.x % nrole;
   const int nsl = (WHOLE ? a.W : 1) * a.P;  // slices this workgroup walks
 
-  // the weight fragment per k-step this wave brings in: n-tile w of the group
-  const u32x4* wsrc = a.wp + lane + (size_t)min(cg * kWideWgTiles + w, a.ntiles - 1) * a.kst * 64;
+  // A stage's fragments, numbered f = ks * KF + (0..7 weights | 8.. activations (row tile, half)), are
+  // dealt to the waves round robin: wave w requests f = w, w + kWideWaves, ..
+  const u32x4* wbase = a.wp + lane;
   // first k-step of stage s of the j-th slice this workgroup walks
   auto kstep0 = [&](int j, int s) {
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
@@ -114,13 +116,14 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
   auto request = [&](int k0, int buf) {
     u32x4* dst = bl + (size_t)buf * SF * 64;
 #pragma unroll
-    for (int ks = 0; ks < kWideStage; ++ks) {
-      frag_to_lds(wsrc + (size_t)(k0 + ks) * 64, dst + (ks * KF + w) * 64);
-      // activation fragments (row tile, half) = w + 8 i of the k-step (ActPack is in consumer lane order)
-      const u32x4* asrc = a.actp + (size_t)(k0 + ks) * (ROWT * 2 * 64) + lane;
-#pragma unroll
-      for (int i = 0; i < RTL / 4; ++i)
-        frag_to_lds(asrc + (w + kWideWaves * i) * 64, dst + (ks * KF + kWideWgTiles + w + kWideWaves * i) * 64);
+    for (int i = 0; i < NPER; ++i) {
+      const int f = w + kWideWaves * i, ks = f / KF, e = f % KF;  // (KF and kWideWaves are compile-time; w is uniform)
+      const u32x4* src;
+      if (e < kWideWgTiles)
+        src = wbase + ((size_t)min(cg * kWideWgTiles + e, a.ntiles - 1) * a.kst + (k0 + ks)) * 64;
+      else  // ActPack is in consumer lane order
+        src = a.actp + ((size_t)(k0 + ks) * (ROWT * 2) + (e - kWideWgTiles)) * 64 + lane;
+      frag_to_lds(src, dst + f * 64);
     }
   };
 
@@ -141,8 +144,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
   // reads, so behind the barrier nobody reads the stage before any more, and its buffer takes the
   // stage after next.  Past the end of the walk the workgroup's first stages are requested and read
   // again (and never used), so the counts hold to the end.
-  constexpr int kAhead = 3;
-  constexpr int BPS = kWideStage * RW;           // blocks per stage (>= 4 > kAhead)
+  constexpr int BPS = kWideStage * RW;           // blocks per stage
+  constexpr int kAhead = BPS >= 4 ? 3 : 1;       // (a power of two minus one, below BPS)
   constexpr int BPSL = kWideSliceStages * BPS;   // blocks per slice (a multiple of 4)
   u32x4 bq[kAhead + 1][2];                       // ring of activation operand pairs
   constexpr int WR = RW >= kAhead ? 2 : 4;       // k-steps whose weight fragments are held (reads run at most that far ahead)
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
   // read the operands of block b of the stage in buffer `buf`; kq = its k-step within the slice
   auto read_block = [&](int buf, int b, int kq, int slot) {
     const u32x4* sb = bl + (size_t)buf * SF * 64 + lane;
-    const int ks = b / RW, rt = (b % RW) * 4 + wm;
+    const int ks = b / RW, rt = (b % RW) * WMS + wm;
     if (b % RW == 0) {
 #pragma unroll
       for (int ra = 0; ra < 4; ++ra) wfb[kq & (WR - 1)][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
@@ -173,8 +176,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
   request(kstep0(0, 0), 0);
   request(kstep0(0, 1), 1);
   if (WHOLE && a.ssq_in != nullptr) {
+    constexpr int RPW = ROWT * 16 / kWideWaves;  // rows whose rstd this wave computes: w, w + kWideWaves, ..
 #pragma unroll
-    for (int h = 0; h < ROWT / 8; ++h) wide_rstd_rows<16>(a, w + 128 * h, kWideWaves, lane, rstd_lds, w + 128 * h);
+    for (int h = 0; h < (RPW + 15) / 16; ++h)
+      wide_rstd_rows<(RPW < 16 ? RPW : 16)>(a, w + 16 * kWideWaves * h, kWideWaves, lane, rstd_lds, w + 16 * kWideWaves * h);
   }
   stage_ready(0, 0);
 #pragma unroll
@@ -192,9 +197,12 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
         }
         read_block(rb, b, pn / RW, pn & kAhead);
       }
+      // (keeps the reads where they are written, kAhead blocks ahead of their use: left alone, the
+      // scheduler sinks them to just in front of their multiplies and every block waits for LDS)
+      __builtin_amdgcn_sched_barrier(0);
       const int kq = bn / RW, r = bn % RW;
       const bool first = kq == 0;  // a slice starts from zero
-      if (r * 4 + wm < x.row_tiles) {  // (wave-uniform) a row tile past the pass is not multiplied
+      if (r * WMS + wm < x.row_tiles) {  // (wave-uniform) a row tile past the pass is not multiplied
         const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
 #pragma unroll
         for (int ra = 0; ra < 4; ++ra)
@@ -207,9 +215,9 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
     // The slice is complete: fold it into the role's running sum, a complete role into the total.
     // (The last products may have been issued in another basic block, where the compiler pads no
     // wait states for the adds below: spell them out.)
-#pragma unroll
-    for (int r = 0; r < RW; ++r)
-      asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0][r]), "+v"(acc[1][r]), "+v"(acc[2][r]), "+v"(acc[3][r]));
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
 #pragma unroll
     for (int ra = 0; ra < 4; ++ra)
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void gemm_wide_kernel(GemmArgs a, 
     const int t = cg * kWideWgTiles + wn * 4 + ra;
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-      const int rt = r * 4 + wm;
+      const int rt = r * WMS + wm;
       if (t < a.ntiles && rt < x.row_tiles) {
         if constexpr (WHOLE) {
           const int row = rt * 16 + (lane & 15);
@@ -311,7 +319,7 @@ static hipError_t launch_wide_rowt(const GemmArgs& a, const WideArgs& x, int gri
   }
   // whole mode: the kernel's own start and end are the GEMM's; split mode: start of the first
   // kernel, end of the second
-  const dim3 block(kWideWaves * 64);
+  const dim3 block(wide_waves(ROWT) * 64);
   if (timed)
     hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, ROWT>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
                           WHOLE ? e1 : nullptr, 0, a, x);
