@@ -250,7 +250,8 @@ struct AttnCall {
 };
 int attn_nsplit(int total_tokens, int chunk);
 int attn_chunk_tokens(int dtype);  // tokens per workgroup of the attention kernel for this cache type
-// Passes of at most kMaxRows rows per client (bf16 cache) take the streaming kernel.  Fills span,
+// Passes of at most kMaxRows rows per client, and prompt blocks of up to 128 rows alone in their
+// pass (bf16 cache), take the streaming kernel.  Fills span,
 // nsplit, part_off and count_off of every client of `b` (row_off, m, start_pos, table_off given) and
 // returns the query tiles per workgroup, or 0 if the pass does not fit (then the split kernels run);
 // *part_floats = size of the partial buffer the launch needs.  A client's split depends on its own

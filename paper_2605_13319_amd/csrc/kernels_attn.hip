@@ -132,6 +132,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 // after every writer has drained its write-through stores and then incremented the counter.
 constexpr int kStreamMinSpan = kAttnWgTokens;  // a client's context is cut into at most kStreamMaxSplits
 constexpr int kStreamMaxSplits = 16;           // splits of 256 * 2^j tokens, j as small as that allows
+constexpr int kStreamMaxRows = 128;            // rows of a client (a prompt block brings up to 128; a NAV pass at most kMaxRows)
 
 template <int HD>
 constexpr size_t stream_lds_bytes(int T) {
@@ -481,7 +482,7 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     }
     if (c.stream_tiles) {  // few rows per client: the streaming kernel (the batch was planned by attn_stream_plan)
       const int T = c.stream_tiles;
-      if ((h != 128 && h != 64) || max_m > kMaxRows || (T != 1 && T != 2) || c.counters == nullptr) return hipErrorInvalidValue;
+      if ((h != 128 && h != 64) || max_m > kStreamMaxRows || (T != 1 && T != 2) || c.counters == nullptr) return hipErrorInvalidValue;
       const int nz = ((group * max_m + 15) / 16 + T - 1) / T;
       static bool stream_lds_allowed = false;
       if (!stream_lds_allowed) {
@@ -558,11 +559,20 @@ int attn_stream_plan(int n_q_heads, int n_kv_heads, int head_dim, AttnBatch& b, 
   long tasks = 0;  // (kv head, split, query tile) over all clients
   for (int i = 0; i < b.n; ++i) {
     AttnClient& cl = b.c[i];
-    if (cl.m > kMaxRows) return 0;
+    if (cl.m > kStreamMaxRows || (cl.m > kMaxRows && b.n != 1)) return 0;
     max_m = std::max(max_m, (int)cl.m);
     const int total = cl.start_pos + cl.m;
     cl.span = kStreamMinSpan;
-    while ((total + cl.span - 1) / cl.span > kStreamMaxSplits) cl.span *= 2;
+    if (cl.m <= kMaxRows) {
+      while ((total + cl.span - 1) / cl.span > kStreamMaxSplits) cl.span *= 2;
+    } else {
+      // a prompt block (alone in its pass): the query tiles alone give many workgroups, so the context
+      // is cut only as far as it takes to have about two workgroups per compute unit
+      const long groups = (long)n_kv_heads * (((group * cl.m + 15) / 16 + 1) / 2);
+      const long want = std::max(1L, std::min((long)kStreamMaxSplits, 2L * device_cu_count() / groups));
+      const int steps = (total + kStreamMinSpan - 1) / kStreamMinSpan;
+      cl.span = (int)((steps + want - 1) / want) * kStreamMinSpan;
+    }
     cl.nsplit = (total + cl.span - 1) / cl.span;
     tasks += (long)n_kv_heads * cl.nsplit * ((group * cl.m + 15) / 16);
   }
