@@ -33,12 +33,15 @@ LLAMA_8B_L2 = I.WORKLOADS["llama-8b"]["shape"].truncated(2)
 
 @pytest.mark.parametrize("shape_name,n_seq,rounds,max_prefix", [("tiny", 5, 4, 150), ("small-bf16", 5, 4, 150),
                                                                  ("small-bf16", 16, 12, 150), ("ragged-bf16", 16, 3, 150),
-                                                                 ("llama-8b-L2", 16, 10, 4096)])
+                                                                 ("llama-8b-L2", 16, 10, 4096),
+                                                                 ("llama-13b-L2", 16, 3, 600)])
 def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, rounds, max_prefix):
-    """bf16: the clients' rows share passes of up to 128 rows (16 clients with k ~ U[1,16] need two);
-    a row's results must not depend on what else is in its pass."""
+    """bf16: the clients' rows share passes of up to 256 rows (16 clients with k ~ U[1,16] bring about
+    150: beyond 128 rows the packed activations have 16 row tiles and the wide GEMM its second shape;
+    at the 13B widths, K = 5120 = 5 x 2 slices, the whole-K products fall back to the narrow kernel
+    on up to 16 row tiles); a row's results must not depend on what else is in its pass."""
     shape = {"tiny": I.WORKLOADS["tiny"]["shape"], "small-bf16": SMALL_BF16, "ragged-bf16": RAGGED_BF16,
-             "llama-8b-L2": LLAMA_8B_L2}[shape_name]
+             "llama-8b-L2": LLAMA_8B_L2, "llama-13b-L2": I.WORKLOADS["llama-13b"]["shape"].truncated(2)}[shape_name]
     w = I.make_weights(shape, 9001)
     model = nav.Model(shape, w)
     rng = np.random.default_rng(9002)
