@@ -70,7 +70,7 @@ struct GemmArgs {
 // filled in by launch_gemm_bf16
 constexpr int kWideMinRowTiles = 5;
 hipError_t launch_gemm_wide(const GemmCall& c, GemmArgs a, hipStream_t st);
-bool gemm_wide_preferred(int N, int K);
+bool gemm_wide_preferred(int N, int K, int row_tiles);
 bool gemm_wide_supported(int N, int K, int act_tiles);  // the wide kernel can run this product on ActPack buffers of that many row tiles
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }

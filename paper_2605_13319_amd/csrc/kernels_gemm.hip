@@ -112,7 +112,7 @@ hipError_t launch_gemm_bf16(const GemmCall& c, hipStream_t st) {
   a.gate = c.gate;
   if (c.gate != nullptr && row_tiles >= kWideMinRowTiles) return hipErrorInvalidValue;  // the wide kernel has no gate
   if (row_tiles >= kWideMinRowTiles && gemm_wide_supported(c.N, c.K, c.act_tiles) &&
-      (c.wide_mode == 2 || (c.wide_mode == 0 && gemm_wide_preferred(c.N, c.K))))
+      (c.wide_mode == 2 || (c.wide_mode == 0 && gemm_wide_preferred(c.N, c.K, row_tiles))))
     return launch_gemm_wide(c, a, st);
   const size_t lds = gemm_lds_floats(p.tg, p.W, 1, 1) * sizeof(float);
   const bool timed = c.ev_start != nullptr && c.ev_stop != nullptr;

@@ -291,10 +291,12 @@ static bool wide_whole(int ntiles, int n_cu) {
 // Measured on the 8B shapes at 116 rows: products whose columns fill the device (gate/up, LM head)
 // and K-split ones with at least ~100 MB of weights (down) are faster here; for the smaller ones
 // (QKV, O) the second kernel of the split costs more than the narrow kernel's L2 re-reads.
-bool gemm_wide_preferred(int N, int K) {
+// Beyond 8 row tiles the narrow kernel's groups of up to 16 workgroups per weight stream lose more
+// than the split's second launch costs: every product the wide kernel supports runs there.
+bool gemm_wide_preferred(int N, int K, int row_tiles) {
   const int n_cu = device_cu_count();
   const long ntiles = (N + 15) / 16;
-  return n_cu > 0 && (wide_whole((int)ntiles, n_cu) || ntiles * (K / 32) >= 100000);
+  return n_cu > 0 && (row_tiles > 8 || wide_whole((int)ntiles, n_cu) || ntiles * (K / 32) >= 100000);
 }
 
 size_t gemm_wide_workspace_bytes(int N, int K) {
