@@ -486,6 +486,29 @@ def extra_configs(np, torch, I, nav, model8, kv8, shape8, seed8, prefix8, sigma8
     for kk in (1, 4, 16):
         guarded(f"llama-8b prefix {prefix8} k={kk} batch 1",
                 lambda kk=kk: single_client_record(np, torch, I, nav, model8, shape8, seed8, prefix8, kk, sigma8, 20, 20, kv=kv8))
+    # the same pass in two halves (pipesd_nav_verify_begin / _end): how long the call that enqueues
+    # the pass keeps the host, of the whole round
+    def two_halves():
+        k = 8
+        d, q = I.make_noisy_target_drafts(lambda ds: kv8.forward_logits(0, ds)[-1], k, shape8.vocab, sigma8,
+                                          seed8 + I.SEED_NOISE + k, seed8 + I.SEED_DRAFT_U + k)
+        q_dev = torch.from_numpy(q).cuda()
+        u = I.make_uniforms(k + 1, seed8 + I.SEED_VERIFY_U + k)
+        begin_s, total_s = [], []
+        for r in range(40):
+            t0 = time.perf_counter()
+            kv8.nav_verify_begin(0, d, q_dev, u)
+            t1 = time.perf_counter()
+            kv8.nav_verify_end()
+            t2 = time.perf_counter()
+            kv8.rollback(0, prefix8)
+            if r >= 20:
+                begin_s.append(t1 - t0)
+                total_s.append(t2 - t0)
+        tb, tt = sum(begin_s) / len(begin_s), sum(total_s) / len(total_s)
+        return {"ms_per_pass": tt * 1e3, "ms_until_begin_returns": tb * 1e3, "host_free_fraction": 1.0 - tb / tt,
+                "verified_tokens_per_sec": k / tt, "passes": len(total_s)}
+    guarded(f"llama-8b prefix {prefix8} k=8 batch 1, verify in two halves (begin / end)", two_halves)
     # 16 clients on the 8B model: prefixes U[256,4096], k U[1,16] redrawn every round, noisy-target
     # drafts, 50 consecutive rounds over sequences that grow
     def cfg4():

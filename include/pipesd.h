@@ -137,6 +137,24 @@ int pipesd_nav_verify(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t p
                       const int32_t *draft_tokens, int32_t k, const float *draft_probs,
                       const float *uniforms, int32_t *accepted_len, int32_t *next_token, void *stream);
 
+/* The same pass in two halves, for a caller that has other work while the GPU runs it (receiving the
+ * next drafts, enqueueing work on other streams): pipesd_nav_verify_begin takes the arguments of
+ * pipesd_nav_verify, runs all its checks, enqueues the whole pass on `stream` and returns WITHOUT
+ * waiting; pipesd_nav_verify_end waits for it and does the bookkeeping, with the results and error
+ * behaviour of pipesd_nav_verify (bit-identical results).  draft_tokens and uniforms are copied by
+ * begin; draft_probs (device memory) must stay valid until end returns.  Between begin and end the
+ * model's buffers and the pool's blocks belong to the pass: every other entry point that computes
+ * with the model (prefill, verify, verify_batch, verify_chain, verify_begin, forward_logits) and
+ * pipesd_kv_rollback / pipesd_seq_reset on that pool return PIPESD_ESTATE, as does end without a
+ * begin.  A model must not be destroyed between begin and end.
+ * pipesd_nav_verify_done sets *done to 1 once the pass has finished on the device (end will not
+ * block), else 0; it never waits. */
+int pipesd_nav_verify_begin(pipesd_model *model, pipesd_kv *kv, int32_t seq, int32_t prefix_len,
+                            const int32_t *draft_tokens, int32_t k, const float *draft_probs,
+                            const float *uniforms, void *stream);
+int pipesd_nav_verify_done(pipesd_model *model, int32_t *done);
+int pipesd_nav_verify_end(pipesd_model *model, int32_t *accepted_len, int32_t *next_token);
+
 /* One NAV pass for each of n_seqs clients (several edge devices verified by one cloud model,
  * Appendix I): client i = seq_ids[i] (pairwise distinct, 1 <= n_seqs <= 256) with committed length
  * prefix_lens[i] and k_per_seq[i] drafts.  draft_tokens_concat (host) holds the clients' drafts one

@@ -55,6 +55,14 @@ struct pipesd_model {
   float* attn_part = nullptr;
   size_t attn_part_floats = 0;
   unsigned* attn_count = nullptr;  // arrival counters of the streaming attention kernel (zero between launches)
+  // a pass begun by pipesd_nav_verify_begin and not yet ended (the model's buffers are in use by it)
+  struct Pending {
+    bool active = false;
+    pipesd_kv* kv = nullptr;
+    int32_t seq = 0, k = 0, text_len = 0;
+    std::vector<int32_t> drafts;
+    hipStream_t st = nullptr;
+  } pending;
   int32_t* chain_alive = nullptr;  // bf16 path: one word per round of a chain (round r runs iff word r holds 1)
   const int32_t* gate = nullptr;   // the word the launches being enqueued are gated by (nullptr: they always run)
   float* row_stats = nullptr;
@@ -383,8 +391,12 @@ static void release_beyond(pipesd_kv* kv, SeqState& s, int32_t rows) {
   if (s.table_synced > keep) s.table_synced = keep;
 }
 
+// a pass begun on this pool and not yet ended still writes the sequences' blocks
+static bool pass_pending(const pipesd_kv* kv) { return kv->model && kv->model->pending.active && kv->model->pending.kv == kv; }
+
 extern "C" int pipesd_seq_reset(pipesd_kv* kv, int32_t seq) {
   if (!seq_ok(kv, seq)) return PIPESD_EINVAL;
+  if (pass_pending(kv)) return PIPESD_ESTATE;
   SeqState& s = kv->seqs[seq];
   release_beyond(kv, s, 0);
   s.text.clear();
@@ -393,6 +405,7 @@ extern "C" int pipesd_seq_reset(pipesd_kv* kv, int32_t seq) {
 
 extern "C" int pipesd_kv_rollback(pipesd_kv* kv, int32_t seq, int32_t new_prefix_len) {
   if (!seq_ok(kv, seq)) return PIPESD_EINVAL;
+  if (pass_pending(kv)) return PIPESD_ESTATE;
   SeqState& s = kv->seqs[seq];
   if (new_prefix_len < 1 || new_prefix_len > (int32_t)s.text.size()) return PIPESD_ESTATE;
   s.text.resize(new_prefix_len);
@@ -861,7 +874,7 @@ static bool layers_flag_raised(pipesd_model* m) {
 }
 
 static bool compute_ready(const pipesd_model* m, const pipesd_kv* kv) {
-  return m && kv && kv->model == m && m->on_device && kv->pool && kv->table_dev;
+  return m && kv && kv->model == m && m->on_device && kv->pool && kv->table_dev && !m->pending.active;
 }
 
 extern "C" int pipesd_prefill(pipesd_model* model, pipesd_kv* kv, int32_t seq, const int32_t* tokens, int32_t n,
@@ -1019,6 +1032,63 @@ extern "C" int pipesd_nav_verify(pipesd_model* model, pipesd_kv* kv, int32_t seq
   }
   rc = commit_verify(model, kv, seq, draft_tokens, k, model->result_host, accepted_len, next_token);
   if (rc) release_beyond(kv, s, lp - 1);
+  return rc;
+}
+
+// The same pass in two halves: everything up to the last launch, and the wait + bookkeeping.
+extern "C" int pipesd_nav_verify_begin(pipesd_model* model, pipesd_kv* kv, int32_t seq, int32_t prefix_len,
+                                       const int32_t* draft_tokens, int32_t k, const float* draft_probs,
+                                       const float* uniforms, void* stream) {
+  if (!model || !kv || kv->model != model) return PIPESD_EINVAL;
+  int rc = check_verify_args(model, kv, seq, prefix_len, draft_tokens, k, draft_probs, uniforms);
+  if (rc) return rc;  // (ESTATE also while another pass is pending: compute_ready)
+  SeqState& s = kv->seqs[seq];
+  hipStream_t st = (hipStream_t)stream;
+  model->result_host[0] = model->result_host[1] = -1;
+  rc = enqueue_verify(model, kv, seq, draft_tokens, k, draft_probs, uniforms, model->result_dev, model->result_host, st);
+  if (rc) return rc;
+  const hipError_t e = read_layers_flag(model, st);
+  if (e != hipSuccess) {
+    (void)hipStreamSynchronize(st);
+    release_beyond(kv, s, (int32_t)s.text.size() - 1);
+    return hip_fail(e, "verify step");
+  }
+  model->pending.active = true;
+  model->pending.kv = kv;
+  model->pending.seq = seq;
+  model->pending.k = k;
+  model->pending.text_len = (int32_t)s.text.size();
+  model->pending.drafts.assign(draft_tokens, draft_tokens + k);
+  model->pending.st = st;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_nav_verify_done(pipesd_model* model, int32_t* done) {
+  if (!model || !done) return PIPESD_EINVAL;
+  if (!model->pending.active) return PIPESD_ESTATE;
+  const hipError_t e = hipStreamQuery(model->pending.st);
+  if (e != hipSuccess && e != hipErrorNotReady) return hip_fail(e, "verify step");
+  *done = e == hipSuccess ? 1 : 0;
+  return PIPESD_OK;
+}
+
+extern "C" int pipesd_nav_verify_end(pipesd_model* model, int32_t* accepted_len, int32_t* next_token) {
+  if (!model || !accepted_len || !next_token) return PIPESD_EINVAL;
+  if (!model->pending.active) return PIPESD_ESTATE;
+  pipesd_model::Pending& p = model->pending;
+  SeqState& s = p.kv->seqs[p.seq];
+  const hipError_t e = hipStreamSynchronize(p.st);
+  p.active = false;  // whatever happens next, the pass is over
+  if (e != hipSuccess) {
+    release_beyond(p.kv, s, p.text_len - 1);
+    return hip_fail(e, "verify step");
+  }
+  if (layers_flag_raised(model)) {
+    release_beyond(p.kv, s, p.text_len - 1);
+    return hip_fail(hipErrorLaunchFailure, "device-wide barrier of the fused layer kernel timed out");
+  }
+  const int rc = commit_verify(model, p.kv, p.seq, p.drafts.data(), p.k, model->result_host, accepted_len, next_token);
+  if (rc) release_beyond(p.kv, s, p.text_len - 1);
   return rc;
 }
 

@@ -49,6 +49,10 @@ _SIGS = {
     "pipesd_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, C.c_int32, C.c_void_p]),
     "pipesd_nav_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_int32, C.c_void_p,
                                     _f32p, _i32p, _i32p, C.c_void_p]),
+    "pipesd_nav_verify_begin": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, _i32p, C.c_int32, C.c_void_p,
+                                          _f32p, C.c_void_p]),
+    "pipesd_nav_verify_done": (C.c_int, [C.c_void_p, _i32p]),
+    "pipesd_nav_verify_end": (C.c_int, [C.c_void_p, _i32p, _i32p]),
     "pipesd_nav_verify_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, _i32p,
                                           C.POINTER(C.c_void_p), _f32p, _i32p, _i32p, C.c_void_p]),
     "pipesd_kv_rollback": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
@@ -316,6 +320,41 @@ class KVCache:
         a, n = C.c_int32(-1), C.c_int32(-1)
         _check(_lib.pipesd_nav_verify(self.model.handle, self.handle, seq, prefix_len, _ptr(d, _i32p), k, qptr,
                                       _ptr(u, _f32p), C.byref(a), C.byref(n), _stream()), "pipesd_nav_verify")
+        return a.value, n.value
+
+    def nav_verify_begin(self, seq: int, drafts: Sequence[int], draft_probs=None, uniforms=None,
+                         prefix_len: Optional[int] = None) -> None:
+        """First half of nav_verify: enqueues the pass and returns without waiting.  The draft
+        distributions are kept alive until nav_verify_end."""
+        d = _i32(drafts)
+        k = len(d)
+        qptr, keep = None, None
+        if draft_probs is not None:
+            if isinstance(draft_probs, np.ndarray):
+                keep = torch.from_numpy(_f32(draft_probs)).cuda()
+            else:
+                keep = draft_probs.contiguous()
+            assert keep.dtype == torch.float32 and keep.numel() == k * self.model.shape.vocab
+            qptr = keep.data_ptr()
+        u = None if uniforms is None else _f32(uniforms)
+        if prefix_len is None:
+            prefix_len = self.length(seq)
+        _check(_lib.pipesd_nav_verify_begin(self.model.handle, self.handle, seq, prefix_len, _ptr(d, _i32p), k, qptr,
+                                            _ptr(u, _f32p), _stream()), "pipesd_nav_verify_begin")
+        self._pending_keep = keep
+
+    def nav_verify_done(self) -> bool:
+        done = C.c_int32(0)
+        _check(_lib.pipesd_nav_verify_done(self.model.handle, C.byref(done)), "pipesd_nav_verify_done")
+        return bool(done.value)
+
+    def nav_verify_end(self):
+        """Second half of nav_verify: waits for the pass begun last and books it; (accepted_len, next_token)."""
+        a, n = C.c_int32(-1), C.c_int32(-1)
+        try:
+            _check(_lib.pipesd_nav_verify_end(self.model.handle, C.byref(a), C.byref(n)), "pipesd_nav_verify_end")
+        finally:
+            self._pending_keep = None
         return a.value, n.value
 
     def nav_verify_batch(self, seqs: Sequence[int], drafts: Sequence[Sequence[int]], draft_probs=None,

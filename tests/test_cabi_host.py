@@ -152,3 +152,17 @@ def test_kv_create_argument_checks():
     # a device pool cannot be attached to a shape-only model
     assert nav._lib.pipesd_kv_create(m.handle, 1, 16, C.c_void_p(0x1000), 10 * bb, C.byref(h)) == nav.ESTATE
     m.close()
+
+
+def test_two_half_verify_without_a_pass_begun():
+    """pipesd_nav_verify_end / _done without a begin are state errors; null arguments are invalid."""
+    rc, h = _create(I.LLAMA_1B)
+    assert rc == nav.OK
+    a, n, done = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    assert nav._lib.pipesd_nav_verify_end(h, C.byref(a), C.byref(n)) == nav.ESTATE
+    assert nav._lib.pipesd_nav_verify_done(h, C.byref(done)) == nav.ESTATE
+    assert nav._lib.pipesd_nav_verify_end(None, C.byref(a), C.byref(n)) == nav.EINVAL
+    assert nav._lib.pipesd_nav_verify_end(h, None, C.byref(n)) == nav.EINVAL
+    assert nav._lib.pipesd_nav_verify_done(h, None) == nav.EINVAL
+    assert nav._lib.pipesd_nav_verify_begin(None, None, 0, 1, None, 1, None, None, None) == nav.EINVAL
+    assert nav._lib.pipesd_model_destroy(h) == nav.OK

@@ -583,3 +583,57 @@ def test_device_chained_rounds_at_the_8b_width(nav):
         kv.rollback(1, prefix)
     print(f"4 chained rounds (2 layers): {np.median(t_chain) * 1e3:.3f} ms with one synchronisation, "
           f"{np.median(t_single) * 1e3:.3f} ms as single calls", flush=True)
+
+
+def test_verify_in_two_halves_equals_the_one_call(nav):
+    """pipesd_nav_verify_begin + _end against pipesd_nav_verify on a twin sequence over 50 growing
+    rounds (sampling and token-matching rounds mixed): bit for bit, same blocks; while a pass is
+    pending every other computing call and rollback are state errors and change nothing.  Prints how
+    much of a round the host is free between begin and end."""
+    import time
+    shape = SMALL_BF16
+    model = nav.Model(shape, I.make_weights(shape, 61))
+    kv = nav.KVCache(model, max_seqs=2, n_blocks=2 * 80)
+    toks = I.make_tokens(40, shape.vocab, 62)
+    kv.prefill(0, toks)
+    kv.prefill(1, toks)
+    rng = np.random.default_rng(63)
+    free_s, total_s = 0.0, 0.0
+    for rnd in range(50):
+        k = int(rng.integers(1, 17))
+        d, q = I.make_independent_drafts(k, shape.vocab, 6400 + rnd, 6500 + rnd, scale=1.0)
+        greedy = rnd % 5 == 4
+        if rnd % 3 == 0:  # drafts the target tends to accept: its own argmax continuation
+            z = kv.forward_logits(1, [])
+            d = d.copy()
+            d[0] = int(z[0].argmax())
+        u = None if greedy else I.make_uniforms(k + 1, 6600 + rnd)
+        qq = None if greedy else q
+        t0 = time.perf_counter()
+        kv.nav_verify_begin(0, d, qq, u)
+        t1 = time.perf_counter()
+        if rnd == 0:
+            for call in (lambda: kv.nav_verify(1, d, qq, u), lambda: kv.nav_verify_begin(1, d, qq, u),
+                         lambda: kv.forward_logits(1, []), lambda: kv.rollback(1, 10), lambda: kv.prefill(1, toks),
+                         lambda: kv.nav_verify_batch([1], [list(d)], None if greedy else [qq], None if greedy else [u])):
+                with pytest.raises(nav.PipesdError) as e:
+                    call()
+                assert e.value.status == nav.ESTATE
+            assert kv.length(1) == 40
+        if rnd == 1:  # polling never blocks and ends with "done"
+            while not kv.nav_verify_done():
+                pass
+        r0 = kv.nav_verify_end()
+        t2 = time.perf_counter()
+        free_s += t2 - t1
+        total_s += t2 - t0
+        r1 = kv.nav_verify(1, d, qq, u)
+        assert r0 == r1, (rnd, r0, r1)
+        assert kv.length(0) == kv.length(1) and kv.seq_blocks(0) == kv.seq_blocks(1)
+    with pytest.raises(nav.PipesdError) as e:
+        kv.nav_verify_end()
+    assert e.value.status == nav.ESTATE
+    probe = I.make_tokens(3, shape.vocab, 64)
+    np.testing.assert_array_equal(kv.forward_logits(0, probe), kv.forward_logits(1, probe))
+    print(f"two-half verify: the host is free {100 * free_s / total_s:.0f} % of a round "
+          f"({1e3 * total_s / 50:.3f} ms per round, begin returns after {1e3 * (total_s - free_s) / 50:.3f} ms)", flush=True)
