@@ -286,6 +286,36 @@ def test_llama_13b_width_batch_of_four(nav):
               f"with fp32 keys and values; accepted {a_b}", flush=True)
 
 
+def test_llama_13b_width_context_beyond_4096_against_the_checker(nav):
+    """One client of the 13B width (2 layers) with a context of 4200 tokens (beyond 4096: the streaming
+    attention cuts it into 512-token splits, 17 rows per KV head = two query tiles per workgroup),
+    k = 16, drafts with sigma 1.0: logits and the decision against the checker."""
+    wl = I.WORKLOADS["llama-13b"]
+    shape, seed = wl["shape"].truncated(2), wl["seed"]
+    w = I.make_weights(shape, seed + I.SEED_WEIGHTS)
+    model = nav.Model(shape, w)
+    n, k = 4200, wl["k"]
+    toks = I.make_tokens(n, shape.vocab, seed + I.SEED_PREFIX + 7)
+    kv = nav.KVCache(model, max_seqs=1, n_blocks=(n + 48) // 16 + 1)
+    kv.prefill(0, toks)
+    oseq = oracle_side(shape, w, toks, n + 40)
+    for rnd in range(2):
+        d, q = drafts_from_oracle(oseq, k, wl["sigma"], seed + I.SEED_NOISE + 40 + rnd, seed + I.SEED_DRAFT_U + 40 + rnd)
+        u = I.make_uniforms(k + 1, seed + I.SEED_VERIFY_U + 40 + rnd)
+        z_ref = oseq.forward_logits(d)
+        z = kv.forward_logits(0, d)
+        err = float(np.abs(z - z_ref).max())
+        assert err <= TOL_BF16, f"round {rnd}: logits max-abs {err}"
+        a_ref, n_ref = oseq.nav_verify(d, q, u)
+        a, nxt = kv.nav_verify(0, [int(t) for t in d], q, u)
+        if a != a_ref:
+            assert decision_excused(softmax_rows(z_ref), q, d, u, a, a_ref), (rnd, (a, nxt), (a_ref, n_ref))
+            break  # the sequences have parted
+        assert nxt == n_ref, (rnd, (a, nxt), (a_ref, n_ref))
+        assert kv.length(0) == len(oseq.committed)
+        print(f"llama-13b-L2, context {kv.length(0)}: logits max-abs {err:.2e} vs the checker; accepted {a}", flush=True)
+
+
 def test_llama_13b_width_long_context_consistency(nav):
     """Prefix 8192, k = 16 on the 13B width (2 layers): the pass reproduces bit for bit after a
     rollback, its rows equal those of shorter passes, and the token-matching decision is the argmax
