@@ -130,17 +130,21 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 // [split] block a whole number of 128-byte lines, so no cache line holds partials of two groups:
 // the merging workgroup reads lines nobody on its compute unit has touched during this kernel,
 // after every writer has drained its write-through stores and then incremented the counter.
-constexpr int kStreamMinSpan = kAttnWgTokens;  // a client's context is cut into at most kStreamMaxSplits
+constexpr int kStreamWaves = 4;                // waves per workgroup: one per SIMD, so that two workgroups in different
+                                               // phases (waiting for keys and values / multiplying) share a compute unit
+constexpr int kStreamWgTokens = kStreamWaves * 32;  // tokens per workgroup and step
+constexpr int kStreamMinSpan = 256;            // a client's context is cut into at most kStreamMaxSplits
 constexpr int kStreamMaxSplits = 16;           // splits of 256 * 2^j tokens, j as small as that allows
 constexpr int kStreamMaxRows = 128;            // rows of a client (a prompt block brings up to 128; a NAV pass at most kMaxRows)
 
+constexpr size_t stream_lds_floats(int hd) { return (size_t)kStreamWaves * 16 * (hd + 4) + 2 * kStreamWaves * 16; }
 template <int HD>
 constexpr size_t stream_lds_bytes(int T) {
-  return attn_lds_floats(HD) * sizeof(float) + (size_t)T * (HD / 32) * 2 * 64 * 16 + 16;
+  return stream_lds_floats(HD) * sizeof(float) + (size_t)T * (HD / 32) * 2 * 64 * 16 + 16;
 }
 
 template <int HD, int T>
-__global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const float* q, KvView kv, int layer, int n_q_heads,
+__global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const float* q, KvView kv, int layer, int n_q_heads,
                                                                       AttnBatch batch, float* part, uint4* outp,
                                                                       int act_tiles, const int32_t* gate,
                                                                       unsigned* counters) {
@@ -155,15 +159,15 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
   const int nqt = (R + 15) / 16, qt0 = (int)blockIdx.z * T;
   if (split >= cl.nsplit || qt0 >= nqt) return;  // whole workgroup
   float(*o_lds)[16][ROW] = (float(*)[16][ROW])lds;
-  float(*m_lds)[16] = (float(*)[16])(lds + (size_t)kAttnWaves * 16 * ROW);
-  float(*l_lds)[16] = m_lds + kAttnWaves;
-  au32x4* q_lds = (au32x4*)(lds + attn_lds_floats(HD));  // [T][KSQ][hi, lo][64 lanes]
+  float(*m_lds)[16] = (float(*)[16])(lds + (size_t)kStreamWaves * 16 * ROW);
+  float(*l_lds)[16] = m_lds + kStreamWaves;
+  au32x4* q_lds = (au32x4*)(lds + stream_lds_floats(HD));  // [T][KSQ][hi, lo][64 lanes]
   int* last_lds = (int*)(q_lds + T * KSQ * 2 * 64);
   const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15, g = lane >> 4;
   const int total = cl.start_pos + m;
   const int span0 = split * cl.span, span1 = min(total, span0 + cl.span);
-  const int nsteps = (span1 - span0 + kAttnWgTokens - 1) / kAttnWgTokens;
+  const int nsteps = (span1 - span0 + kStreamWgTokens - 1) / kStreamWgTokens;
   const uint16_t* pool = (const uint16_t*)kv.pool;
   const int32_t* table = kv.table + cl.table_off;
   const float scale = 1.0f / sqrtf((float)HD);
@@ -172,17 +176,21 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
 
   // ---- queries of the T tiles: global (row = [qd hi halves][qd lo halves]) -> LDS in operand order ----
   constexpr int QCH = 16 * (HD / 8) * 2;  // 16-byte pieces per tile
-  au32x4 qreg[T];
-  const bool q_mine = tid < QCH;
+  constexpr int QPT = (QCH + kStreamWaves * 64 - 1) / (kStreamWaves * 64);  // pieces per thread and tile
+  au32x4 qreg[T][QPT];
   {
-    const int hl = tid / (16 * (HD / 8)), rem = tid % (16 * (HD / 8)), qc = rem / (HD / 8), j = rem % (HD / 8);
     const uint16_t* q16 = (const uint16_t*)q + (size_t)cl.row_off * 2 * qd;
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-      const int rr = (qt0 + t) * 16 + qc;  // rows beyond the head group read row 0 of the group (their results are dropped)
-      const int gq = rr < R ? div_small(rr, m_rinv) : 0, r = rr < R ? rr - gq * m : 0;
-      qreg[t] = q_mine ? *(const au32x4*)(q16 + (size_t)r * 2 * qd + hl * qd + (kvh * group + gq) * HD + j * 8)
-                       : au32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < QPT; ++i) {
+      const int piece = tid + i * kStreamWaves * 64;
+      const int hl = piece / (16 * (HD / 8)), rem = piece % (16 * (HD / 8)), qc = rem / (HD / 8), j = rem % (HD / 8);
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        const int rr = (qt0 + t) * 16 + qc;  // rows beyond the head group read row 0 of the group (their results are dropped)
+        const int gq = rr < R ? div_small(rr, m_rinv) : 0, r = rr < R ? rr - gq * m : 0;
+        qreg[t][i] = piece < QCH ? *(const au32x4*)(q16 + (size_t)r * 2 * qd + hl * qd + (kvh * group + gq) * HD + j * 8)
+                                 : au32x4{0u, 0u, 0u, 0u};
+      }
     }
   }
 
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
     au32x2 lo[HT], hi[HT];
   };
   auto kv_base = [&](int it, int tt) {
-    const int tb = span0 + it * kAttnWgTokens + w * 32 + tt * 16;
+    const int tb = span0 + it * kStreamWgTokens + w * 32 + tt * 16;
     const int blk = table[tb < total ? tb / kBlockTokens : 0];
     return (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
   };
@@ -238,7 +246,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
   // the scores of both tiles.
   constexpr bool V_AHEAD = T == 1;
   auto consume = [&](const KRegs& bk, VRegs& bv, int it) {
-    const int tok0 = span0 + it * kAttnWgTokens + w * 32;
+    const int tok0 = span0 + it * kStreamWgTokens + w * 32;
     if (tok0 >= total) return;  // (wave-uniform) nothing cached there
     if constexpr (!V_AHEAD) request_v(bv, it);
     asm volatile("" ::: "memory");  // the queries are read from LDS in every step, not kept in registers
@@ -326,10 +334,14 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
     request_k(kb, 1);
     if constexpr (V_AHEAD) request_v(vb, 1);
   }
-  if (q_mine) {
-    const int hl = tid / (16 * (HD / 8)), rem = tid % (16 * (HD / 8)), qc = rem / (HD / 8), j = rem % (HD / 8);
 #pragma unroll
-    for (int t = 0; t < T; ++t) q_lds[((t * KSQ + (j >> 2)) * 2 + hl) * 64 + (j & 3) * 16 + qc] = qreg[t];
+  for (int i = 0; i < QPT; ++i) {
+    const int piece = tid + i * kStreamWaves * 64;
+    const int hl = piece / (16 * (HD / 8)), rem = piece % (16 * (HD / 8)), qc = rem / (HD / 8), j = rem % (HD / 8);
+    if (piece < QCH) {
+#pragma unroll
+      for (int t = 0; t < T; ++t) q_lds[((t * KSQ + (j >> 2)) * 2 + hl) * 64 + (j & 3) * 16 + qc] = qreg[t][i];
+    }
   }
   __syncthreads();
   for (int it = 0; it < nsteps; it += 2) {
@@ -366,12 +378,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_stream_kernel(const floa
     if (mr < 16) {
       float M = m_lds[0][mr];
 #pragma unroll
-      for (int ww = 1; ww < kAttnWaves; ++ww) M = fmaxf(M, m_lds[ww][mr]);
+      for (int ww = 1; ww < kStreamWaves; ++ww) M = fmaxf(M, m_lds[ww][mr]);
       const float M_ref = (M == -INFINITY) ? 0.f : M;
       float L = 0.f;
       f32x4 oa = f32x4{0.f, 0.f, 0.f, 0.f}, ob = oa;
 #pragma unroll
-      for (int ww = 0; ww < kAttnWaves; ++ww) {
+      for (int ww = 0; ww < kStreamWaves; ++ww) {
         const float sw = attn_exp(m_lds[ww][mr] - M_ref);
         L += l_lds[ww][mr] * sw;
         oa += *(const f32x4*)&o_lds[ww][mr][e0] * sw;
@@ -494,7 +506,7 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
         if (e != hipSuccess) return e;
         stream_lds_allowed = true;
       }
-      const dim3 grid(c.kv.n_kv_heads, splits, nz), block(kAttnWaves * 64);
+      const dim3 grid(c.kv.n_kv_heads, splits, nz), block(kStreamWaves * 64);
       uint4* outp = (uint4*)c.outp;
       if (h == 128 && T == 2)
         attn_stream_kernel<128, 2><<<grid, block, stream_lds_bytes<128>(2), st>>>(c.q, c.kv, c.layer, c.n_q_heads, b, c.part, outp, c.act_tiles, c.gate, c.counters);

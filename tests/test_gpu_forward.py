@@ -349,7 +349,7 @@ def test_fused_layer_kernel_agrees_with_per_projection_launches(nav, shape, pref
     """One cooperative kernel for all layers (opt-in) vs one kernel per projection: the projections
     run the same device code on the same tiles in the same order; attention sums the context in
     256-token splits there and in the streaming kernel's order here, so logits agree to rounding
-    (1e-4) and the cached keys and values to a bf16 rounding step; the fused kernel itself is
+    (5e-4) and the cached keys and values to a bf16 rounding step; the fused kernel itself is
     reproducible bit for bit."""
     w = I.make_weights(shape, 77)
     toks = I.make_tokens(prefix, shape.vocab, 78)
@@ -365,7 +365,7 @@ def test_fused_layer_kernel_agrees_with_per_projection_launches(nav, shape, pref
     z_fused = kv.forward_logits(1, d)
     assert model.fused_launches() > 0
     np.testing.assert_array_equal(z_fused, kv.forward_logits(1, d))
-    np.testing.assert_allclose(z_plain, z_fused, rtol=0, atol=1e-4)
+    np.testing.assert_allclose(z_plain, z_fused, rtol=0, atol=5e-4)
     for layer in range(shape.n_layers):
         for pos in (0, prefix // 2, prefix - 2):
             k0, v0 = kv.read_kv(0, layer, pos)
