@@ -112,13 +112,13 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 }
 
 // ------------------------------------------------------------------------------------------------
-// bf16 cache, passes of few rows per client (the NAV pass itself): one workgroup walks a whole span
-// of the context
+// bf16 cache, passes of few rows per client (the NAV pass itself) and prompt blocks: one workgroup
+// walks a whole split of the context
 // ------------------------------------------------------------------------------------------------
-// Workgroup (kv head, split of a client's context, T query tiles): wave w takes tokens
-// span0 + it*256 + w*32 .. + 31 in step it and keeps a running (max, sum, O) per query tile in
+// Workgroup (kv head, split of a client's context, T query tiles) of four waves: wave w takes tokens
+// span0 + it*128 + w*32 .. + 31 in step it and keeps a running (max, sum, O) per query tile in
 // registers (a step's keys, and for T = 1 its values, are requested one step ahead).  After the
-// last step the eight waves' states are merged through LDS, waves in index order.  A client whose
+// last step the four waves' states are merged through LDS, waves in index order.  A client whose
 // context is one split gets its normalised rows written straight in the packed form the O
 // projection reads.  Otherwise the workgroup writes its partial through to memory and counts
 // itself in; the workgroup that arrives last merges the splits, in index order, and writes the
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
     }
   }
 
-  // ---- merge of the eight waves, tile after tile: thread -> (query row, 8 consecutive elements) ----
+  // ---- merge of the waves, tile after tile: thread -> (query row, 8 consecutive elements) ----
   constexpr int TPR = HD / 8;
   const int mr = tid / TPR, e0 = (tid % TPR) * 8;
   const int nz = (nqt + T - 1) / T;
