@@ -27,6 +27,8 @@
 //    in a workspace; a second small kernel adds the W sums in order and runs the epilogue.
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "device_gemm.h"
 
 namespace pipesd {
@@ -105,26 +107,52 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
   const int nsl = (WHOLE ? a.W : 1) * a.P;  // slices this workgroup walks
 
   // A stage's fragments, numbered f = ks * KF + (0..7 weights | 8.. activations (row tile, half)), are
-  // dealt to the waves round robin: wave w requests f = w, w + kWideWaves, ..
-  const u32x4* wbase = a.wp + lane;
-  // first k-step of stage s of the j-th slice this workgroup walks
-  auto kstep0 = [&](int j, int s) {
-    const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
-    return (p * a.W + wj) * 16 + s * kWideStage;
-  };
-  // request this wave's share of the stage whose first k-step is k0 into ring buffer `buf`
-  auto request = [&](int k0, int buf) {
-    u32x4* dst = bl + (size_t)buf * SF * 64;
+  // dealt to the waves round robin: wave w requests f = w, w + kWideWaves, ..  What a wave asks for is
+  // fixed for the whole walk except for the k-step, so each of its NPER requests keeps a source
+  // pointer that moves on by one stage with every request (and by the jump to the next slice of the
+  // walk at a slice boundary): no per-request index arithmetic on the scalar unit, which all waves of
+  // the compute unit share.
+  const char* rp[NPER];  // this lane's 16 bytes of fragment i of the next stage to request
+  int rstep[NPER];       // bytes per k-step of that operand (wave-uniform)
+  int rlds[NPER];        // where the fragment goes in a stage buffer (bytes)
+  const int kslice0 = WHOLE ? 0 : role;  // first slice of the walk
+#pragma unroll
+  for (int i = 0; i < NPER; ++i) {
+    const int f = w + kWideWaves * i, ks = f / KF, e = f % KF;  // (w is uniform)
+    rlds[i] = f * 1024;
+    if (e < kWideWgTiles) {
+      rstep[i] = 1024;
+      rp[i] = (const char*)(a.wp + ((size_t)min(cg * kWideWgTiles + e, a.ntiles - 1) * a.kst + ks) * 64 + lane);
+    } else {  // ActPack is in consumer lane order
+      rstep[i] = ROWT * 2 * 1024;
+      rp[i] = (const char*)(a.actp + ((size_t)ks * (ROWT * 2) + (e - kWideWgTiles)) * 64 + lane);
+    }
+    rp[i] += (ptrdiff_t)(kslice0 * 16) * rstep[i];
+  }
+  // request this wave's share of the next stage into the stage buffer at byte offset `buf`
+  auto request = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NPER; ++i) {
-      const int f = w + kWideWaves * i, ks = f / KF, e = f % KF;  // (KF and kWideWaves are compile-time; w is uniform)
-      const u32x4* src;
-      if (e < kWideWgTiles)
-        src = wbase + ((size_t)min(cg * kWideWgTiles + e, a.ntiles - 1) * a.kst + (k0 + ks)) * 64;
-      else  // ActPack is in consumer lane order
-        src = a.actp + ((size_t)(k0 + ks) * (ROWT * 2) + (e - kWideWgTiles)) * 64 + lane;
-      frag_to_lds(src, dst + f * 64);
+      frag_to_lds((const u32x4*)rp[i], (u32x4*)((char*)bl + buf + rlds[i]));
+      rp[i] += (size_t)(kWideStage * rstep[i]);
     }
+  };
+  // the requests have covered a slice: move to the next slice of the walk (slice p*W + w follows
+  // (p-1)*W + w; role w + 1 follows role w); past the end of the walk, to the last slice again
+  int rq_j = 0, rq_p = 0;
+  auto request_turn = [&]() {
+    int dsl = 0;  // slices from the one just requested to the next
+    if (rq_j + 1 < nsl) {
+      dsl = a.W;
+      if constexpr (WHOLE) {
+        if (rq_p + 1 == a.P) dsl = 1 - (a.P - 1) * a.W;
+      }
+    }
+    ++rq_j;
+    rq_p = rq_p + 1 == a.P ? 0 : rq_p + 1;
+    const int dk = (dsl - 1) * 16;  // (the pointers are already one slice further)
+#pragma unroll
+    for (int i = 0; i < NPER; ++i) rp[i] += (ptrdiff_t)(dk * rstep[i]);
   };
 
   // acc: the slice being accumulated; run: running sum of this role's slices (P > 1); tot: sum of
@@ -142,96 +170,128 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
   // must have landed: this wave's loads of it have once at most the next stage's are outstanding,
   // and behind the workgroup barrier every wave's have.  The same wait covers this wave's own LDS
   // reads, so behind the barrier nobody reads the stage before any more, and its buffer takes the
-  // stage after next.  Past the end of the walk the workgroup's first stages are requested and read
+  // stage after next.  Past the end of the walk the last slice's first stages are requested and read
   // again (and never used), so the counts hold to the end.
   constexpr int BPS = kWideStage * RW;           // blocks per stage
   constexpr int kAhead = BPS >= 4 ? 3 : 1;       // (a power of two minus one, below BPS)
   constexpr int BPSL = kWideSliceStages * BPS;   // blocks per slice (a multiple of 4)
+  constexpr int kStageBytes = SF * 1024;
   u32x4 bq[kAhead + 1][2];                       // ring of activation operand pairs
   constexpr int WR = RW >= kAhead ? 2 : 4;       // k-steps whose weight fragments are held (reads run at most that far ahead)
   u32x4 wfb[WR][4];                              // weight fragments of the last WR k-steps
-  int rb = 0;                                    // ring buffer of the stage being read
-  // read the operands of block b of the stage in buffer `buf`; kq = its k-step within the slice
-  auto read_block = [&](int buf, int b, int kq, int slot) {
-    const u32x4* sb = bl + (size_t)buf * SF * 64 + lane;
-    const int ks = b / RW, rt = (b % RW) * WMS + wm;
-    if (b % RW == 0) {
-#pragma unroll
-      for (int ra = 0; ra < 4; ++ra) wfb[kq & (WR - 1)][ra] = sb[(ks * KF + wn * 4 + ra) * 64];
-    }
-    if (rt < x.row_tiles) {  // (wave-uniform) a row tile past the pass is neither read nor multiplied
-      bq[slot][0] = sb[(ks * KF + kWideWgTiles + rt * 2) * 64];
-      bq[slot][1] = sb[(ks * KF + kWideWgTiles + rt * 2 + 1) * 64];
-    }
-  };
-  // the stage (j, s) has landed for every wave and the stage before it is no longer read; ask for
-  // the stage after next
-  auto stage_ready = [&](int j, int s) {
+  int rd = 0;                                    // stage buffer being read (byte offset in the ring)
+  // this lane's 16 bytes of the wave's first weight fragment / first activation fragment in a stage buffer
+  const char* lw = (const char*)bl + (wn * 4 * 64 + lane) * 16;
+  const char* la = (const char*)bl + ((kWideWgTiles + wm * 2) * 64 + lane) * 16;
+  // the next stage has landed for every wave and the stage before it is no longer read: move on to
+  // it and ask for the stage after next; s = the new stage's place in its slice
+  auto stage_ready = [&](int s) {
+    const int freed = rd;
+    rd = rd == (kWideRing - 1) * kStageBytes ? 0 : rd + kStageBytes;
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER) : "memory");
     __builtin_amdgcn_s_barrier();
-    const int s2 = (s + 2) % kWideSliceStages, j2 = j + (s + 2) / kWideSliceStages;
-    request(j2 < nsl ? kstep0(j2, s2) : kstep0(0, s2), rb == 0 ? kWideRing - 1 : rb - 1);
+    if ((s + 2) % kWideSliceStages == 0) request_turn();
+    request(freed);
   };
 
-  request(kstep0(0, 0), 0);
-  request(kstep0(0, 1), 1);
+  request(0);
+  request(kStageBytes);
   if (WHOLE && a.ssq_in != nullptr) {
     constexpr int RPW = ROWT * 16 / kWideWaves;  // rows whose rstd this wave computes: w, w + kWideWaves, ..
 #pragma unroll
     for (int h = 0; h < (RPW + 15) / 16; ++h)
       wide_rstd_rows<(RPW < 16 ? RPW : 16)>(a, w + 16 * kWideWaves * h, kWideWaves, lane, rstd_lds, w + 16 * kWideWaves * h);
   }
-  stage_ready(0, 0);
-#pragma unroll
-  for (int b = 0; b < kAhead; ++b) read_block(0, b, b / RW, b);
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER) : "memory");
+  __builtin_amdgcn_s_barrier();
+  request(2 * kStageBytes);
 
-  for (int j = 0; j < nsl; ++j) {
+  // The walk, compiled once per number LR of this wave's live row tiles (they are r*WMS + wm,
+  // r < LR): a row tile past the pass is neither read nor multiplied, and no block asks whether it
+  // is live.
+  auto walk = [&](auto lrc) {
+    constexpr int LR = decltype(lrc)::value;
+    // read the operands of block b of the stage being read; kq = its k-step within the slice
+    auto read_block = [&](int b, int kq, int slot) {
+      const int ks = b / RW, r = b % RW;
+      if (r == 0 && LR > 0) {
 #pragma unroll
-    for (int bn = 0; bn < BPSL; ++bn) {
-      {  // operands of the block kAhead ahead
-        const int pn = (bn + kAhead) % BPSL, jn = j + (bn + kAhead) / BPSL;
-        const int sn = pn / BPS, b = pn % BPS;
-        if (b == 0) {
-          rb = rb == kWideRing - 1 ? 0 : rb + 1;
-          stage_ready(jn, sn);
+        for (int ra = 0; ra < 4; ++ra) wfb[kq & (WR - 1)][ra] = *(const u32x4*)(lw + rd + (ks * KF + ra) * 1024);
+      }
+      if (r < LR) {
+        bq[slot][0] = *(const u32x4*)(la + rd + (ks * KF + r * WMS * 2) * 1024);
+        bq[slot][1] = *(const u32x4*)(la + rd + (ks * KF + r * WMS * 2 + 1) * 1024);
+      }
+    };
+#pragma unroll
+    for (int b = 0; b < kAhead; ++b) read_block(b, b / RW, b);
+
+    int p = 0, wj = kslice0;  // the slice being multiplied is p*W + wj
+    for (int j = 0; j < nsl; ++j) {
+#pragma unroll
+      for (int bn = 0; bn < BPSL; ++bn) {
+        {  // operands of the block kAhead ahead
+          const int pn = (bn + kAhead) % BPSL;
+          const int sn = pn / BPS, b = pn % BPS;
+          if (b == 0) stage_ready(sn);
+          read_block(b, pn / RW, pn & kAhead);
         }
-        read_block(rb, b, pn / RW, pn & kAhead);
+        // (keeps the reads where they are written, kAhead blocks ahead of their use: left alone, the
+        // scheduler sinks them to just in front of their multiplies and every block waits for LDS)
+        __builtin_amdgcn_sched_barrier(0);
+        const int kq = bn / RW, r = bn % RW;
+        const bool first = kq == 0;  // a slice starts from zero
+        if (r < LR) {
+          const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
+#pragma unroll
+          for (int ra = 0; ra < 4; ++ra)
+            acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
+#pragma unroll
+          for (int ra = 0; ra < 4; ++ra)
+            acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bo, acc[ra][r], 0, 0, 0);
+        }
       }
-      // (keeps the reads where they are written, kAhead blocks ahead of their use: left alone, the
-      // scheduler sinks them to just in front of their multiplies and every block waits for LDS)
+      // The slice is complete: fold it into the role's running sum, a complete role into the total.
+      // (The last products may have been issued in another basic block, where the compiler pads no
+      // wait states for the adds below: spell them out.)
       __builtin_amdgcn_sched_barrier(0);
-      const int kq = bn / RW, r = bn % RW;
-      const bool first = kq == 0;  // a slice starts from zero
-      if (r * WMS + wm < x.row_tiles) {  // (wave-uniform) a row tile past the pass is not multiplied
-        const bf16x8 bh = as_bf16x8(bq[bn & kAhead][0]), bo = as_bf16x8(bq[bn & kAhead][1]);
+      asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bh, first ? zero : acc[ra][r], 0, 0, 0);
+      for (int ra = 0; ra < 4; ++ra)
 #pragma unroll
-        for (int ra = 0; ra < 4; ++ra)
-          acc[ra][r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wfb[kq & (WR - 1)][ra]), bo, acc[ra][r], 0, 0, 0);
-      }
-    }
-    // The slice is complete: fold it into the role's running sum, a complete role into the total.
-    // (The last products may have been issued in another basic block, where the compiler pads no
-    // wait states for the adds below: spell them out.)
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    const int wj = WHOLE ? j / a.P : role, p = WHOLE ? j % a.P : j;
-#pragma unroll
-    for (int ra = 0; ra < 4; ++ra)
-#pragma unroll
-      for (int r = 0; r < RW; ++r) {
-        if constexpr (P1) {
-          if constexpr (WHOLE) tot[ra][r] = tot[ra][r] + acc[ra][r];  // (zero + first role)
-        } else {
-          run[ra][r] = p == 0 ? acc[ra][r] : run[ra][r] + acc[ra][r];
-          if constexpr (WHOLE) {
-            if (p == a.P - 1) tot[ra][r] = (wj == 0 ? zero : tot[ra][r]) + run[ra][r];
+        for (int r = 0; r < LR; ++r) {
+          if constexpr (P1) {
+            if constexpr (WHOLE) tot[ra][r] = tot[ra][r] + acc[ra][r];  // (zero + first role)
+          } else {
+            run[ra][r] = p == 0 ? acc[ra][r] : run[ra][r] + acc[ra][r];
+            if constexpr (WHOLE) {
+              if (p == a.P - 1) tot[ra][r] = (wj == 0 ? zero : tot[ra][r]) + run[ra][r];
+            }
           }
         }
+      if (++p == a.P) {
+        p = 0;
+        if constexpr (WHOLE) ++wj;
       }
+    }
+  };
+  {
+    int lr = 0;  // this wave's live row tiles
+#pragma unroll
+    for (int r = 0; r < RW; ++r) lr += (r * WMS + wm < x.row_tiles) ? 1 : 0;
+    static_assert(RW == 1 || RW == 4, "the dispatch below lists the live counts");
+    if constexpr (RW == 1) {
+      if (lr == 1) walk(std::integral_constant<int, 1>{}); else walk(std::integral_constant<int, 0>{});
+    } else {
+      switch (lr) {
+        case 4: walk(std::integral_constant<int, 4>{}); break;
+        case 3: walk(std::integral_constant<int, 3>{}); break;
+        case 2: walk(std::integral_constant<int, 2>{}); break;
+        case 1: walk(std::integral_constant<int, 1>{}); break;
+        default: walk(std::integral_constant<int, 0>{}); break;
+      }
+    }
   }
   // the requests past the end of the walk must have landed before the workgroup gives its LDS back
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
