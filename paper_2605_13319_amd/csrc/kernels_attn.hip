@@ -8,6 +8,7 @@
 #include <algorithm>
 
 #include "device_attn.h"
+#include "device_dma.h"
 
 namespace pipesd {
 
@@ -117,8 +118,12 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 // ------------------------------------------------------------------------------------------------
 // Workgroup (kv head, split of a client's context, T query tiles) of four waves: wave w takes tokens
 // span0 + it*128 + w*32 .. + 31 in step it and keeps a running (max, sum, O) per query tile in
-// registers (a step's keys, and for T = 1 its values, are requested one step ahead).  After the
-// last step the four waves' states are merged through LDS, waves in index order.  A client whose
+// registers.  A step's keys are requested one step ahead, into registers.  So are its values for
+// T = 1; for T = 2 (twice the running state, no registers left for that) the values of the next
+// step are copied from memory straight into an LDS buffer of the wave's own (the LDS its state goes
+// to in the merge) as soon as the wave has read the current step's out of it, and travel during the
+// rest of the step and the next step's scores.  After the last step the four waves' states are
+// merged through LDS, waves in index order.  A client whose
 // context is one split gets its normalised rows written straight in the packed form the O
 // projection reads.  Otherwise the workgroup writes its partial through to memory and counts
 // itself in; the workgroup that arrives last merges the splits, in index order, and writes the
@@ -133,6 +138,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void attn_mfma_kernel(const float*
 constexpr int kStreamWaves = 4;                // waves per workgroup: one per SIMD, so that two workgroups in different
                                                // phases (waiting for keys and values / multiplying) share a compute unit
 constexpr int kStreamWgTokens = kStreamWaves * 32;  // tokens per workgroup and step
+constexpr int kStreamMaxSteps = 64;            // steps of a split (a lane per step holds its block-table entries)
 constexpr int kStreamMinSpan = 256;            // a client's context is cut into at most kStreamMaxSplits
 constexpr int kStreamMaxSplits = 16;           // splits of 256 * 2^j tokens, j as small as that allows
 constexpr int kStreamMaxRows = 128;            // rows of a client (a prompt block brings up to 128; a NAV pass at most kMaxRows)
@@ -200,15 +206,24 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
   struct VRegs {
     au32x2 lo[HT], hi[HT];
   };
-  auto kv_base = [&](int it, int tt) {
-    const int tb = span0 + it * kStreamWgTokens + w * 32 + tt * 16;
-    const int blk = table[tb < total ? tb / kBlockTokens : 0];
+  // The block-table entries of this wave's tokens are read once, before the first step, and held in
+  // registers: lane L has the two of step L (a split is at most 64 steps).  Looked up from memory
+  // per request, every request would first wait for all loads before it, the step's keys and
+  // values among them.
+  int step_blk[2];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    const int tb = span0 + lane * kStreamWgTokens + w * 32 + tt * 16;
+    step_blk[tt] = table[tb < total ? tb / kBlockTokens : 0];
+  }
+  auto block_base = [&](int it, int tt) {
+    const int blk = __builtin_amdgcn_readlane(step_blk[tt], it);
     return (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems;
   };
   auto request_k = [&](KRegs& b, int it) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int64_t base = kv_base(it, tt);
+      const int64_t base = block_base(it, tt);
 #pragma unroll
       for (int s = 0; s < KSQ; ++s)
         b.k[tt][s] = *(const au32x4*)(pool + base + ((int64_t)kvh * kBlockTokens + c) * HD + s * 32 + g * 8);
@@ -217,11 +232,29 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
   auto request_v = [&](VRegs& b, int it) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int64_t base = kv_base(it, tt);
+      const int64_t base = block_base(it, tt);
 #pragma unroll
       for (int j = 0; j < HT; ++j) {
         const au32x2 v = *(const au32x2*)(pool + base + kv.v_offset + ((int64_t)kvh * HD + j * 16 + c) * kBlockTokens + g * 4);
         if (tt == 0) b.lo[j] = v; else b.hi[j] = v;
+      }
+    }
+  };
+
+  // T = 2: the values of a step through LDS.  The wave's buffer holds the step's two blocks as they
+  // are in memory ([element][16 tokens]); one load instruction copies 32 elements' rows (lane ->
+  // element lane/2, tokens 8 (lane&1) .. +7).
+  constexpr int NVL = 2 * (HD / 32);  // load instructions per step
+  char* vbuf = (char*)lds + (size_t)w * 16 * ROW * sizeof(float);  // (= the wave's rows of o_lds)
+  static_assert(2 * HD * kBlockTokens * 2 <= 16 * ROW * (int)sizeof(float), "a step's values fit the wave's merge rows");
+  auto request_v_lds = [&](int it) {
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int64_t base = block_base(it, tt);
+#pragma unroll
+      for (int qd32 = 0; qd32 < HD / 32; ++qd32) {
+        const uint16_t* src = pool + base + kv.v_offset + ((int64_t)kvh * HD + qd32 * 32 + (lane >> 1)) * kBlockTokens + (lane & 1) * 8;
+        lds_dma16(src, vbuf + (tt * (HD / 32) + qd32) * 1024);
       }
     }
   };
@@ -241,14 +274,15 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
     pos_q[t] = cl.start_pos + (rr < R ? rr - div_small(rr, m_rinv) * m : 0);
   }
 
-  // T = 1: keys and values of a step are both requested a step ahead.  T = 2 (twice the running
-  // state): only the keys are; the values are requested when the step begins and travel during
-  // the scores of both tiles.
+  // T = 1: keys and values of a step are both requested a step ahead, into registers.  T = 2: the
+  // keys are; the values come through the wave's LDS buffer.  This wave's vector-memory operations
+  // complete in the order issued, and the order is: keys 0, values 0, keys 1 (all landed before
+  // step 0) | step 0: values 1, keys 2 | step 1: values 2, keys 3 | ..  So a step's values have
+  // landed once at most the loads of the next step's keys (if there is a next step) are outstanding.
   constexpr bool V_AHEAD = T == 1;
   auto consume = [&](const KRegs& bk, VRegs& bv, int it) {
     const int tok0 = span0 + it * kStreamWgTokens + w * 32;
     if (tok0 >= total) return;  // (wave-uniform) nothing cached there
-    if constexpr (!V_AHEAD) request_v(bv, it);
     asm volatile("" ::: "memory");  // the queries are read from LDS in every step, not kept in registers
     // all 32 tokens are cached tokens that every row of the pass sees: no masks needed
     const bool full = tok0 + 31 <= cl.start_pos;
@@ -257,8 +291,22 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
     for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
       for (int s = 0; s < KSQ; ++s) kf[tt][s] = __builtin_bit_cast(bf16x8, bk.k[tt][s]);
+    if constexpr (V_AHEAD) {
 #pragma unroll
-    for (int j = 0; j < HT; ++j) vf[j] = __builtin_bit_cast(bf16x8, au32x4{bv.lo[j].x, bv.lo[j].y, bv.hi[j].x, bv.hi[j].y});
+      for (int j = 0; j < HT; ++j) vf[j] = __builtin_bit_cast(bf16x8, au32x4{bv.lo[j].x, bv.lo[j].y, bv.hi[j].x, bv.hi[j].y});
+    } else {
+      if (it + 1 < nsteps)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * KSQ) : "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < HT; ++j) {
+        const au32x2 lo = *(const au32x2*)(vbuf + (j * 16 + c) * (kBlockTokens * 2) + g * 8);
+        const au32x2 hi = *(const au32x2*)(vbuf + HD * kBlockTokens * 2 + (j * 16 + c) * (kBlockTokens * 2) + g * 8);
+        vf[j] = __builtin_bit_cast(bf16x8, au32x4{lo.x, lo.y, hi.x, hi.y});
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the buffer has been read: it can take the next step's values
+    }
     if (!full) {
       // values of tokens at or beyond `total` read as zero (their weights are exact zeros, but what the
       // cache holds there need not be a number); their keys need nothing: those scores are masked below
@@ -291,6 +339,18 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) sc[tt * 4 + i] = acc[i] * scale;
+      }
+      if constexpr (!V_AHEAD) {
+        // The next step's values are asked for here, behind the first tile's scores: every key
+        // fragment of the step has been used by now, so the compiler's waits for them, which do not
+        // count these copies, have all been passed and none of them ends up waiting for the copies.
+        // (Asked for without a branch, which would put a block boundary between the multiplies and
+        // the first use of their results: the last step asks for its own values again, never read.)
+        if (t == 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          request_v_lds(min(it + 1, nsteps - 1));
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       if (!full) {
 #pragma unroll
@@ -329,7 +389,7 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
   KRegs ka, kb;
   VRegs va, vb;
   request_k(ka, 0);
-  if constexpr (V_AHEAD) request_v(va, 0);
+  if constexpr (V_AHEAD) request_v(va, 0); else request_v_lds(0);
   if (nsteps > 1) {
     request_k(kb, 1);
     if constexpr (V_AHEAD) request_v(vb, 1);
@@ -358,6 +418,15 @@ __global__ __launch_bounds__(kStreamWaves * 64, 2) void attn_stream_kernel(const
       }
     }
   }
+
+  // (T = 2: a wave that found nothing cached in its last steps never waited for the values it had
+  // requested; they must have landed before its merge rows, the same LDS, are written)
+  if constexpr (!V_AHEAD) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // (The last products may have been issued in another basic block, where the compiler pads too few
+  // wait states for the LDS stores of their results below: spell them out.)
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- merge of the waves, tile after tile: thread -> (query row, 8 consecutive elements) ----
   constexpr int TPR = HD / 8;
@@ -495,6 +564,8 @@ hipError_t launch_attention(const AttnCall& c, hipStream_t st) {
     if (c.stream_tiles) {  // few rows per client: the streaming kernel (the batch was planned by attn_stream_plan)
       const int T = c.stream_tiles;
       if ((h != 128 && h != 64) || max_m > kStreamMaxRows || (T != 1 && T != 2) || c.counters == nullptr) return hipErrorInvalidValue;
+      for (int i = 0; i < b.n; ++i)  // (a lane per step holds the step's block-table entries)
+        if (b.c[i].span < kStreamWgTokens || b.c[i].span > kStreamMaxSteps * kStreamWgTokens) return hipErrorInvalidValue;
       const int nz = ((group * max_m + 15) / 16 + T - 1) / T;
       static bool stream_lds_allowed = false;
       if (!stream_lds_allowed) {
@@ -581,11 +652,13 @@ int attn_stream_plan(int n_q_heads, int n_kv_heads, int head_dim, AttnBatch& b, 
       // a prompt block (alone in its pass): the query tiles alone give many workgroups, so the context
       // is cut only as far as it takes to have about two workgroups per compute unit
       const long groups = (long)n_kv_heads * (((group * cl.m + 15) / 16 + 1) / 2);
-      const long want = std::max(1L, std::min((long)kStreamMaxSplits, 2L * device_cu_count() / groups));
+      const long fit = ((long)total + kStreamMaxSteps * kStreamWgTokens - 1) / (kStreamMaxSteps * kStreamWgTokens);
+      const long want = std::max(fit, std::min((long)kStreamMaxSplits, 2L * device_cu_count() / groups));
       const int steps = (total + kStreamMinSpan - 1) / kStreamMinSpan;
       cl.span = (int)((steps + want - 1) / want) * kStreamMinSpan;
     }
     cl.nsplit = (total + cl.span - 1) / cl.span;
+    if (cl.span > kStreamMaxSteps * kStreamWgTokens || cl.nsplit > kStreamMaxSplits) return 0;  // (contexts beyond 131072 tokens)
     tasks += (long)n_kv_heads * cl.nsplit * ((group * cl.m + 15) / 16);
   }
   // two tiles per workgroup (keys and values read once for both) where a head group has exactly

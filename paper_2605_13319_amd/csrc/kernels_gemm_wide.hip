@@ -29,6 +29,7 @@
 
 #include <type_traits>
 
+#include "device_dma.h"
 #include "device_gemm.h"
 
 namespace pipesd {
@@ -75,11 +76,15 @@ __device__ __forceinline__ void wide_rstd_rows(const GemmArgs& a, int row0, int 
   }
 }
 
-// one 1 KB fragment from memory straight into LDS: lane i's 16 bytes land at dst + 16 i (dst is the
-// same for the whole wave); the load counts as one outstanding vector-memory load until it has landed
-__device__ __forceinline__ void frag_to_lds(const u32x4* src_lane, u32x4* dst_wave) {
-  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src_lane,
-                                   (void __attribute__((address_space(3)))*)dst_wave, 16, 0, 0);
+// f(integral_constant<int, n>) for the run-time n in 0..N
+template <int N, class F>
+__device__ __forceinline__ void wide_dispatch_count(int n, F& f) {
+  if constexpr (N == 0) {
+    f(std::integral_constant<int, 0>{});
+  } else {
+    if (n == N) f(std::integral_constant<int, N>{});
+    else wide_dispatch_count<N - 1>(n, f);
+  }
 }
 
 // Eight waves, two per SIMD (one wave alone issues a matrix-core instruction only every ~30 cycles):
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
   auto request = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NPER; ++i) {
-      frag_to_lds((const u32x4*)rp[i], (u32x4*)((char*)bl + buf + rlds[i]));
+      lds_dma16(rp[i], (char*)bl + buf + rlds[i]);
       rp[i] += (size_t)(kWideStage * rstep[i]);
     }
   };
@@ -280,18 +285,7 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
     int lr = 0;  // this wave's live row tiles
 #pragma unroll
     for (int r = 0; r < RW; ++r) lr += (r * WMS + wm < x.row_tiles) ? 1 : 0;
-    static_assert(RW == 1 || RW == 4, "the dispatch below lists the live counts");
-    if constexpr (RW == 1) {
-      if (lr == 1) walk(std::integral_constant<int, 1>{}); else walk(std::integral_constant<int, 0>{});
-    } else {
-      switch (lr) {
-        case 4: walk(std::integral_constant<int, 4>{}); break;
-        case 3: walk(std::integral_constant<int, 3>{}); break;
-        case 2: walk(std::integral_constant<int, 2>{}); break;
-        case 1: walk(std::integral_constant<int, 1>{}); break;
-        default: walk(std::integral_constant<int, 0>{}); break;
-      }
-    }
+    wide_dispatch_count<RW>(lr, walk);
   }
   // the requests past the end of the walk must have landed before the workgroup gives its LDS back
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
