@@ -6,16 +6,17 @@
 // of the pass with 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they
 // get there without passing through registers: every wave asks for its share of a stage's fragments
 // (per k-step the 8 weight fragments and the row tiles' activation fragments, hi and lo) with loads
-// that write straight into LDS, into a ring of three stage buffers, two stages ahead of the
-// multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
+// that write straight into LDS, into a ring of three (or four) stage buffers, two (three) stages
+// ahead of the multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
 // consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this wave's
-// loads of the stage have landed (they return in order: all but the next stage's may be outstanding)
-// and its own LDS reads have returned, one workgroup barrier, request the stage after next into the
-// buffer the barrier has just freed.  The multiplies run as a stream of blocks (k-step, row tile)
+// loads of the stage have landed (they return in order: all but the later stages' may be
+// outstanding) and its own LDS reads have returned, one workgroup barrier, request the stage a
+// ring's length minus one ahead into the buffer the barrier has just freed.  The multiplies run as a stream of blocks (k-step, row tile)
 // whose operands are read from LDS three blocks ahead, across stage boundaries.  Wave (wm, wn) owns
 // row tiles wm, wm + 4, .. x n-tiles wn*4 .. +3; row tiles past the pass are neither read nor
 // multiplied.  Up to 128 rows the packed activations have 8 row tiles and a stage is two k-steps;
-// up to 256 rows they have 16 and a stage is one.
+// up to 256 rows they have 16 and a stage is one (up to 192 rows only 12 of them are staged, and
+// the ring has four buffers).
 //
 // Results are bit-identical to the narrow kernel's, row by row: K is cut into the same W * P slices
 // of 512 columns, every slice is accumulated from zero in the same k-step order (hi half, then lo
@@ -34,15 +35,18 @@
 
 namespace pipesd {
 
-// Two shapes: ROWT = 8 row tiles (passes of 65..128 rows; the packed activations have 8 row tiles)
-// with stages of two k-steps, and ROWT = 16 (129..256 rows; 16 row tiles) with stages of one.
-constexpr int kWideRing = 3;        // stage buffers
+// Shapes: ROWT = 8 row tiles (passes of 65..128 rows; the packed activations have 8 row tiles) with
+// stages of two k-steps, and ROWT = 16 (129..256 rows; 16 row tiles) with stages of one.  Of the 16
+// row tiles only the first RTL are brought into LDS: RTL = 12 for passes of up to 192 rows, whose
+// smaller stages leave room for a fourth stage buffer (requests three stages ahead), else 16.
+constexpr int wide_ring(int rtl) { return rtl == 12 ? 4 : 3; }  // stage buffers
 constexpr int kWideWgTiles = 8;     // n-tiles per workgroup: 2 wave columns x 4
 constexpr int wide_stage_ksteps(int rowt) { return rowt == 16 ? 1 : 2; }
 // 1 KB fragments of one k-step in a stage buffer: the 8 weight fragments, then (row tile, half)
 constexpr int wide_kstep_frags(int rowt) { return kWideWgTiles + 2 * rowt; }
-constexpr size_t wide_ring_bytes(int rowt) { return (size_t)kWideRing * wide_stage_ksteps(rowt) * wide_kstep_frags(rowt) * 1024; }
-constexpr size_t kWideLdsBytes = (wide_ring_bytes(8) > wide_ring_bytes(16) ? wide_ring_bytes(8) : wide_ring_bytes(16)) + 256 * sizeof(float);
+constexpr size_t wide_ring_bytes(int rowt, int rtl) { return (size_t)wide_ring(rtl) * wide_stage_ksteps(rowt) * wide_kstep_frags(rtl) * 1024; }
+constexpr size_t wide_max(size_t a, size_t b) { return a > b ? a : b; }
+constexpr size_t kWideLdsBytes = wide_max(wide_ring_bytes(8, 8), wide_max(wide_ring_bytes(16, 12), wide_ring_bytes(16, 16))) + 256 * sizeof(float);
 
 struct WideArgs {
   f32x4* partials;  // split: [W][ntiles][ROWT][64] running sums of role w
@@ -92,11 +96,11 @@ __device__ __forceinline__ void wide_dispatch_count(int n, F& f) {
 // w + 4 share a SIMD; with wm = w/2 the two of a SIMD hold row tiles {wm, wm + 4} and {wm + 2, wm + 6},
 // so a pass of 5 live row tiles costs every SIMD at most 3 of its 4 blocks.
 constexpr int wide_waves(int rowt) { return rowt == 8 ? 16 : 8; }
-template <bool WHOLE, bool P1, int ROWT>
+template <bool WHOLE, bool P1, int ROWT, int RTL>
 __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
   extern __shared__ float lds_f[];
   constexpr int kWideWaves = wide_waves(ROWT), WMS = kWideWaves / 2;  // waves, wave rows
-  constexpr int RTL = ROWT;
+  constexpr int kWideRing = wide_ring(RTL);           // stage buffers
   constexpr int kWideStage = wide_stage_ksteps(ROWT); // k-steps per ring stage
   constexpr int kWideSliceStages = 16 / kWideStage;   // stages per 512-column slice
   constexpr int KF = wide_kstep_frags(RTL);           // fragments per k-step
@@ -172,10 +176,10 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
   // The multiplies run as one stream of blocks (k-step, row tile of this wave): 8 MFMAs on a pair of
   // activation fragments (hi, lo) and the k-step's 4 weight fragments.  Operands are read from LDS
   // kAhead blocks ahead of their block.  When the block to read is the first of a stage, that stage
-  // must have landed: this wave's loads of it have once at most the next stage's are outstanding,
-  // and behind the workgroup barrier every wave's have.  The same wait covers this wave's own LDS
-  // reads, so behind the barrier nobody reads the stage before any more, and its buffer takes the
-  // stage after next.  Past the end of the walk the last slice's first stages are requested and read
+  // must have landed: this wave's loads of it have once at most the later stages' (ring - 2 of
+  // them) are outstanding, and behind the workgroup barrier every wave's have.  The same wait covers
+  // this wave's own LDS reads, so behind the barrier nobody reads the stage before any more, and
+  // its buffer takes the stage ring - 1 ahead.  Past the end of the walk the last slice's first stages are requested and read
   // again (and never used), so the counts hold to the end.
   constexpr int BPS = kWideStage * RW;           // blocks per stage
   constexpr int kAhead = BPS >= 4 ? 3 : 1;       // (a power of two minus one, below BPS)
@@ -189,27 +193,27 @@ __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmAr
   const char* lw = (const char*)bl + (wn * 4 * 64 + lane) * 16;
   const char* la = (const char*)bl + ((kWideWgTiles + wm * 2) * 64 + lane) * 16;
   // the next stage has landed for every wave and the stage before it is no longer read: move on to
-  // it and ask for the stage after next; s = the new stage's place in its slice
+  // it and ask for the stage ring - 1 ahead of it; s = the new stage's place in its slice
   auto stage_ready = [&](int s) {
     const int freed = rd;
     rd = rd == (kWideRing - 1) * kStageBytes ? 0 : rd + kStageBytes;
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER * (kWideRing - 2)) : "memory");
     __builtin_amdgcn_s_barrier();
-    if ((s + 2) % kWideSliceStages == 0) request_turn();
+    if ((s + kWideRing - 1) % kWideSliceStages == 0) request_turn();
     request(freed);
   };
 
-  request(0);
-  request(kStageBytes);
+#pragma unroll
+  for (int b = 0; b < kWideRing - 1; ++b) request(b * kStageBytes);
   if (WHOLE && a.ssq_in != nullptr) {
     constexpr int RPW = ROWT * 16 / kWideWaves;  // rows whose rstd this wave computes: w, w + kWideWaves, ..
 #pragma unroll
     for (int h = 0; h < (RPW + 15) / 16; ++h)
       wide_rstd_rows<(RPW < 16 ? RPW : 16)>(a, w + 16 * kWideWaves * h, kWideWaves, lane, rstd_lds, w + 16 * kWideWaves * h);
   }
-  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER) : "memory");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(NPER * (kWideRing - 2)) : "memory");
   __builtin_amdgcn_s_barrier();
-  request(2 * kStageBytes);
+  request((kWideRing - 1) * kStageBytes);
 
   // The walk, compiled once per number LR of this wave's live row tiles (they are r*WMS + wm,
   // r < LR): a row tile past the pass is neither read nor multiplied, and no block asks whether it
@@ -363,12 +367,12 @@ size_t gemm_wide_workspace_bytes(int N, int K) {
   return (size_t)W * ntiles * 16 * 64 * sizeof(f32x4);  // (sized for the 16-row-tile shape)
 }
 
-template <bool WHOLE, bool P1, int ROWT>
+template <bool WHOLE, bool P1, int ROWT, int RTL>
 static hipError_t launch_wide_rowt(const GemmArgs& a, const WideArgs& x, int grid, bool timed, hipEvent_t e0,
                                    hipEvent_t e1, hipStream_t st) {
   static bool attr_set = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1, ROWT>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_wide_kernel<WHOLE, P1, ROWT, RTL>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kWideLdsBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -377,10 +381,10 @@ static hipError_t launch_wide_rowt(const GemmArgs& a, const WideArgs& x, int gri
   // kernel, end of the second
   const dim3 block(wide_waves(ROWT) * 64);
   if (timed)
-    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, ROWT>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
+    hipExtLaunchKernelGGL((gemm_wide_kernel<WHOLE, P1, ROWT, RTL>), dim3(grid), block, (uint32_t)kWideLdsBytes, st, e0,
                           WHOLE ? e1 : nullptr, 0, a, x);
   else
-    gemm_wide_kernel<WHOLE, P1, ROWT><<<grid, block, kWideLdsBytes, st>>>(a, x);
+    gemm_wide_kernel<WHOLE, P1, ROWT, RTL><<<grid, block, kWideLdsBytes, st>>>(a, x);
   return hipGetLastError();
 }
 
@@ -390,9 +394,10 @@ static hipError_t launch_wide_variant(const GemmArgs& a, const WideArgs& x, int 
   if (x.rowt == 16) {
     // (a whole-K walk with phases needs three accumulator sets of 64 registers: not built for 16 row tiles)
     if constexpr (WHOLE && !P1) return hipErrorInvalidValue;
-    else return launch_wide_rowt<WHOLE, P1, 16>(a, x, grid, timed, e0, e1, st);
+    else if (x.row_tiles <= 12) return launch_wide_rowt<WHOLE, P1, 16, 12>(a, x, grid, timed, e0, e1, st);
+    else return launch_wide_rowt<WHOLE, P1, 16, 16>(a, x, grid, timed, e0, e1, st);
   }
-  return launch_wide_rowt<WHOLE, P1, 8>(a, x, grid, timed, e0, e1, st);
+  return launch_wide_rowt<WHOLE, P1, 8, 8>(a, x, grid, timed, e0, e1, st);
 }
 
 // whether the wide kernel can run this product on `act_tiles` row tiles
