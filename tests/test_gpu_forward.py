@@ -138,6 +138,19 @@ def test_small_bf16_models(nav, shape, prefix, ks):
     print("cache entries off by one bf16 step:", bad, flush=True)
 
 
+def test_two_query_tiles_per_workgroup_at_head_dim_64(nav):
+    """Head dim 64, four query heads per KV head: k = 6, 5, 7 bring 28, 24, 32 rows per KV head, two
+    query tiles per workgroup (a step's values then travel through the wave's LDS buffer); a context
+    of 700 tokens is three splits of up to two steps, merged by the last workgroup to arrive."""
+    shape, prefix = SMALL_BF16, 700
+    oseq, model, kv = _both(nav, shape, 4646, prefix, n_blocks=(prefix + 64) // 16 + 2, max_len=prefix + 64)
+    for r, k in enumerate((6, 5, 7)):
+        d, q = drafts_from_oracle(oseq, k, 0.5, 4700 + r, 4800 + r)
+        u = I.make_uniforms(k + 1, 4900 + r)
+        err, a = _check_pass(kv, oseq, d, q, u, TOL_BF16)
+        print(f"{shape.name} context {kv.length(0)} k={k}: err {err:.2e} accepted {a}", flush=True)
+
+
 def test_rollback_reproduces_and_matches_fresh_prefill(nav):
     shape = SMALL_BF16
     oseq, model, kv = _both(nav, shape, 5151, 40, n_blocks=24, max_len=300)
