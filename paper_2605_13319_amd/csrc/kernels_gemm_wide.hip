@@ -2,19 +2,19 @@
 //
 // At this many rows the activations of a K slice no longer fit a wave's registers, and spreading the
 // rows over workgroups that re-read the weights from the L2 (the narrow kernel's way) moves many
-// times the weights through it.  Here a workgroup of eight waves, two per SIMD, multiplies ALL rows
-// of the pass with 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they
+// times the weights through it.  Here a workgroup of sixteen or eight waves (four or two per SIMD)
+// multiplies ALL rows of the pass with 8 n-tiles of weights.  Both operands reach the matrix cores through LDS, and they
 // get there without passing through registers: every wave asks for its share of a stage's fragments
 // (per k-step the 8 weight fragments and the row tiles' activation fragments, hi and lo) with loads
 // that write straight into LDS, into a ring of three (or four) stage buffers, two (three) stages
-// ahead of the multiplies.  ActPack and the re-tiled weights are already in the lane order the matrix cores
-// consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this wave's
+// ahead of the multiplies.  ActPack and the re-tiled weights are already in the lane order the
+// matrix cores consume, so a fragment is 64 lanes x 16 bytes, copied as it is.  Per stage: wait until this wave's
 // loads of the stage have landed (they return in order: all but the later stages' may be
 // outstanding) and its own LDS reads have returned, one workgroup barrier, request the stage a
-// ring's length minus one ahead into the buffer the barrier has just freed.  The multiplies run as a stream of blocks (k-step, row tile)
-// whose operands are read from LDS three blocks ahead, across stage boundaries.  Wave (wm, wn) owns
-// row tiles wm, wm + 4, .. x n-tiles wn*4 .. +3; row tiles past the pass are neither read nor
-// multiplied.  Up to 128 rows the packed activations have 8 row tiles and a stage is two k-steps;
+// ring's length minus one ahead into the buffer the barrier has just freed.  The multiplies run as
+// a stream of blocks (k-step, row tile) whose operands are read from LDS one or three blocks ahead,
+// across stage boundaries.  Wave (wm, wn) owns row tiles wm, wm + (waves / 2), .. x n-tiles
+// wn*4 .. +3; row tiles past the pass are neither read nor multiplied.  Up to 128 rows the packed activations have 8 row tiles and a stage is two k-steps;
 // up to 256 rows they have 16 and a stage is one (up to 192 rows only 12 of them are staged, and
 // the ring has four buffers).
 //
@@ -91,10 +91,11 @@ __device__ __forceinline__ void wide_dispatch_count(int n, F& f) {
   }
 }
 
-// Eight waves, two per SIMD (one wave alone issues a matrix-core instruction only every ~30 cycles):
-// wave (wm, wn) owns row tiles r*4 + wm (r = 0, 1) x n-tiles wn*4 .. +3 of the group.  Waves w and
-// w + 4 share a SIMD; with wm = w/2 the two of a SIMD hold row tiles {wm, wm + 4} and {wm + 2, wm + 6},
-// so a pass of 5 live row tiles costs every SIMD at most 3 of its 4 blocks.
+// At least two waves per SIMD (one wave alone issues a matrix-core instruction only every ~30
+// cycles): sixteen waves of one row tile each for 8 row tiles, eight waves of three or four row
+// tiles each for 12 or 16.  Wave (wm, wn) = (w / 2, w % 2) owns row tiles r * (waves / 2) + wm x
+// n-tiles wn*4 .. +3 of the group; waves w and w + 4 share a SIMD, so the live row tiles of a pass
+// that does not fill its last tiles spread evenly over the SIMDs.
 constexpr int wide_waves(int rowt) { return rowt == 8 ? 16 : 8; }
 template <bool WHOLE, bool P1, int ROWT, int RTL>
 __global__ __launch_bounds__(wide_waves(ROWT) * 64) void gemm_wide_kernel(GemmArgs a, WideArgs x) {
