@@ -55,9 +55,10 @@ def test_batched_call_equals_single_calls_bit_for_bit(nav, shape_name, n_seq, ro
         kv_s.prefill(s, toks)
     for rnd in range(rounds):
         ks = [int(x) for x in rng.integers(1, 17, n_seq)]
-        if n_seq == 16 and rnd < 2:
-            # a full pass (256 rows: all 16 row tiles) and one of 192 rows (the 12-row-tile shape, all live)
-            ks = [15 if rnd == 0 else 11] * n_seq
+        fixed = {0: 15, 1: 11, 2: 13, 3: 9}
+        if n_seq == 16 and rnd in fixed and rnd < rounds - 1:
+            # passes of 256, 192, 224 and 160 rows: each staged-row-tile shape of the wide GEMM, all tiles live
+            ks = [fixed[rnd]] * n_seq
         drafts, probs, us = [], [], []
         for s in range(n_seq):
             d, q = I.make_independent_drafts(ks[s], shape.vocab, 9200 + 100 * rnd + s, 9300 + 100 * rnd + s, scale=1.0)
